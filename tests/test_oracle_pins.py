@@ -1,0 +1,290 @@
+"""Pins of the CPU oracle against what the paper and plain mathematics fix.
+
+None of these tests calls the oracle to produce its own expected value: the
+expected side is the paper's worked example (tests/golden), a NumPy library
+routine (take / fancy assignment), a literal dictionary model, or a closed
+form of the stateless fill.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import kvmig as orc
+from workload import SplitMix64, fill_pool_u16, fill_words, make_case, M8B
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rand_pool(rng, L, S, Hl, D, dtype=np.uint16):
+    n = L * 2 * S * Hl * D
+    bits = rng.words(n)
+    return (bits & np.uint64(np.iinfo(dtype).max)).astype(dtype).reshape(L, 2, S, Hl, D)
+
+
+# ---------------------------------------------------------------- routing ---
+
+def test_route_reproduces_paper_worked_example():
+    """Sec. 3.2.2: the seven moves the text spells out for 4 GPUs / 8 heads."""
+    rows = []
+    with open(os.path.join(GOLDEN, "tp_switch_example.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                step, s, d, a, b = line.split()
+                rows.append((step, int(s), int(d), int(a), int(b)))
+    assert len(rows) == 7
+    H = 8
+    steps = {
+        "TP1->TP2": ([[1], [2], [3], [4]], [[1, 2], [3, 4]], {1: 0, 2: 0, 3: 1, 4: 1}),
+        "TP2->TP4": ([[1, 2], [3, 4]], [[1, 2, 3, 4]], {1: 0, 2: 0, 3: 0, 4: 0}),
+    }
+    for step, s, d, a, b in rows:
+        old, new, newgroup_of_gpu = steps[step]
+        go = next(i for i, g in enumerate(old) if s in g)
+        gn = newgroup_of_gpu[d]
+        assert d in new[gn]
+        so, do, w = orc.route(H, len(old[go]), old[go].index(s), len(new[gn]), new[gn].index(d))
+        sa, _ = orc.head_interval(H, len(old[go]), old[go].index(s))
+        da, _ = orc.head_interval(H, len(new[gn]), new[gn].index(d))
+        assert w == b - a + 1, (step, s, d)
+        assert sa + so == a and da + do == a, (step, s, d)
+
+
+def test_route_full_pair_table_of_the_example():
+    """The example's complete table (stated moves plus the ones "and so on"
+    implies): cross-GPU moves only, as (src, dst, first, last)."""
+    H = 8
+    # one request per original GPU
+    old, new = [[1], [2], [3], [4]], [[1, 2], [3, 4]]
+    pairs = orc.transition_pairs(H, old, new, {10: 0, 20: 1, 30: 2, 40: 3}, {10: 0, 20: 0, 30: 1, 40: 1})
+    got = sorted((s, d, orc.head_interval(H, 1, 0)[0] + so, w) for s, d, _, so, _, w in pairs if s != d)
+    assert got == [(1, 2, 4, 4), (2, 1, 0, 4), (3, 4, 4, 4), (4, 3, 0, 4)]
+    stay = sorted((s, so, w) for s, d, _, so, _, w in pairs if s == d)
+    assert stay == [(1, 0, 4), (2, 4, 4), (3, 0, 4), (4, 4, 4)]
+    old, new = [[1, 2], [3, 4]], [[1, 2, 3, 4]]
+    pairs = orc.transition_pairs(H, old, new, {10: 0, 30: 1}, {10: 0, 30: 0})
+    got = set()
+    for s, d, reqs, so, do, w in pairs:
+        first = orc.head_interval(H, 2, old[0].index(s) if s in old[0] else old[1].index(s))[0] + so
+        got.add((s, d, first, first + w - 1))
+    want = {(1, 1, 0, 1), (3, 1, 0, 1), (1, 2, 2, 3), (3, 2, 2, 3),
+            (2, 3, 4, 5), (4, 3, 4, 5), (2, 4, 6, 7), (4, 4, 6, 7)}
+    assert got == want
+
+
+@pytest.mark.parametrize("H", [8, 16, 32])
+def test_route_partitions_every_source_interval(H):
+    """Even split on heads: what rank rs sends to all rd tiles its interval
+    exactly once, and every destination ends up with H/Nd heads."""
+    for Ns, Nd in itertools.product([1, 2, 4, 8], repeat=2):
+        got_at_dst = {rd: [] for rd in range(Nd)}
+        for rs in range(Ns):
+            cover = []
+            for rd in range(Nd):
+                so, do, w = orc.route(H, Ns, rs, Nd, rd)
+                if w:
+                    base_s = rs * (H // Ns)
+                    base_d = rd * (H // Nd)
+                    assert 0 <= so and so + w <= H // Ns and 0 <= do and do + w <= H // Nd
+                    assert base_s + so == base_d + do          # same global heads on both ends
+                    cover += list(range(base_s + so, base_s + so + w))
+                    got_at_dst[rd] += list(range(base_d + do, base_d + do + w))
+            assert cover == list(range(rs * (H // Ns), (rs + 1) * (H // Ns)))
+        for rd in range(Nd):
+            assert sorted(got_at_dst[rd]) == list(range(rd * (H // Nd), (rd + 1) * (H // Nd)))
+
+
+def test_route_rejects_uneven_split():
+    with pytest.raises(ValueError):
+        orc.route(8, 3, 0, 1, 0)
+    with pytest.raises(ValueError):
+        orc.route(8, 2, 2, 1, 0)
+
+
+# ------------------------------------------------------------- flattening ---
+
+def test_flatten_token_pages_are_the_slots():
+    ctx = [3, 0, 2]
+    pages = [7, 1, 4, 9, 0]
+    assert orc.flatten(ctx, pages, 1).tolist() == pages
+
+
+def test_flatten_pages_of_four_with_partial_tail():
+    # request 0: 6 tokens in pages 5, 2 (tail holds 2 of 4); request 1: 4 tokens in page 0
+    got = orc.flatten([6, 4], [5, 2, 0], 4).tolist()
+    assert got == [20, 21, 22, 23, 8, 9, 0, 1, 2, 3]
+
+
+def test_flatten_rejects_wrong_table_length():
+    with pytest.raises(ValueError):
+        orc.flatten([5], [1], 4)
+
+
+# ------------------------------------------------------------ pack/unpack ---
+
+@pytest.mark.parametrize("Hs,off,w", [(8, 0, 8), (8, 4, 4), (4, 1, 2), (2, 1, 1), (3, 0, 2)])
+@pytest.mark.parametrize("dtype", [np.uint16, np.uint8, np.uint32])
+def test_pack_is_row_gather_with_column_slice(Hs, off, w, dtype):
+    rng = SplitMix64(100 + Hs + off)
+    L, S, D, T = 3, 37, 6, 23
+    src = rand_pool(rng, L, S, Hs, D, dtype)
+    sslot = rng.integers(0, S - 1, T).astype(np.int32)          # repeats allowed on the source
+    got = orc.pack(src, sslot, off, w)
+    want = np.take(src, sslot, axis=2)[:, :, :, off:off + w, :]
+    assert got.shape == (L, 2, T, w, D)
+    assert np.array_equal(got, want)
+
+
+def test_pack_identity_case_is_a_prefix_copy():
+    rng = SplitMix64(5)
+    src = rand_pool(rng, 2, 16, 4, 8)
+    got = orc.pack(src, np.arange(11, dtype=np.int32), 0, 4)
+    assert got.tobytes() == np.ascontiguousarray(src[:, :, :11]).tobytes()
+
+
+@pytest.mark.parametrize("Hd,off,w", [(8, 0, 8), (4, 0, 4), (4, 2, 2), (8, 7, 1)])
+def test_unpack_is_row_scatter_and_touches_nothing_else(Hd, off, w):
+    rng = SplitMix64(200 + Hd + off)
+    L, S, D, T = 2, 41, 4, 29
+    stream = rand_pool(rng, L, T, w, D)
+    dst0 = rand_pool(rng, L, S, Hd, D)
+    dslot = rng.permutation(S)[:T].astype(np.int32)
+    got = dst0.copy()
+    orc.unpack(stream, got, dslot, off)
+    want = dst0.copy()
+    want[:, :, dslot, off:off + w, :] = stream
+    assert np.array_equal(got, want)
+    mask = np.ones(dst0.shape, dtype=bool)
+    mask[:, :, dslot, off:off + w, :] = False
+    assert np.array_equal(got[mask], dst0[mask])                 # sentinel bytes survive
+    assert mask.sum() == dst0.size - stream.size
+
+
+def test_unpack_full_permutation_permutes_rows():
+    rng = SplitMix64(9)
+    L, S, Hd, D = 2, 12, 2, 4
+    stream = rand_pool(rng, L, S, Hd, D)
+    perm = rng.permutation(S).astype(np.int32)
+    dst = np.zeros((L, 2, S, Hd, D), np.uint16)
+    orc.unpack(stream, dst, perm, 0)
+    assert np.array_equal(dst[:, :, perm], stream)
+    assert sorted(map(bytes, dst.reshape(L * 2 * S, -1))) == sorted(map(bytes, stream.reshape(L * 2 * S, -1)))
+
+
+def test_unpack_rejects_duplicate_destination_slots():
+    stream = np.zeros((1, 2, 2, 1, 2), np.uint16)
+    dst = np.zeros((1, 2, 4, 1, 2), np.uint16)
+    with pytest.raises(ValueError):
+        orc.unpack(stream, dst, np.array([1, 1], np.int32), 0)
+
+
+def test_stream_bytes_match_paper_size_identity():
+    """Sec. 3.2.2 equates 4096 tokens with 0.5 GB and 40960 with 5 GB for a
+    16-bit 8B Llama: 128 KiB per token, GB read as GiB."""
+    src = np.zeros((M8B.L, 2, 4, M8B.H, M8B.D), np.uint16)
+    s = orc.pack(src, np.arange(4, dtype=np.int32), 0, M8B.H)
+    per_token = s.nbytes // 4
+    assert per_token == 131072 == M8B.token_bytes
+    assert 4096 * per_token == 2 ** 29 and 40960 * per_token == 5 * 2 ** 30
+
+
+# ---------------------------------------------------------------- migrate ---
+
+@pytest.mark.parametrize("tr", [(1, 0, 2, 1), (2, 1, 4, 2), (4, 3, 8, 7), (8, 2, 4, 1), (4, 1, 2, 0), (2, 1, 1, 0), (1, 0, 1, 0)])
+def test_migrate_equals_direct_and_closed_form_of_fill(tr):
+    Ns, rs, Nd, rd = tr
+    H, L, D, S, T = 8, 2, 8, 64, 40
+    so, do, w = orc.route(H, Ns, rs, Nd, rd)
+    Hs, Hd = H // Ns, H // Nd
+    rng = SplitMix64(300 + Ns * 10 + Nd)
+    src = fill_pool_u16(11, L * 2 * S * Hs * D).reshape(L, 2, S, Hs, D)
+    dst0 = fill_pool_u16(12, L * 2 * S * Hd * D).reshape(L, 2, S, Hd, D)
+    sslot = rng.permutation(S)[:T].astype(np.int32)
+    dslot = rng.permutation(S)[:T].astype(np.int32)
+    a, b = dst0.copy(), dst0.copy()
+    orc.migrate(src, a, sslot, dslot, so, do, w)
+    orc.migrate_direct(src, b, sslot, dslot, so, do, w)
+    assert np.array_equal(a, b)
+    # closed form: each moved element equals the fill word of its SOURCE coordinate
+    for l, c, j, h, x in itertools.product(range(L), range(2), [0, 7, T - 1], range(w), [0, D - 1]):
+        lin = ((((l * 2 + c) * S + int(sslot[j])) * Hs + so + h) * D + x)
+        word = int(fill_words(11, lin // 4, 1)[0])
+        assert int(a[l, c, dslot[j], do + h, x]) == (word >> (16 * (lin % 4))) & 0xFFFF
+    # and an untouched element still equals the destination's own fill
+    free = sorted(set(range(S)) - set(dslot.tolist()))[0]
+    lin = (((0 * S + free) * Hd + 0) * D + 3)
+    assert int(a[0, 0, free, 0, 3]) == (int(fill_words(12, lin // 4, 1)[0]) >> (16 * (lin % 4))) & 0xFFFF
+
+
+@pytest.mark.parametrize("p", [1, 2, 4])
+def test_whole_chain_against_dictionary_model(p):
+    """Tiny exhaustive check: the chain route -> flatten -> pack -> unpack must
+    place every (request, token, layer, K|V, head) where a literal dictionary
+    model of paged KV says it lives."""
+    H, L, D = 4, 2, 2
+    ctx = [3, 1, 2]
+    n_pg = [(n + p - 1) // p for n in ctx]
+    tot_pg = sum(n_pg)
+    S = (tot_pg + 2) * p
+    base = list(range(tot_pg + 2))
+    perms = list(itertools.permutations(base, tot_pg)) if tot_pg <= 4 else None
+    rng = SplitMix64(77 + p)
+    trials = perms[:200] if perms else [tuple(rng.permutation(tot_pg + 2)[:tot_pg]) for _ in range(60)]
+    for Ns, rs, Nd, rd in [(1, 0, 2, 1), (2, 0, 4, 1), (4, 2, 2, 1), (2, 1, 1, 0)]:
+        Hs, Hd = H // Ns, H // Nd
+        so, do, w = orc.route(H, Ns, rs, Nd, rd)
+        assert w > 0
+        for trial_i, src_pages in enumerate(trials[:: max(1, len(trials) // 25)]):
+            dst_pages = tuple(reversed(src_pages)) if trial_i % 2 else tuple(
+                (x + 1) % (tot_pg + 2) for x in src_pages)
+            # dictionary model: value of (req, tok, l, c, global head, x)
+            val = {}
+            src = np.zeros((L, 2, S, Hs, D), np.uint16)
+            want = np.full((L, 2, S, Hd, D), 0xEEEE, np.uint16)
+            k = 1
+            pg_at = 0
+            for r, n in enumerate(ctx):
+                for t in range(n):
+                    s_slot = src_pages[pg_at + t // p] * p + t % p
+                    d_slot = dst_pages[pg_at + t // p] * p + t % p
+                    for l in range(L):
+                        for c in range(2):
+                            for gh in range(H):
+                                for x in range(D):
+                                    val[(r, t, l, c, gh, x)] = k
+                                    if rs * Hs <= gh < (rs + 1) * Hs:
+                                        src[l, c, s_slot, gh - rs * Hs, x] = k
+                                        if rd * Hd <= gh < (rd + 1) * Hd:
+                                            want[l, c, d_slot, gh - rd * Hd, x] = k
+                                    k += 1
+                pg_at += n_pg[r]
+            got = np.full((L, 2, S, Hd, D), 0xEEEE, np.uint16)
+            sslot = orc.flatten(ctx, list(src_pages), p)
+            dslot = orc.flatten(ctx, list(dst_pages), p)
+            stream = orc.pack(src, sslot, so, w)
+            orc.unpack(stream, got, dslot, do)
+            assert np.array_equal(got, want), (p, Ns, rs, Nd, rd, src_pages)
+
+
+def test_chain_on_generated_case_c1():
+    """The generated small configuration runs through the oracle and its
+    result is independent of how the stream is cut into chunks."""
+    for case in make_case("c1", tokens=48)[:3]:
+        sh = case.shape
+        so, do, w = orc.route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
+        L, D = 2, 8                                         # reduced layers/dim for speed
+        src = fill_pool_u16(case.seed_src, L * 2 * case.S_src * case.Hs * D).reshape(L, 2, case.S_src, case.Hs, D)
+        dst = fill_pool_u16(case.seed_dst, L * 2 * case.S_dst * case.Hd * D).reshape(L, 2, case.S_dst, case.Hd, D)
+        sslot = orc.flatten(case.ctx_len, case.src_pages, case.p)
+        dslot = orc.flatten(case.ctx_len, case.dst_pages, case.p)
+        whole = dst.copy()
+        orc.migrate(src, whole, sslot, dslot, so, do, w)
+        # chunked: flat stream cut at arbitrary fragment boundaries, then reassembled
+        stream = orc.pack(src, sslot, so, w)
+        flat = stream.reshape(-1, w * D)
+        pieces = [flat[i:i + 7] for i in range(0, flat.shape[0], 7)]
+        again = np.concatenate(pieces).reshape(stream.shape)
+        chunked = dst.copy()
+        orc.unpack(np.ascontiguousarray(again), chunked, dslot, do)
+        assert np.array_equal(whole, chunked)
