@@ -1,0 +1,193 @@
+/*
+ * nitsum_kvmig.h: C ABI of the MI355X KV-cache migration library.
+ *
+ * The operation is the "aggregated and pipelined KV migration" of the Nitsum
+ * paper, Sec. 3.2.2: when the tensor-parallel (TP) level of a serving group
+ * changes, every GPU must hand the KV heads it no longer owns to the GPUs that
+ * own them under the new level.  KV lives in a paged pool, so the bytes of one
+ * request are scattered; the method gathers the moved head slice of every
+ * token into a contiguous stream ("pack"), moves the stream in chunks through
+ * two staging buffers so that copying and transmission overlap, and the
+ * receiver scatters the stream into its own paged pool ("unpack").
+ *
+ * Conventions
+ *   - All functions return NTS_OK (0) or a negative nts_status.  Nothing throws
+ *     or aborts across this boundary.  nts_last_error() gives the text of the
+ *     last failure on a context.
+ *   - "host" / "device" on a pointer says where the memory lives.  The caller
+ *     owns every buffer it passes in (pools, stream, staging) and the HIP
+ *     stream; the library owns only the device index arrays inside a plan.
+ *   - run calls only enqueue work on the given HIP stream (a hipStream_t passed
+ *     as void*, NULL = the default stream), allocate nothing and never block
+ *     the host.  A context and its plans may be used by one host thread at a time.
+ *
+ * Data layout (the paper fixes none; this is the layout of this library)
+ *   pool      per GPU and per (layer l, c = 0 for K / 1 for V) one array
+ *             [S slots][H_local heads][D elements] of elem_bytes each, given by
+ *             its device base pointer: 2L pointers, index l*2+c.  Consecutive
+ *             slots are token_stride bytes apart (0 means H_local*D*elem_bytes).
+ *             One allocation [L][2][S][H_local][D] is the common special case.
+ *   fragment  the w*D*elem_bytes contiguous bytes that one (layer, K|V, token)
+ *             contributes: heads [head_off, head_off+w) of that token's row.
+ *   stream    fragments in the order [l][c][j], j = 0..T-1 the flattened token
+ *             index (requests in the order given, tokens by position).  Chunk k
+ *             is bytes [k*chunk_bytes, (k+1)*chunk_bytes) of the stream, with
+ *             chunk_bytes a multiple of the fragment size, so the stream does
+ *             not depend on the staging size.
+ */
+#ifndef NITSUM_KVMIG_H
+#define NITSUM_KVMIG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct nts_ctx nts_ctx;
+typedef struct nts_plan nts_plan;
+
+typedef enum nts_status {
+    NTS_OK = 0,
+    NTS_EINVAL = -1,  /* null pointer, bad geometry, head slice outside a pool's heads */
+    NTS_ERANGE = -2,  /* a page id lies outside its pool */
+    NTS_EDUP = -3,    /* two migrated tokens share a destination slot */
+    NTS_EALIAS = -4,  /* source and destination byte ranges overlap */
+    NTS_ENOMEM = -5,  /* host or device allocation failed */
+    NTS_EHIP = -6     /* a HIP call failed; see nts_last_error() */
+} nts_status;
+
+enum {
+    NTS_MAX_LAYERS = 96,          /* 2*L base pointers travel as kernel arguments */
+    NTS_VALIDATE_UNIQUE_DST = 1u, /* plan flag: check destination slots are distinct */
+    NTS_DEFAULT_STAGING_BYTES = 64 << 20
+};
+
+/*
+ * One (source GPU -> destination GPU) migration: the metadata the paper's
+ * handshake exchanges (request, KV heads, context length; Sec. 3.2.2) plus the
+ * page tables of both ends.
+ */
+typedef struct nts_desc {
+    int32_t L;             /* layers */
+    int32_t D;             /* head dimension in elements */
+    int32_t elem_bytes;    /* 1, 2 or 4 */
+    int32_t page_size;     /* p >= 1 tokens per page */
+    int32_t Hs;            /* heads held per token by the source GPU (H / Ns) */
+    int32_t Hd;            /* heads held per token by the destination GPU (H / Nd) */
+    int32_t src_head_off;  /* first moved head, local to the source's Hs */
+    int32_t dst_head_off;  /* first moved head, local to the destination's Hd */
+    int32_t w;             /* heads moved, > 0 (see nts_route) */
+    int32_t n_req;         /* requests to migrate, >= 0 */
+    int64_t S_src;         /* source pool capacity in token slots (multiple of p) */
+    int64_t S_dst;         /* destination pool capacity in token slots */
+    const int32_t *ctx_len;   /* host [n_req]: tokens of each request, >= 0 */
+    const int32_t *src_pages; /* host: page ids, CSR by request, ceil(ctx_len/p) each */
+    const int32_t *dst_pages; /* host: same shape; destination pages must be distinct */
+    int64_t src_token_stride; /* bytes between source slots; 0 = Hs*D*elem_bytes */
+    int64_t dst_token_stride; /* bytes between destination slots; 0 = Hd*D*elem_bytes */
+    int64_t staging_bytes;    /* B: size of ONE staging buffer; 0 = 64 MiB.  Rounded
+                                 down to a whole number of fragments (at least one). */
+    uint32_t flags;           /* NTS_VALIDATE_UNIQUE_DST */
+    uint32_t reserved;
+} nts_desc;
+
+typedef struct nts_info {
+    int64_t T;            /* tokens migrated */
+    int64_t F;            /* fragments = T * L * 2 */
+    int64_t frag_bytes;   /* w * D * elem_bytes */
+    int64_t X;            /* payload bytes = F * frag_bytes = stream size */
+    int64_t chunk_frags;  /* fragments per chunk */
+    int64_t chunk_bytes;  /* chunk_frags * frag_bytes <= staging_bytes */
+    int64_t n_chunks;     /* ceil(F / chunk_frags); 0 for an empty plan */
+    int32_t vec_bytes;    /* bytes each lane moves per access (16, 8 or 4) */
+    int32_t reserved;
+} nts_info;
+
+/* Create a context on HIP device `device_id`.  *out is owned by the caller
+ * until nts_free.  Fails with NTS_EHIP when no such device exists. */
+int nts_init(int device_id, nts_ctx **out);
+
+/* Destroy a context.  Plans made from it must be freed first. */
+int nts_free(nts_ctx *ctx);
+
+/* Text of the last failure on `ctx` (host string owned by the context, valid
+ * until the next failing call); never NULL. */
+const char *nts_last_error(const nts_ctx *ctx);
+
+/* Name of a status code; never NULL. */
+const char *nts_strerror(int status);
+
+/*
+ * Routing step (host only, integer).  KV heads are split evenly over the GPUs
+ * of a TP group (Sec. 3.2.2); rank r of a group at level N holds heads
+ * [r*H/N, (r+1)*H/N).  The heads to move from source rank rs (level Ns) to
+ * destination rank rd (level Nd) are the intersection of the two intervals.
+ * Outputs are local to each side's own range; *w == 0 means nothing moves.
+ * NTS_EINVAL if H is not a multiple of Ns and Nd or a rank is out of range.
+ */
+int nts_route(int H, int Ns, int rs, int Nd, int rd,
+              int *src_head_off, int *dst_head_off, int *w);
+
+/*
+ * Planning step.  Flattens the request list and page tables of `d` into one
+ * source slot and one destination slot per migrated token (token t of a
+ * request sits in slot pages[t / p] * p + t % p; only the ctx_len valid tokens
+ * of a last partial page move), validates them on the GPU and fixes the chunk
+ * geometry.  Host arrays in `d` are copied and may be freed on return.  The
+ * call synchronises with the device.  Errors: NTS_EINVAL (null pointers, w <= 0,
+ * head slice outside Hs / Hd, elem_bytes not 1/2/4, fragment size or strides
+ * not a multiple of 4 bytes, L > NTS_MAX_LAYERS, negative ctx_len, more than
+ * 2^31-1 tokens), NTS_ERANGE, NTS_EDUP (only with NTS_VALIDATE_UNIQUE_DST),
+ * NTS_ENOMEM, NTS_EHIP.  A plan with zero tokens is legal; its run calls do nothing.
+ */
+int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out);
+int nts_plan_free(nts_plan *plan);
+int nts_plan_info(const nts_plan *plan, nts_info *out);
+
+/* Copy the flattened slot lists back to the host (each int32 [T], either may
+ * be NULL).  Synchronises; meant for tests and debugging. */
+int nts_plan_slots(const nts_plan *plan, int32_t *sslot_host, int32_t *dslot_host);
+
+/*
+ * Pack (aggregate): stream_out[l][c][j][0:w][0:D] =
+ *     src[l][c][sslot[j]][src_head_off : src_head_off+w][0:D]   for all l, c, j.
+ * src_layer_ptrs: host array of 2L device pointers.  stream_out: device, X bytes.
+ * Pointers must be aligned to vec_bytes.
+ */
+int nts_run_pack(nts_plan *plan, const void *const *src_layer_ptrs, void *stream_out,
+                 void *hip_stream);
+
+/* Pack chunk k only, into a device buffer of chunk_bytes (the last chunk may
+ * be shorter).  This is what a sender calls once per staging buffer. */
+int nts_run_pack_chunk(nts_plan *plan, const void *const *src_layer_ptrs, int64_t k,
+                       void *chunk_out, void *hip_stream);
+
+/*
+ * Unpack: dst[l][c][dslot[j]][dst_head_off : dst_head_off+w][0:D] =
+ *     stream_in[l][c][j][0:w][0:D]; every other byte of dst keeps its value.
+ * The paper does not describe the receiving side; this is the mirror of pack.
+ */
+int nts_run_unpack(nts_plan *plan, const void *stream_in, void *const *dst_layer_ptrs,
+                   void *hip_stream);
+int nts_run_unpack_chunk(nts_plan *plan, const void *chunk_in, int64_t k,
+                         void *const *dst_layer_ptrs, void *hip_stream);
+
+/*
+ * The whole migration on one GPU with the wire left out: chunk k is packed
+ * into staging buffer k&1 while chunk k-1 is unpacked from the other one
+ * (double buffering of Sec. 3.2.2, the consumer being the unpack instead of
+ * the interconnect).  staging: device, 2 * chunk_bytes.  Packs run on
+ * hip_stream, unpacks on a stream the context owns; hip_stream waits for the
+ * last unpack before the call's work is complete, so the caller sees one
+ * ordered operation.  NTS_EALIAS if a source layer range overlaps a
+ * destination layer range or the staging area.
+ */
+int nts_run_migrate(nts_plan *plan, const void *const *src_layer_ptrs,
+                    void *const *dst_layer_ptrs, void *staging, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NITSUM_KVMIG_H */

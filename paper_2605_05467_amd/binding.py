@@ -1,0 +1,204 @@
+"""ctypes binding of include/nitsum_kvmig.h: argument marshalling only.
+
+Functions carry the C names and semantics; see the header for layouts,
+ownership and errors.  Device buffers are passed as integer addresses
+(``tensor.data_ptr()``) and HIP streams as ``torch.cuda.Stream.cuda_stream``
+integers; torch is imported only so that both share one HIP runtime.  A non-zero status raises
+``NtsError`` with the library's message.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnts_kvmig.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2605_05467_amd.build` "
+        "(there is no fallback path)")
+
+# PyTorch ships its own copy of the HIP runtime.  Loading it first makes this
+# library bind to that same copy; the other order would put two runtimes in one
+# process, and device pointers from one are unknown to the other.
+try:
+    import torch  # noqa: F401
+except ImportError:  # the library also works without PyTorch in the process
+    pass
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+NTS_OK, NTS_EINVAL, NTS_ERANGE, NTS_EDUP, NTS_EALIAS, NTS_ENOMEM, NTS_EHIP = 0, -1, -2, -3, -4, -5, -6
+NTS_MAX_LAYERS = 96
+NTS_VALIDATE_UNIQUE_DST = 1
+NTS_DEFAULT_STAGING_BYTES = 64 << 20
+
+EXPORTS = (
+    "nts_init", "nts_free", "nts_last_error", "nts_strerror", "nts_route",
+    "nts_plan_create", "nts_plan_free", "nts_plan_info", "nts_plan_slots",
+    "nts_run_pack", "nts_run_pack_chunk", "nts_run_unpack", "nts_run_unpack_chunk",
+    "nts_run_migrate",
+)
+
+
+class nts_desc(ctypes.Structure):
+    _fields_ = [
+        ("L", ctypes.c_int32), ("D", ctypes.c_int32), ("elem_bytes", ctypes.c_int32),
+        ("page_size", ctypes.c_int32), ("Hs", ctypes.c_int32), ("Hd", ctypes.c_int32),
+        ("src_head_off", ctypes.c_int32), ("dst_head_off", ctypes.c_int32), ("w", ctypes.c_int32),
+        ("n_req", ctypes.c_int32), ("S_src", ctypes.c_int64), ("S_dst", ctypes.c_int64),
+        ("ctx_len", ctypes.c_void_p), ("src_pages", ctypes.c_void_p), ("dst_pages", ctypes.c_void_p),
+        ("src_token_stride", ctypes.c_int64), ("dst_token_stride", ctypes.c_int64),
+        ("staging_bytes", ctypes.c_int64), ("flags", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+    ]
+
+
+class nts_info(ctypes.Structure):
+    _fields_ = [
+        ("T", ctypes.c_int64), ("F", ctypes.c_int64), ("frag_bytes", ctypes.c_int64),
+        ("X", ctypes.c_int64), ("chunk_frags", ctypes.c_int64), ("chunk_bytes", ctypes.c_int64),
+        ("n_chunks", ctypes.c_int64), ("vec_bytes", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    ]
+
+
+_vp, _i, _i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+_pi = ctypes.POINTER(ctypes.c_int)
+_lib.nts_init.argtypes = [_i, ctypes.POINTER(_vp)]
+_lib.nts_free.argtypes = [_vp]
+_lib.nts_last_error.argtypes = [_vp]
+_lib.nts_last_error.restype = ctypes.c_char_p
+_lib.nts_strerror.argtypes = [_i]
+_lib.nts_strerror.restype = ctypes.c_char_p
+_lib.nts_route.argtypes = [_i, _i, _i, _i, _i, _pi, _pi, _pi]
+_lib.nts_plan_create.argtypes = [_vp, ctypes.POINTER(nts_desc), ctypes.POINTER(_vp)]
+_lib.nts_plan_free.argtypes = [_vp]
+_lib.nts_plan_info.argtypes = [_vp, ctypes.POINTER(nts_info)]
+_lib.nts_plan_slots.argtypes = [_vp, _vp, _vp]
+_lib.nts_run_pack.argtypes = [_vp, _vp, _vp, _vp]
+_lib.nts_run_pack_chunk.argtypes = [_vp, _vp, _i64, _vp, _vp]
+_lib.nts_run_unpack.argtypes = [_vp, _vp, _vp, _vp]
+_lib.nts_run_unpack_chunk.argtypes = [_vp, _vp, _i64, _vp, _vp]
+_lib.nts_run_migrate.argtypes = [_vp, _vp, _vp, _vp, _vp]
+for _name in EXPORTS:
+    if _name not in ("nts_last_error", "nts_strerror"):
+        getattr(_lib, _name).restype = _i
+
+
+class NtsError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{nts_strerror(status)} ({status}): {message}")
+        self.status = status
+
+
+def nts_strerror(status: int) -> str:
+    return _lib.nts_strerror(status).decode()
+
+
+def nts_last_error(ctx: int) -> str:
+    return _lib.nts_last_error(ctx).decode()
+
+
+def _check(status: int, ctx: Optional[int]) -> None:
+    if status != NTS_OK:
+        raise NtsError(status, nts_last_error(ctx) if ctx else "")
+
+
+def nts_init(device_id: int = 0) -> int:
+    out = _vp()
+    _check(_lib.nts_init(device_id, ctypes.byref(out)), None)
+    return out.value
+
+
+def nts_free(ctx: int) -> None:
+    _check(_lib.nts_free(ctx), ctx)
+
+
+def nts_route(H: int, Ns: int, rs: int, Nd: int, rd: int) -> Tuple[int, int, int]:
+    so, do, w = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    st = _lib.nts_route(H, Ns, rs, Nd, rd, ctypes.byref(so), ctypes.byref(do), ctypes.byref(w))
+    if st != NTS_OK:
+        raise NtsError(st, "nts_route")
+    return so.value, do.value, w.value
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def nts_plan_create(ctx: int, *, L: int, D: int, elem_bytes: int, page_size: int, Hs: int, Hd: int,
+                    src_head_off: int, dst_head_off: int, w: int, S_src: int, S_dst: int,
+                    ctx_len, src_pages, dst_pages, src_token_stride: int = 0,
+                    dst_token_stride: int = 0, staging_bytes: int = 0, flags: int = 0) -> int:
+    ctx_len, src_pages, dst_pages = _i32(ctx_len), _i32(src_pages), _i32(dst_pages)
+    d = nts_desc(L=L, D=D, elem_bytes=elem_bytes, page_size=page_size, Hs=Hs, Hd=Hd,
+                 src_head_off=src_head_off, dst_head_off=dst_head_off, w=w, n_req=len(ctx_len),
+                 S_src=S_src, S_dst=S_dst, ctx_len=ctx_len.ctypes.data,
+                 src_pages=src_pages.ctypes.data, dst_pages=dst_pages.ctypes.data,
+                 src_token_stride=src_token_stride, dst_token_stride=dst_token_stride,
+                 staging_bytes=staging_bytes, flags=flags)
+    out = _vp()
+    _check(_lib.nts_plan_create(ctx, ctypes.byref(d), ctypes.byref(out)), ctx)
+    return out.value
+
+
+def nts_plan_free(plan: int) -> None:
+    st = _lib.nts_plan_free(plan)
+    if st != NTS_OK:
+        raise NtsError(st, "nts_plan_free")
+
+
+def nts_plan_info(plan: int) -> nts_info:
+    info = nts_info()
+    st = _lib.nts_plan_info(plan, ctypes.byref(info))
+    if st != NTS_OK:
+        raise NtsError(st, "nts_plan_info")
+    return info
+
+
+def nts_plan_slots(plan: int) -> Tuple[np.ndarray, np.ndarray]:
+    T = nts_plan_info(plan).T
+    s, d = np.empty(T, np.int32), np.empty(T, np.int32)
+    st = _lib.nts_plan_slots(plan, s.ctypes.data, d.ctypes.data)
+    if st != NTS_OK:
+        raise NtsError(st, "nts_plan_slots")
+    return s, d
+
+
+def layer_ptrs(base_ptr: int, L: int, slab_bytes: int):
+    """Host table of 2L device pointers for one allocation [L][2][S][H_local][D]."""
+    return (ctypes.c_void_p * (2 * L))(*[base_ptr + i * slab_bytes for i in range(2 * L)])
+
+
+def _tab(ptrs):
+    if isinstance(ptrs, ctypes.Array):
+        return ptrs
+    return (ctypes.c_void_p * len(ptrs))(*[int(p) for p in ptrs])
+
+
+def _run(status: int) -> None:
+    if status != NTS_OK:
+        raise NtsError(status, "run call rejected (see nts_last_error on the context)")
+
+
+def nts_run_pack(plan: int, src_layer_ptrs, stream_out: int, hip_stream: int = 0) -> None:
+    _run(_lib.nts_run_pack(plan, _tab(src_layer_ptrs), stream_out, hip_stream))
+
+
+def nts_run_pack_chunk(plan: int, src_layer_ptrs, k: int, chunk_out: int, hip_stream: int = 0) -> None:
+    _run(_lib.nts_run_pack_chunk(plan, _tab(src_layer_ptrs), k, chunk_out, hip_stream))
+
+
+def nts_run_unpack(plan: int, stream_in: int, dst_layer_ptrs, hip_stream: int = 0) -> None:
+    _run(_lib.nts_run_unpack(plan, stream_in, _tab(dst_layer_ptrs), hip_stream))
+
+
+def nts_run_unpack_chunk(plan: int, chunk_in: int, k: int, dst_layer_ptrs, hip_stream: int = 0) -> None:
+    _run(_lib.nts_run_unpack_chunk(plan, chunk_in, k, _tab(dst_layer_ptrs), hip_stream))
+
+
+def nts_run_migrate(plan: int, src_layer_ptrs, dst_layer_ptrs, staging: int, hip_stream: int = 0) -> None:
+    _run(_lib.nts_run_migrate(plan, _tab(src_layer_ptrs), _tab(dst_layer_ptrs), staging, hip_stream))

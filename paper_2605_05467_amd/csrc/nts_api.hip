@@ -1,0 +1,441 @@
+// C ABI of the KV-migration library: contexts, routing, planning, run calls.
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "nts_internal.h"
+
+namespace {
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        if (prev != dev) ok = hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard()
+    {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+int fail(nts_ctx *ctx, int code, const char *what)
+{
+    if (ctx) ctx->err = what;
+    return code;
+}
+
+int fail_hip(nts_ctx *ctx, hipError_t e, const char *where)
+{
+    if (ctx) {
+        char buf[256];
+        snprintf(buf, sizeof buf, "%s: %s", where, hipGetErrorString(e));
+        ctx->err = buf;
+    }
+    (void)hipGetLastError();
+    return NTS_EHIP;
+}
+
+#define NTS_HIP(ctx, call)                                         \
+    do {                                                           \
+        hipError_t e_ = (call);                                    \
+        if (e_ != hipSuccess) return fail_hip((ctx), e_, #call);   \
+    } while (0)
+
+inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+int fill_tab(const nts_plan *pl, const void *const *ptrs, NtsLayerTab &tab)
+{
+    const int n = 2 * pl->L;
+    for (int i = 0; i < n; ++i) {
+        if (!ptrs[i]) return NTS_EINVAL;
+        if (reinterpret_cast<uintptr_t>(ptrs[i]) % uintptr_t(pl->vec)) return NTS_EINVAL;
+        tab.p[i] = static_cast<char *>(const_cast<void *>(ptrs[i]));
+    }
+    for (int i = n; i < NTS_MAX_LAYER_PTRS; ++i) tab.p[i] = nullptr;
+    return NTS_OK;
+}
+
+bool overlaps(const char *a, int64_t na, const char *b, int64_t nb)
+{
+    return a < b + nb && b < a + na;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *nts_strerror(int status)
+{
+    switch (status) {
+    case NTS_OK: return "ok";
+    case NTS_EINVAL: return "invalid argument";
+    case NTS_ERANGE: return "page id outside its pool";
+    case NTS_EDUP: return "duplicate destination slot";
+    case NTS_EALIAS: return "source and destination overlap";
+    case NTS_ENOMEM: return "out of memory";
+    case NTS_EHIP: return "HIP error";
+    default: return "unknown status";
+    }
+}
+
+const char *nts_last_error(const nts_ctx *ctx) { return ctx ? ctx->err.c_str() : "no context"; }
+
+int nts_init(int device_id, nts_ctx **out)
+{
+    if (!out) return NTS_EINVAL;
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || device_id < 0 || device_id >= n) {
+        (void)hipGetLastError();
+        return NTS_EHIP;
+    }
+    nts_ctx *ctx = new (std::nothrow) nts_ctx;
+    if (!ctx) return NTS_ENOMEM;
+    ctx->device = device_id;
+    DeviceGuard guard(device_id);
+    hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+        e = hipEventCreateWithFlags(&ctx->ev_packed[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_unpacked[i], hipEventDisableTiming);
+    }
+    if (e != hipSuccess) {
+        nts_free(ctx);
+        (void)hipGetLastError();
+        return NTS_EHIP;
+    }
+    *out = ctx;
+    return NTS_OK;
+}
+
+int nts_free(nts_ctx *ctx)
+{
+    if (!ctx) return NTS_OK;
+    if (ctx->n_plans != 0) return fail(ctx, NTS_EINVAL, "plans of this context are still alive");
+    DeviceGuard guard(ctx->device);
+    if (ctx->aux) {
+        (void)hipStreamSynchronize(ctx->aux);
+        (void)hipStreamDestroy(ctx->aux);
+    }
+    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+    for (int i = 0; i < 2; ++i) {
+        if (ctx->ev_packed[i]) (void)hipEventDestroy(ctx->ev_packed[i]);
+        if (ctx->ev_unpacked[i]) (void)hipEventDestroy(ctx->ev_unpacked[i]);
+    }
+    delete ctx;
+    return NTS_OK;
+}
+
+int nts_route(int H, int Ns, int rs, int Nd, int rd, int *src_head_off, int *dst_head_off, int *w)
+{
+    if (!src_head_off || !dst_head_off || !w) return NTS_EINVAL;
+    if (H <= 0 || Ns <= 0 || Nd <= 0 || H % Ns || H % Nd) return NTS_EINVAL;
+    if (rs < 0 || rs >= Ns || rd < 0 || rd >= Nd) return NTS_EINVAL;
+    const int hs = H / Ns, hd = H / Nd;
+    const int s_lo = rs * hs, s_hi = s_lo + hs;
+    const int d_lo = rd * hd, d_hi = d_lo + hd;
+    const int lo = s_lo > d_lo ? s_lo : d_lo;
+    const int hi = s_hi < d_hi ? s_hi : d_hi;
+    if (hi <= lo) {
+        *src_head_off = *dst_head_off = *w = 0;
+        return NTS_OK;
+    }
+    *src_head_off = lo - s_lo;
+    *dst_head_off = lo - d_lo;
+    *w = hi - lo;
+    return NTS_OK;
+}
+
+int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
+{
+    if (!ctx) return NTS_EINVAL;
+    if (!d || !out) return fail(ctx, NTS_EINVAL, "null descriptor or output");
+    *out = nullptr;
+    if (d->L <= 0 || d->L > NTS_MAX_LAYERS) return fail(ctx, NTS_EINVAL, "L outside 1..NTS_MAX_LAYERS");
+    if (d->D <= 0 || d->page_size <= 0 || d->Hs <= 0 || d->Hd <= 0)
+        return fail(ctx, NTS_EINVAL, "D, page_size, Hs and Hd must be positive");
+    if (d->elem_bytes != 1 && d->elem_bytes != 2 && d->elem_bytes != 4)
+        return fail(ctx, NTS_EINVAL, "elem_bytes must be 1, 2 or 4");
+    if (d->w <= 0) return fail(ctx, NTS_EINVAL, "w must be positive");
+    if (d->src_head_off < 0 || d->src_head_off + d->w > d->Hs)
+        return fail(ctx, NTS_EINVAL, "moved heads outside the source's heads");
+    if (d->dst_head_off < 0 || d->dst_head_off + d->w > d->Hd)
+        return fail(ctx, NTS_EINVAL, "moved heads outside the destination's heads");
+    if (d->n_req < 0 || (d->n_req > 0 && !d->ctx_len)) return fail(ctx, NTS_EINVAL, "bad request list");
+    const int p = d->page_size;
+    if (d->S_src <= 0 || d->S_dst <= 0 || d->S_src % p || d->S_dst % p)
+        return fail(ctx, NTS_EINVAL, "pool capacities must be positive multiples of the page size");
+    if (d->S_src > INT32_MAX || d->S_dst > INT32_MAX)
+        return fail(ctx, NTS_EINVAL, "pool capacity above 2^31-1 slots");
+
+    const int64_t head_bytes = int64_t(d->D) * d->elem_bytes;
+    const int64_t frag = head_bytes * d->w;
+    const int64_t src_row = head_bytes * d->Hs, dst_row = head_bytes * d->Hd;
+    const int64_t src_stride = d->src_token_stride ? d->src_token_stride : src_row;
+    const int64_t dst_stride = d->dst_token_stride ? d->dst_token_stride : dst_row;
+    if (src_stride < src_row || dst_stride < dst_row)
+        return fail(ctx, NTS_EINVAL, "token stride smaller than a token row");
+    const int64_t so = head_bytes * d->src_head_off, dof = head_bytes * d->dst_head_off;
+    int vec = 16;
+    while (vec >= 4 && (frag % vec || src_stride % vec || dst_stride % vec || so % vec || dof % vec)) vec >>= 1;
+    if (vec < 4) return fail(ctx, NTS_EINVAL, "fragment size, head offsets and strides must be multiples of 4 bytes");
+
+    // host prefix sums over requests
+    std::vector<int32_t> tok_off, pg_off;
+    try {
+        tok_off.resize(size_t(d->n_req) + 1);
+        pg_off.resize(size_t(d->n_req) + 1);
+    } catch (...) {
+        return fail(ctx, NTS_ENOMEM, "host allocation failed");
+    }
+    int64_t T = 0, NP = 0;
+    for (int r = 0; r < d->n_req; ++r) {
+        const int32_t n = d->ctx_len[r];
+        if (n < 0) return fail(ctx, NTS_EINVAL, "negative context length");
+        tok_off[r] = int32_t(T);
+        pg_off[r] = int32_t(NP);
+        T += n;
+        NP += (int64_t(n) + p - 1) / p;
+        if (T > INT32_MAX) return fail(ctx, NTS_EINVAL, "more than 2^31-1 tokens");
+    }
+    tok_off[d->n_req] = int32_t(T);
+    pg_off[d->n_req] = int32_t(NP);
+    if (T > 0 && (!d->src_pages || !d->dst_pages)) return fail(ctx, NTS_EINVAL, "null page table");
+
+    nts_plan *pl = new (std::nothrow) nts_plan;
+    if (!pl) return fail(ctx, NTS_ENOMEM, "host allocation failed");
+    pl->ctx = ctx;
+    pl->L = d->L; pl->D = d->D; pl->e = d->elem_bytes; pl->p = p;
+    pl->Hs = d->Hs; pl->Hd = d->Hd;
+    pl->src_head_off = d->src_head_off; pl->dst_head_off = d->dst_head_off; pl->w = d->w;
+    pl->S_src = d->S_src; pl->S_dst = d->S_dst;
+    pl->src_stride = src_stride; pl->dst_stride = dst_stride;
+    pl->T = T;
+    pl->F = T * 2 * d->L;
+    pl->frag_bytes = frag;
+    pl->X = pl->F * frag;
+    pl->vec = vec;
+    int64_t B = d->staging_bytes > 0 ? d->staging_bytes : int64_t(NTS_DEFAULT_STAGING_BYTES);
+    int64_t cf = B / frag;
+    if (cf < 1) cf = 1;
+    if (cf > (int64_t(1) << 30)) cf = int64_t(1) << 30;   // a launch covers fewer than 2^31 fragments
+    pl->chunk_frags = cf;
+    pl->chunk_bytes = cf * frag;
+    pl->n_chunks = (pl->F + cf - 1) / cf;
+
+    if (T == 0) {
+        ++ctx->n_plans;
+        *out = pl;
+        return NTS_OK;
+    }
+
+    DeviceGuard guard(ctx->device);
+    // one device block: sslot | dslot | [tok_off | pg_off | src pages | dst pages | bitmap | err]
+    const bool uniq = (d->flags & NTS_VALIDATE_UNIQUE_DST) != 0;
+    const int64_t n_off = int64_t(d->n_req) + 1;
+    const int64_t b_slots = align_up(T * 4, 256);
+    const int64_t b_off = align_up(n_off * 4, 256);
+    const int64_t b_pages = align_up(NP * 4, 256);
+    const int64_t bitmap_words = uniq ? (d->S_dst + 31) / 32 : 0;
+    const int64_t b_bitmap = align_up(bitmap_words * 4, 256);
+    const int64_t total = 2 * b_slots + 2 * b_off + 2 * b_pages + b_bitmap + 256;
+    char *blk = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&blk), size_t(total));
+    if (e != hipSuccess) {
+        delete pl;
+        (void)hipGetLastError();
+        return fail(ctx, e == hipErrorOutOfMemory ? NTS_ENOMEM : NTS_EHIP, "device allocation of the plan failed");
+    }
+    pl->d_block = blk;
+    pl->d_sslot = reinterpret_cast<int32_t *>(blk);
+    pl->d_dslot = reinterpret_cast<int32_t *>(blk + b_slots);
+    int32_t *d_tok = reinterpret_cast<int32_t *>(blk + 2 * b_slots);
+    int32_t *d_pg = reinterpret_cast<int32_t *>(blk + 2 * b_slots + b_off);
+    int32_t *d_sp = reinterpret_cast<int32_t *>(blk + 2 * b_slots + 2 * b_off);
+    int32_t *d_dp = reinterpret_cast<int32_t *>(blk + 2 * b_slots + 2 * b_off + b_pages);
+    uint32_t *d_bm = uniq ? reinterpret_cast<uint32_t *>(blk + 2 * b_slots + 2 * b_off + 2 * b_pages) : nullptr;
+    int32_t *d_err = reinterpret_cast<int32_t *>(blk + total - 256);
+
+    int32_t h_err[2] = {0, 0};
+    hipStream_t st = ctx->aux;
+    do {
+        if ((e = hipMemcpyAsync(d_tok, tok_off.data(), size_t(n_off) * 4, hipMemcpyHostToDevice, st)) != hipSuccess) break;
+        if ((e = hipMemcpyAsync(d_pg, pg_off.data(), size_t(n_off) * 4, hipMemcpyHostToDevice, st)) != hipSuccess) break;
+        if ((e = hipMemcpyAsync(d_sp, d->src_pages, size_t(NP) * 4, hipMemcpyHostToDevice, st)) != hipSuccess) break;
+        if ((e = hipMemcpyAsync(d_dp, d->dst_pages, size_t(NP) * 4, hipMemcpyHostToDevice, st)) != hipSuccess) break;
+        if ((e = hipMemsetAsync(d_err, 0, 8, st)) != hipSuccess) break;
+        if (uniq && (e = hipMemsetAsync(d_bm, 0, size_t(bitmap_words) * 4, st)) != hipSuccess) break;
+        if ((e = nts_launch_flatten(d_tok, d_pg, d_sp, d->n_req, uint32_t(T), p, d->S_src / p,
+                                    pl->d_sslot, nullptr, d_err, st)) != hipSuccess) break;
+        if ((e = nts_launch_flatten(d_tok, d_pg, d_dp, d->n_req, uint32_t(T), p, d->S_dst / p,
+                                    pl->d_dslot, d_bm, d_err, st)) != hipSuccess) break;
+        if ((e = hipMemcpyAsync(h_err, d_err, 8, hipMemcpyDeviceToHost, st)) != hipSuccess) break;
+        e = hipStreamSynchronize(st);
+    } while (0);
+    if (e != hipSuccess || h_err[0] || h_err[1]) {
+        (void)hipFree(blk);
+        delete pl;
+        if (e != hipSuccess) return fail_hip(ctx, e, "nts_plan_create");
+        if (h_err[0]) return fail(ctx, NTS_ERANGE, "a page id lies outside its pool");
+        return fail(ctx, NTS_EDUP, "two migrated tokens share a destination slot");
+    }
+    ++ctx->n_plans;
+    *out = pl;
+    return NTS_OK;
+}
+
+int nts_plan_free(nts_plan *pl)
+{
+    if (!pl) return NTS_OK;
+    nts_ctx *ctx = pl->ctx;
+    int rc = NTS_OK;
+    if (pl->d_block) {
+        DeviceGuard guard(ctx->device);
+        hipError_t e = hipFree(pl->d_block);
+        if (e != hipSuccess) rc = fail_hip(ctx, e, "hipFree");
+    }
+    --ctx->n_plans;
+    delete pl;
+    return rc;
+}
+
+int nts_plan_info(const nts_plan *pl, nts_info *out)
+{
+    if (!pl || !out) return NTS_EINVAL;
+    out->T = pl->T;
+    out->F = pl->F;
+    out->frag_bytes = pl->frag_bytes;
+    out->X = pl->X;
+    out->chunk_frags = pl->chunk_frags;
+    out->chunk_bytes = pl->chunk_bytes;
+    out->n_chunks = pl->n_chunks;
+    out->vec_bytes = pl->vec;
+    out->reserved = 0;
+    return NTS_OK;
+}
+
+int nts_plan_slots(const nts_plan *pl, int32_t *sslot_host, int32_t *dslot_host)
+{
+    if (!pl) return NTS_EINVAL;
+    if (pl->T == 0) return NTS_OK;
+    DeviceGuard guard(pl->ctx->device);
+    if (sslot_host) NTS_HIP(pl->ctx, hipMemcpy(sslot_host, pl->d_sslot, size_t(pl->T) * 4, hipMemcpyDeviceToHost));
+    if (dslot_host) NTS_HIP(pl->ctx, hipMemcpy(dslot_host, pl->d_dslot, size_t(pl->T) * 4, hipMemcpyDeviceToHost));
+    return NTS_OK;
+}
+
+static int run_range(nts_plan *pl, NtsMoveMode mode, const void *const *layer_ptrs, int64_t q0,
+                     int64_t n_frag, void *linear, void *hip_stream)
+{
+    if (!pl) return NTS_EINVAL;
+    nts_ctx *ctx = pl->ctx;
+    if (!layer_ptrs) return fail(ctx, NTS_EINVAL, "null layer pointer table");
+    if (n_frag <= 0) return NTS_OK;
+    if (!linear) return fail(ctx, NTS_EINVAL, "null stream buffer");
+    if (reinterpret_cast<uintptr_t>(linear) % uintptr_t(pl->vec)) return fail(ctx, NTS_EINVAL, "stream buffer misaligned");
+    NtsLayerTab tab;
+    if (fill_tab(pl, layer_ptrs, tab) != NTS_OK) return fail(ctx, NTS_EINVAL, "null or misaligned layer pointer");
+    DeviceGuard guard(ctx->device);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    // a launch covers at most chunk-limit fragments; the whole stream may need several
+    const int64_t lim = int64_t(1) << 30;
+    char *lin = static_cast<char *>(linear);
+    for (int64_t done = 0; done < n_frag; done += lim) {
+        const int64_t n = n_frag - done < lim ? n_frag - done : lim;
+        NTS_HIP(ctx, nts_launch_move(mode, pl, q0 + done, n, tab, lin + done * pl->frag_bytes, st));
+    }
+    return NTS_OK;
+}
+
+int nts_run_pack(nts_plan *pl, const void *const *src_layer_ptrs, void *stream_out, void *hip_stream)
+{
+    if (!pl) return NTS_EINVAL;
+    return run_range(pl, NTS_MOVE_PACK, src_layer_ptrs, 0, pl->F, stream_out, hip_stream);
+}
+
+int nts_run_unpack(nts_plan *pl, const void *stream_in, void *const *dst_layer_ptrs, void *hip_stream)
+{
+    if (!pl) return NTS_EINVAL;
+    return run_range(pl, NTS_MOVE_UNPACK, dst_layer_ptrs, 0, pl->F, const_cast<void *>(stream_in), hip_stream);
+}
+
+static int chunk_range(const nts_plan *pl, int64_t k, int64_t *q0, int64_t *n)
+{
+    if (k < 0 || k >= pl->n_chunks) return NTS_EINVAL;
+    *q0 = k * pl->chunk_frags;
+    *n = pl->F - *q0 < pl->chunk_frags ? pl->F - *q0 : pl->chunk_frags;
+    return NTS_OK;
+}
+
+int nts_run_pack_chunk(nts_plan *pl, const void *const *src_layer_ptrs, int64_t k, void *chunk_out, void *hip_stream)
+{
+    if (!pl) return NTS_EINVAL;
+    int64_t q0, n;
+    if (chunk_range(pl, k, &q0, &n) != NTS_OK) return fail(pl->ctx, NTS_EINVAL, "chunk index out of range");
+    return run_range(pl, NTS_MOVE_PACK, src_layer_ptrs, q0, n, chunk_out, hip_stream);
+}
+
+int nts_run_unpack_chunk(nts_plan *pl, const void *chunk_in, int64_t k, void *const *dst_layer_ptrs, void *hip_stream)
+{
+    if (!pl) return NTS_EINVAL;
+    int64_t q0, n;
+    if (chunk_range(pl, k, &q0, &n) != NTS_OK) return fail(pl->ctx, NTS_EINVAL, "chunk index out of range");
+    return run_range(pl, NTS_MOVE_UNPACK, dst_layer_ptrs, q0, n, const_cast<void *>(chunk_in), hip_stream);
+}
+
+int nts_run_migrate(nts_plan *pl, const void *const *src_layer_ptrs, void *const *dst_layer_ptrs,
+                    void *staging, void *hip_stream)
+{
+    if (!pl) return NTS_EINVAL;
+    nts_ctx *ctx = pl->ctx;
+    if (!src_layer_ptrs || !dst_layer_ptrs) return fail(ctx, NTS_EINVAL, "null layer pointer table");
+    if (pl->F == 0) return NTS_OK;
+    if (!staging) return fail(ctx, NTS_EINVAL, "null staging area");
+    if (reinterpret_cast<uintptr_t>(staging) % uintptr_t(pl->vec)) return fail(ctx, NTS_EINVAL, "staging area misaligned");
+    NtsLayerTab stab, dtab;
+    if (fill_tab(pl, src_layer_ptrs, stab) != NTS_OK || fill_tab(pl, reinterpret_cast<const void *const *>(dst_layer_ptrs), dtab) != NTS_OK)
+        return fail(ctx, NTS_EINVAL, "null or misaligned layer pointer");
+    // byte ranges: source layers vs destination layers vs staging
+    const int64_t src_span = pl->S_src * pl->src_stride, dst_span = pl->S_dst * pl->dst_stride;
+    // chunk_bytes is a multiple of the vector width, so the second buffer stays aligned
+    const int64_t buf_stride = pl->chunk_bytes;
+    const char *stg = static_cast<const char *>(staging);
+    const int64_t stg_span = 2 * pl->chunk_bytes;
+    const int n = 2 * pl->L;
+    for (int i = 0; i < n; ++i) {
+        if (overlaps(stab.p[i], src_span, stg, stg_span) || overlaps(dtab.p[i], dst_span, stg, stg_span))
+            return fail(ctx, NTS_EALIAS, "staging area overlaps a pool");
+        for (int k = 0; k < n; ++k)
+            if (overlaps(stab.p[i], src_span, dtab.p[k], dst_span))
+                return fail(ctx, NTS_EALIAS, "source and destination pools overlap");
+    }
+
+    DeviceGuard guard(ctx->device);
+    hipStream_t a = static_cast<hipStream_t>(hip_stream), b = ctx->aux;
+    char *buf[2] = {static_cast<char *>(staging), static_cast<char *>(staging) + buf_stride};
+    NTS_HIP(ctx, hipEventRecord(ctx->ev_fork, a));
+    NTS_HIP(ctx, hipStreamWaitEvent(b, ctx->ev_fork, 0));
+    for (int64_t k = 0; k < pl->n_chunks; ++k) {
+        const int s = int(k & 1);
+        int64_t q0, nf;
+        chunk_range(pl, k, &q0, &nf);
+        if (k >= 2) NTS_HIP(ctx, hipStreamWaitEvent(a, ctx->ev_unpacked[s], 0));   // buffer s is free again
+        NTS_HIP(ctx, nts_launch_move(NTS_MOVE_PACK, pl, q0, nf, stab, buf[s], a));
+        NTS_HIP(ctx, hipEventRecord(ctx->ev_packed[s], a));
+        NTS_HIP(ctx, hipStreamWaitEvent(b, ctx->ev_packed[s], 0));
+        NTS_HIP(ctx, nts_launch_move(NTS_MOVE_UNPACK, pl, q0, nf, dtab, buf[s], b));
+        NTS_HIP(ctx, hipEventRecord(ctx->ev_unpacked[s], b));
+    }
+    // join: the caller's stream completes after the last unpacks
+    NTS_HIP(ctx, hipStreamWaitEvent(a, ctx->ev_unpacked[(pl->n_chunks - 1) & 1], 0));
+    if (pl->n_chunks >= 2) NTS_HIP(ctx, hipStreamWaitEvent(a, ctx->ev_unpacked[(pl->n_chunks - 2) & 1], 0));
+    return NTS_OK;
+}
+
+}  // extern "C"

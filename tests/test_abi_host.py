@@ -1,0 +1,68 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, and its host-only routing step agrees with
+the oracle."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import kvmig as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2605_05467_amd import binding
+    return binding
+
+
+def declared_symbols():
+    names = []
+    for fn in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names += re.findall(r"\b(nts_[a-z_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol(b):
+    names = declared_symbols()
+    assert len(names) >= 14
+    lib = ctypes.CDLL(b.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(b.EXPORTS) == names
+
+
+def test_route_matches_oracle_everywhere(b):
+    for H in (8, 16, 32, 64):
+        for Ns in (1, 2, 4, 8):
+            for Nd in (1, 2, 4, 8):
+                for rs in range(Ns):
+                    for rd in range(Nd):
+                        assert b.nts_route(H, Ns, rs, Nd, rd) == orc.route(H, Ns, rs, Nd, rd)
+    for bad in [(8, 3, 0, 1, 0), (8, 2, 2, 1, 0), (8, 1, 0, 16, 0), (0, 1, 0, 1, 0), (8, 2, -1, 2, 0)]:
+        with pytest.raises(b.NtsError) as ei:
+            b.nts_route(*bad)
+        assert ei.value.status == b.NTS_EINVAL
+
+
+def test_null_arguments_are_rejected_without_a_gpu(b):
+    lib = ctypes.CDLL(b.LIB_PATH)
+    assert lib.nts_plan_create(None, None, None) == b.NTS_EINVAL
+    assert lib.nts_plan_info(None, None) == b.NTS_EINVAL
+    assert lib.nts_run_pack(None, None, None, None) == b.NTS_EINVAL
+    assert lib.nts_run_migrate(None, None, None, None, None) == b.NTS_EINVAL
+    assert lib.nts_plan_free(None) == b.NTS_OK and lib.nts_free(None) == b.NTS_OK
+    assert lib.nts_init(0, None) == b.NTS_EINVAL
+    assert b.nts_strerror(b.NTS_EALIAS) == "source and destination overlap"
+    assert b.nts_strerror(12345) == "unknown status"
+
+
+def test_struct_sizes_match_the_header(b):
+    # nts_desc: 10 int32, 2 int64, 3 pointers, 3 int64, 2 uint32; nts_info: 7 int64 + 2 int32
+    assert ctypes.sizeof(b.nts_desc) == 40 + 16 + 24 + 24 + 8
+    assert ctypes.sizeof(b.nts_info) == 64

@@ -1,0 +1,282 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Byte movers: the bar is bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import kvmig as orc
+from workload import M8B, ModelShape, fill_pool_u16, make_case, SplitMix64
+from workload.configs import PairCase, random_pages, lengths_uniform
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2605_05467_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def ctx(b):
+    c = b.nts_init(0)
+    yield c
+    b.nts_free(c)
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    return torch
+
+
+def _expected_full(case, L, D):
+    """Oracle result on whole pools (small cases only)."""
+    from gpu_util import host_layers, oracle_slots
+    so, do, w = orc.route(case.shape.H, case.Ns, case.rs, case.Nd, case.rd)
+    src = host_layers(case, "src", range(L), D=D)
+    dst = host_layers(case, "dst", range(L), D=D).copy()
+    sslot, dslot = oracle_slots(case)
+    stream = orc.pack(src, sslot, so, w)
+    orc.unpack(stream, dst, dslot, do)
+    return src, stream, dst
+
+
+def test_device_fill_matches_host_fill(torch):
+    from workload import device as wdev
+    from workload import fill_words
+    t = torch.empty(8 * 100003, dtype=torch.uint8, device="cuda")
+    wdev.fill_tensor(t, 1234, start_word=77)
+    got = t.cpu().numpy().view("<u8")
+    assert np.array_equal(got, fill_words(1234, 77, 100003))
+    assert wdev.count_mismatch(t, 1234, start_word=77) == 0
+    t[8 * 5] ^= 1
+    assert wdev.count_mismatch(t, 1234, start_word=77) == 1
+
+
+@pytest.mark.parametrize("p", [1, 4, 16])
+def test_plan_flattening_matches_oracle(b, ctx, p):
+    from gpu_util import make_plan, oracle_slots
+    rng = SplitMix64(40 + p)
+    ctx_len = np.array([0, 5, 17, 0, 1, 64, 33, 0], np.int32)
+    S = 256
+    case = PairCase(name="t", shape=M8B, p=p, Ns=1, rs=0, Nd=2, rd=1, S_src=S, S_dst=S, ctx_len=ctx_len,
+                    src_pages=random_pages(rng, ctx_len, p, S // p, "fragmented"),
+                    dst_pages=random_pages(rng, ctx_len, p, S // p, "fragmented"),
+                    seed_src=1, seed_dst=2)
+    plan = make_plan(b, ctx, case, L=2)
+    try:
+        s, d = b.nts_plan_slots(plan)
+        es, ed = oracle_slots(case)
+        assert np.array_equal(s, es) and np.array_equal(d, ed)
+        info = b.nts_plan_info(plan)
+        assert info.T == int(ctx_len.sum()) and info.F == info.T * 4
+        assert info.frag_bytes == 4 * 128 * 2 and info.X == info.F * info.frag_bytes
+    finally:
+        b.nts_plan_free(plan)
+
+
+@pytest.mark.parametrize("idx", range(7))
+def test_c1_pack_unpack_migrate(b, ctx, torch, idx):
+    """Configuration 1 (~1e4 fragments), every TP-switch shape, whole outputs."""
+    from gpu_util import device_pool, make_plan, slab_bytes, to_host
+    case = make_case("c1")[idx]
+    sh = case.shape
+    src_h, stream_h, dst_h = _expected_full(case, sh.L, sh.D)
+    src_d, dst_d = device_pool(case, "src"), device_pool(case, "dst")
+    assert np.array_equal(to_host(src_d).view(np.uint16), src_h.reshape(-1))
+    sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+    dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
+    plan = make_plan(b, ctx, case)
+    try:
+        info = b.nts_plan_info(plan)
+        assert info.X == stream_h.nbytes
+        out = torch.zeros(info.X, dtype=torch.uint8, device="cuda")
+        st = torch.cuda.current_stream().cuda_stream
+        b.nts_run_pack(plan, sp, out.data_ptr(), st)
+        torch.cuda.synchronize()
+        assert to_host(out).tobytes() == stream_h.tobytes()
+        b.nts_run_unpack(plan, out.data_ptr(), dp, st)
+        torch.cuda.synchronize()
+        assert to_host(dst_d).tobytes() == dst_h.tobytes()
+        assert np.array_equal(to_host(src_d).view(np.uint16), src_h.reshape(-1))   # source untouched
+    finally:
+        b.nts_plan_free(plan)
+    # the pipelined migration gives the same pool for any staging size
+    for B in (0, info.frag_bytes, 7 * info.frag_bytes, 65536 + 512, 1 << 20):
+        dst2 = device_pool(case, "dst")
+        dp2 = b.layer_ptrs(dst2.data_ptr(), sh.L, slab_bytes(case, "dst"))
+        if B == info.frag_bytes and info.F > 4096:
+            B = info.frag_bytes * 3
+        plan = make_plan(b, ctx, case, staging_bytes=B)
+        try:
+            i2 = b.nts_plan_info(plan)
+            staging = torch.empty(2 * i2.chunk_bytes, dtype=torch.uint8, device="cuda")
+            b.nts_run_migrate(plan, sp, dp2, staging.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            assert to_host(dst2).tobytes() == dst_h.tobytes(), B
+        finally:
+            b.nts_plan_free(plan)
+
+
+def test_chunks_concatenate_to_the_stream(b, ctx, torch):
+    from gpu_util import device_pool, make_plan, slab_bytes, to_host
+    case = make_case("c1")[0]
+    sh = case.shape
+    _, stream_h, _ = _expected_full(case, sh.L, sh.D)
+    src_d = device_pool(case, "src")
+    sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+    plan = make_plan(b, ctx, case, staging_bytes=300 * 1024 + 4)     # 293 fragments per chunk
+    try:
+        info = b.nts_plan_info(plan)
+        assert info.chunk_frags == (300 * 1024 + 4) // info.frag_bytes
+        parts = []
+        for k in range(info.n_chunks):
+            buf = torch.full((info.chunk_bytes,), 0xA5, dtype=torch.uint8, device="cuda")
+            b.nts_run_pack_chunk(plan, sp, k, buf.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            n = min(info.chunk_frags, info.F - k * info.chunk_frags) * info.frag_bytes
+            h = to_host(buf)
+            assert (h[n:] == 0xA5).all()                              # nothing past the chunk
+            parts.append(h[:n])
+        assert np.concatenate(parts).tobytes() == stream_h.tobytes()
+    finally:
+        b.nts_plan_free(plan)
+
+
+@pytest.mark.parametrize("shape,tr,p,T", [
+    (ModelShape(L=3, H=8, D=64, e=1), (1, 0, 2, 1), 1, 300),      # fp8 KV, 256 B fragments
+    (ModelShape(L=2, H=6, D=40, e=2), (1, 0, 2, 0), 2, 157),      # 240 B fragments: 48 B-aligned -> 16 B vectors
+    (ModelShape(L=2, H=6, D=20, e=2), (2, 1, 1, 0), 4, 97),       # 120 B fragments -> 8 B vectors
+    (ModelShape(L=2, H=3, D=1, e=4), (1, 0, 1, 0), 1, 513),       # 12 B fragments -> 4 B vectors
+    (ModelShape(L=5, H=32, D=128, e=2), (1, 0, 1, 0), 16, 200),   # 8 KiB fragments: several column steps
+    (ModelShape(L=2, H=12, D=128, e=2), (1, 0, 4, 3), 1, 333),    # 3 heads: 768 B, 48 of 64 lanes
+    (ModelShape(L=1, H=8, D=128, e=4), (4, 1, 8, 2), 1, 1),       # a single token
+])
+def test_other_geometries(b, ctx, torch, shape, tr, p, T):
+    from gpu_util import device_pool, make_plan, slab_bytes, to_host
+    rng = SplitMix64(T)
+    n_req = min(5, T)
+    ctx_len = lengths_uniform(rng, n_req, 1, 50, T)
+    S = ((T + n_req * p) * 2 // p + 1) * p
+    Ns, rs, Nd, rd = tr
+    case = PairCase(name="g", shape=shape, p=p, Ns=Ns, rs=rs, Nd=Nd, rd=rd, S_src=S, S_dst=S,
+                    ctx_len=ctx_len, src_pages=random_pages(rng, ctx_len, p, S // p, "fragmented"),
+                    dst_pages=random_pages(rng, ctx_len, p, S // p, "fragmented"), seed_src=5, seed_dst=6)
+    if (2 * S * case.Hs * shape.D * shape.e) % 8 or (2 * S * case.Hd * shape.D * shape.e) % 8:
+        pytest.skip("layer size not a multiple of the fill word")
+    _, stream_h, dst_h = _expected_full(case, shape.L, shape.D)
+    src_d, dst_d = device_pool(case, "src"), device_pool(case, "dst")
+    sp = b.layer_ptrs(src_d.data_ptr(), shape.L, slab_bytes(case, "src"))
+    dp = b.layer_ptrs(dst_d.data_ptr(), shape.L, slab_bytes(case, "dst"))
+    plan = make_plan(b, ctx, case, staging_bytes=40000)
+    try:
+        info = b.nts_plan_info(plan)
+        out = torch.zeros(info.X, dtype=torch.uint8, device="cuda")
+        b.nts_run_pack(plan, sp, out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert to_host(out).tobytes() == stream_h.tobytes()
+        staging = torch.empty(2 * info.chunk_bytes, dtype=torch.uint8, device="cuda")
+        b.nts_run_migrate(plan, sp, dp, staging.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert to_host(dst_d).tobytes() == dst_h.tobytes()
+    finally:
+        b.nts_plan_free(plan)
+
+
+def test_separate_layer_allocations_and_padded_rows(b, ctx, torch):
+    """2L independent allocations with a token stride wider than a row."""
+    from gpu_util import to_host
+    L, H, D, e, S, T = 3, 4, 32, 2, 64, 50
+    row = H * D * e
+    stride = row + 64
+    rng = SplitMix64(9)
+    ctx_len = np.array([20, 30], np.int32)
+    sp_h = rng.permutation(S)[:T].astype(np.int32)
+    dp_h = rng.permutation(S)[:T].astype(np.int32)
+    src_h = [(rng.words(S * stride // 8)).view(np.uint8).copy() for _ in range(2 * L)]
+    dst_h = [(rng.words(S * stride // 8)).view(np.uint8).copy() for _ in range(2 * L)]
+    src_d = [torch.from_numpy(a).cuda() for a in src_h]
+    dst_d = [torch.from_numpy(a).cuda() for a in dst_h]
+    so, do, w = b.nts_route(H, 1, 0, 1, 0)
+    plan = b.nts_plan_create(ctx, L=L, D=D, elem_bytes=e, page_size=1, Hs=H, Hd=H, src_head_off=so,
+                             dst_head_off=do, w=w, S_src=S, S_dst=S, ctx_len=ctx_len, src_pages=sp_h,
+                             dst_pages=dp_h, src_token_stride=stride, dst_token_stride=stride,
+                             staging_bytes=4096, flags=b.NTS_VALIDATE_UNIQUE_DST)
+    try:
+        info = b.nts_plan_info(plan)
+        staging = torch.empty(2 * info.chunk_bytes, dtype=torch.uint8, device="cuda")
+        b.nts_run_migrate(plan, [t.data_ptr() for t in src_d], [t.data_ptr() for t in dst_d],
+                          staging.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+    finally:
+        b.nts_plan_free(plan)
+    # oracle on the row part of each array (the padding is not KV and must not change)
+    for i in range(2 * L):
+        s2 = src_h[i].reshape(S, stride)[:, :row].copy().view(np.uint16).reshape(1, 1, S, H, D)
+        d2 = dst_h[i].reshape(S, stride)[:, :row].copy().view(np.uint16).reshape(1, 1, S, H, D)
+        s2 = np.concatenate([s2, s2], axis=1)
+        d2 = np.concatenate([d2, d2], axis=1).copy()
+        orc.migrate_direct(np.ascontiguousarray(s2), d2, orc.flatten(ctx_len, sp_h, 1),
+                           orc.flatten(ctx_len, dp_h, 1), so, do, w)
+        got = to_host(dst_d[i]).reshape(S, stride)
+        assert got[:, :row].tobytes() == d2[0, 0].tobytes()
+        assert np.array_equal(got[:, row:], dst_h[i].reshape(S, stride)[:, row:])
+
+
+def test_error_paths_and_empty_plans(b, ctx, torch):
+    kw = dict(L=2, D=128, elem_bytes=2, page_size=1, Hs=8, Hd=4, src_head_off=4, dst_head_off=0, w=4,
+              S_src=32, S_dst=32, flags=b.NTS_VALIDATE_UNIQUE_DST)
+    ok = dict(ctx_len=[3, 2], src_pages=[1, 2, 3, 4, 5], dst_pages=[9, 8, 7, 6, 5])
+
+    def status(**over):
+        args = {**kw, **ok, **over}
+        try:
+            plan = b.nts_plan_create(ctx, **args)
+        except b.NtsError as e:
+            return e.status
+        b.nts_plan_free(plan)
+        return 0
+
+    assert status() == 0
+    assert status(src_pages=[1, 2, 3, 4, 32]) == b.NTS_ERANGE
+    assert status(dst_pages=[9, 8, -1, 6, 5]) == b.NTS_ERANGE
+    assert status(dst_pages=[9, 8, 7, 9, 5]) == b.NTS_EDUP
+    assert status(dst_pages=[9, 8, 7, 9, 5], flags=0) == 0           # not checked unless asked
+    assert status(src_pages=[1, 1, 1, 1, 1]) == 0                     # shared source pages are fine
+    assert status(w=0) == b.NTS_EINVAL
+    assert status(src_head_off=5) == b.NTS_EINVAL
+    assert status(dst_head_off=1) == b.NTS_EINVAL
+    assert status(elem_bytes=3) == b.NTS_EINVAL
+    assert status(L=b.NTS_MAX_LAYERS + 1) == b.NTS_EINVAL
+    assert status(ctx_len=[3, -2]) == b.NTS_EINVAL
+    assert status(page_size=3) == b.NTS_EINVAL                        # pool not a multiple of p
+    assert status(D=1, elem_bytes=1, w=1, src_head_off=0) == b.NTS_EINVAL   # 1-byte fragments
+    # zero tokens: legal, run calls are no-ops
+    plan = b.nts_plan_create(ctx, **{**kw, "ctx_len": [0, 0], "src_pages": [], "dst_pages": []})
+    info = b.nts_plan_info(plan)
+    assert (info.T, info.F, info.X, info.n_chunks) == (0, 0, 0, 0)
+    z = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    tab = [z.data_ptr()] * 4
+    b.nts_run_pack(plan, tab, 0)
+    b.nts_run_unpack(plan, 0, tab)
+    b.nts_run_migrate(plan, tab, tab, 0)
+    b.nts_plan_free(plan)
+    plan = b.nts_plan_create(ctx, **{**kw, "ctx_len": [], "src_pages": [], "dst_pages": []})
+    assert b.nts_plan_info(plan).T == 0
+    b.nts_plan_free(plan)
+    # aliasing pools are rejected
+    plan = b.nts_plan_create(ctx, **{**kw, **ok, "Hd": 8, "dst_head_off": 0})
+    pool = torch.zeros(2 * 2 * 32 * 8 * 128 * 2, dtype=torch.uint8, device="cuda")
+    tab = b.layer_ptrs(pool.data_ptr(), 2, 32 * 8 * 128 * 2)
+    staging = torch.zeros(2 * b.nts_plan_info(plan).chunk_bytes, dtype=torch.uint8, device="cuda")
+    with pytest.raises(b.NtsError) as ei:
+        b.nts_run_migrate(plan, tab, tab, staging.data_ptr())
+    assert ei.value.status == b.NTS_EALIAS
+    with pytest.raises(b.NtsError) as ei:
+        b.nts_run_pack(plan, tab, 0)
+    assert ei.value.status == b.NTS_EINVAL
+    with pytest.raises(b.NtsError) as ei:
+        b.nts_run_pack_chunk(plan, tab, 99, staging.data_ptr())
+    assert ei.value.status == b.NTS_EINVAL
+    b.nts_plan_free(plan)
+    torch.cuda.synchronize()
