@@ -20,6 +20,8 @@
  *   - run calls only enqueue work on the given HIP stream (a hipStream_t passed
  *     as void*, NULL = the default stream), allocate nothing and never block
  *     the host.  A context and its plans may be used by one host thread at a time.
+ *     A context keeps a pinned host buffer and one spare device block between
+ *     plans so that planning in a steady loop allocates nothing.
  *
  * Data layout (the paper fixes none; this is the layout of this library)
  *   pool      per GPU and per (layer l, c = 0 for K / 1 for V) one array
@@ -175,14 +177,14 @@ int nts_run_unpack_chunk(nts_plan *plan, const void *chunk_in, int64_t k,
                          void *const *dst_layer_ptrs, void *hip_stream);
 
 /*
- * The whole migration on one GPU with the wire left out: chunk k is packed
- * into staging buffer k&1 while chunk k-1 is unpacked from the other one
- * (double buffering of Sec. 3.2.2, the consumer being the unpack instead of
- * the interconnect).  staging: device, 2 * chunk_bytes.  Packs run on
- * hip_stream, unpacks on a stream the context owns; hip_stream waits for the
- * last unpack before the call's work is complete, so the caller sees one
- * ordered operation.  NTS_EALIAS if a source layer range overlaps a
- * destination layer range or the staging area.
+ * The whole migration on one GPU with the wire left out: the double buffering
+ * of Sec. 3.2.2 with the unpack as the consumer instead of the interconnect.
+ * staging: device, 2 * chunk_bytes (two buffers).  Stage k is ONE kernel launch
+ * whose workgroups alternate between packing chunk k into buffer k&1 and
+ * unpacking chunk k-1 from the other buffer, so the two copies overlap; the
+ * n_chunks + 1 launches go to hip_stream in order, which hands each buffer
+ * from its producer to its consumer.  NTS_EALIAS if a source layer range
+ * overlaps a destination layer range or the staging area.
  */
 int nts_run_migrate(nts_plan *plan, const void *const *src_layer_ptrs,
                     void *const *dst_layer_ptrs, void *staging, void *hip_stream);

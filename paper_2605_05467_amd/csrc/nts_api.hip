@@ -100,11 +100,6 @@ int nts_init(int device_id, nts_ctx **out)
     DeviceGuard guard(device_id);
     hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
-    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
-        e = hipEventCreateWithFlags(&ctx->ev_packed[i], hipEventDisableTiming);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_unpacked[i], hipEventDisableTiming);
-    }
     if (e != hipSuccess) {
         nts_free(ctx);
         (void)hipGetLastError();
@@ -123,11 +118,8 @@ int nts_free(nts_ctx *ctx)
         (void)hipStreamSynchronize(ctx->aux);
         (void)hipStreamDestroy(ctx->aux);
     }
-    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
-    for (int i = 0; i < 2; ++i) {
-        if (ctx->ev_packed[i]) (void)hipEventDestroy(ctx->ev_packed[i]);
-        if (ctx->ev_unpacked[i]) (void)hipEventDestroy(ctx->ev_unpacked[i]);
-    }
+    if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
+    if (ctx->d_spare) (void)hipFree(ctx->d_spare);
     delete ctx;
     return NTS_OK;
 }
@@ -224,7 +216,8 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     int64_t B = d->staging_bytes > 0 ? d->staging_bytes : int64_t(NTS_DEFAULT_STAGING_BYTES);
     int64_t cf = B / frag;
     if (cf < 1) cf = 1;
-    if (cf > (int64_t(1) << 30)) cf = int64_t(1) << 30;   // a launch covers fewer than 2^31 fragments
+    const int64_t cf_max = nts_max_frags_per_launch(pl) / 2;   // a stage launch packs one chunk and unpacks another
+    if (cf > cf_max) cf = cf_max > 1 ? cf_max : 1;
     pl->chunk_frags = cf;
     pl->chunk_bytes = cf * frag;
     pl->n_chunks = (pl->F + cf - 1) / cf;
@@ -236,53 +229,88 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     }
 
     DeviceGuard guard(ctx->device);
-    // one device block: sslot | dslot | [tok_off | pg_off | src pages | dst pages | bitmap | err]
+    // device block: sslot | dslot | meta (tok_off | pg_off | src pages | dst pages) | bitmap | err
+    // pinned host block: err readback (256 B) | meta
     const bool uniq = (d->flags & NTS_VALIDATE_UNIQUE_DST) != 0;
     const int64_t n_off = int64_t(d->n_req) + 1;
     const int64_t b_slots = align_up(T * 4, 256);
     const int64_t b_off = align_up(n_off * 4, 256);
     const int64_t b_pages = align_up(NP * 4, 256);
+    const int64_t b_meta = 2 * b_off + 2 * b_pages;
     const int64_t bitmap_words = uniq ? (d->S_dst + 31) / 32 : 0;
     const int64_t b_bitmap = align_up(bitmap_words * 4, 256);
-    const int64_t total = 2 * b_slots + 2 * b_off + 2 * b_pages + b_bitmap + 256;
+    const int64_t total = 2 * b_slots + b_meta + b_bitmap + 256;
+
+    hipError_t e = hipSuccess;
+    if (ctx->h_pinned_bytes < size_t(b_meta + 256)) {
+        if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
+        ctx->h_pinned = nullptr;
+        ctx->h_pinned_bytes = 0;
+        const size_t want = size_t(b_meta + 256) * 2;
+        e = hipHostMalloc(&ctx->h_pinned, want, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            delete pl;
+            (void)hipGetLastError();
+            return fail(ctx, NTS_ENOMEM, "pinned host allocation failed");
+        }
+        ctx->h_pinned_bytes = want;
+    }
     char *blk = nullptr;
-    hipError_t e = hipMalloc(reinterpret_cast<void **>(&blk), size_t(total));
-    if (e != hipSuccess) {
-        delete pl;
-        (void)hipGetLastError();
-        return fail(ctx, e == hipErrorOutOfMemory ? NTS_ENOMEM : NTS_EHIP, "device allocation of the plan failed");
+    size_t blk_bytes = 0;
+    if (ctx->d_spare && ctx->d_spare_bytes >= size_t(total)) {      // reuse the last freed plan's block
+        blk = static_cast<char *>(ctx->d_spare);
+        blk_bytes = ctx->d_spare_bytes;
+        ctx->d_spare = nullptr;
+        ctx->d_spare_bytes = 0;
+    } else {
+        e = hipMalloc(reinterpret_cast<void **>(&blk), size_t(total));
+        if (e != hipSuccess) {
+            delete pl;
+            (void)hipGetLastError();
+            return fail(ctx, e == hipErrorOutOfMemory ? NTS_ENOMEM : NTS_EHIP, "device allocation of the plan failed");
+        }
+        blk_bytes = size_t(total);
     }
     pl->d_block = blk;
+    pl->d_block_bytes = blk_bytes;
     pl->d_sslot = reinterpret_cast<int32_t *>(blk);
     pl->d_dslot = reinterpret_cast<int32_t *>(blk + b_slots);
-    int32_t *d_tok = reinterpret_cast<int32_t *>(blk + 2 * b_slots);
-    int32_t *d_pg = reinterpret_cast<int32_t *>(blk + 2 * b_slots + b_off);
-    int32_t *d_sp = reinterpret_cast<int32_t *>(blk + 2 * b_slots + 2 * b_off);
-    int32_t *d_dp = reinterpret_cast<int32_t *>(blk + 2 * b_slots + 2 * b_off + b_pages);
-    uint32_t *d_bm = uniq ? reinterpret_cast<uint32_t *>(blk + 2 * b_slots + 2 * b_off + 2 * b_pages) : nullptr;
-    int32_t *d_err = reinterpret_cast<int32_t *>(blk + total - 256);
+    char *d_meta = blk + 2 * b_slots;
+    char *h_meta = static_cast<char *>(ctx->h_pinned) + 256;
+    volatile int32_t *h_err = static_cast<volatile int32_t *>(ctx->h_pinned);
+    memcpy(h_meta, tok_off.data(), size_t(n_off) * 4);
+    memcpy(h_meta + b_off, pg_off.data(), size_t(n_off) * 4);
+    memcpy(h_meta + 2 * b_off, d->src_pages, size_t(NP) * 4);
+    memcpy(h_meta + 2 * b_off + b_pages, d->dst_pages, size_t(NP) * 4);
+    h_err[0] = h_err[1] = 0;
+    char *d_bm = d_meta + b_meta;
+    int32_t *d_err = reinterpret_cast<int32_t *>(d_bm + b_bitmap);
+    NtsFlattenSide fs, fd;
+    fs.pages = reinterpret_cast<const int32_t *>(d_meta + 2 * b_off);
+    fs.slots = pl->d_sslot;
+    fs.bitmap = nullptr;
+    fs.n_pool_pages = d->S_src / p;
+    fd.pages = reinterpret_cast<const int32_t *>(d_meta + 2 * b_off + b_pages);
+    fd.slots = pl->d_dslot;
+    fd.bitmap = uniq ? reinterpret_cast<uint32_t *>(d_bm) : nullptr;
+    fd.n_pool_pages = d->S_dst / p;
 
-    int32_t h_err[2] = {0, 0};
     hipStream_t st = ctx->aux;
     do {
-        if ((e = hipMemcpyAsync(d_tok, tok_off.data(), size_t(n_off) * 4, hipMemcpyHostToDevice, st)) != hipSuccess) break;
-        if ((e = hipMemcpyAsync(d_pg, pg_off.data(), size_t(n_off) * 4, hipMemcpyHostToDevice, st)) != hipSuccess) break;
-        if ((e = hipMemcpyAsync(d_sp, d->src_pages, size_t(NP) * 4, hipMemcpyHostToDevice, st)) != hipSuccess) break;
-        if ((e = hipMemcpyAsync(d_dp, d->dst_pages, size_t(NP) * 4, hipMemcpyHostToDevice, st)) != hipSuccess) break;
-        if ((e = hipMemsetAsync(d_err, 0, 8, st)) != hipSuccess) break;
-        if (uniq && (e = hipMemsetAsync(d_bm, 0, size_t(bitmap_words) * 4, st)) != hipSuccess) break;
-        if ((e = nts_launch_flatten(d_tok, d_pg, d_sp, d->n_req, uint32_t(T), p, d->S_src / p,
-                                    pl->d_sslot, nullptr, d_err, st)) != hipSuccess) break;
-        if ((e = nts_launch_flatten(d_tok, d_pg, d_dp, d->n_req, uint32_t(T), p, d->S_dst / p,
-                                    pl->d_dslot, d_bm, d_err, st)) != hipSuccess) break;
-        if ((e = hipMemcpyAsync(h_err, d_err, 8, hipMemcpyDeviceToHost, st)) != hipSuccess) break;
+        if ((e = hipMemcpyAsync(d_meta, h_meta, size_t(b_meta), hipMemcpyHostToDevice, st)) != hipSuccess) break;
+        if ((e = hipMemsetAsync(d_bm, 0, size_t(b_bitmap + 256), st)) != hipSuccess) break;
+        if ((e = nts_launch_flatten(reinterpret_cast<const int32_t *>(d_meta),
+                                    reinterpret_cast<const int32_t *>(d_meta + b_off), d->n_req,
+                                    uint32_t(T), p, fs, fd, d_err, st)) != hipSuccess) break;
+        if ((e = hipMemcpyAsync(const_cast<int32_t *>(h_err), d_err, 8, hipMemcpyDeviceToHost, st)) != hipSuccess) break;
         e = hipStreamSynchronize(st);
     } while (0);
-    if (e != hipSuccess || h_err[0] || h_err[1]) {
+    const int err_range = h_err[0], err_dup = h_err[1];
+    if (e != hipSuccess || err_range || err_dup) {
         (void)hipFree(blk);
         delete pl;
         if (e != hipSuccess) return fail_hip(ctx, e, "nts_plan_create");
-        if (h_err[0]) return fail(ctx, NTS_ERANGE, "a page id lies outside its pool");
+        if (err_range) return fail(ctx, NTS_ERANGE, "a page id lies outside its pool");
         return fail(ctx, NTS_EDUP, "two migrated tokens share a destination slot");
     }
     ++ctx->n_plans;
@@ -296,9 +324,18 @@ int nts_plan_free(nts_plan *pl)
     nts_ctx *ctx = pl->ctx;
     int rc = NTS_OK;
     if (pl->d_block) {
-        DeviceGuard guard(ctx->device);
-        hipError_t e = hipFree(pl->d_block);
-        if (e != hipSuccess) rc = fail_hip(ctx, e, "hipFree");
+        // the larger of (this block, the context's spare) is kept for the next plan
+        void *drop = pl->d_block;
+        if (pl->d_block_bytes > ctx->d_spare_bytes) {
+            drop = ctx->d_spare;
+            ctx->d_spare = pl->d_block;
+            ctx->d_spare_bytes = pl->d_block_bytes;
+        }
+        if (drop) {
+            DeviceGuard guard(ctx->device);
+            hipError_t e = hipFree(drop);
+            if (e != hipSuccess) rc = fail_hip(ctx, e, "hipFree");
+        }
     }
     --ctx->n_plans;
     delete pl;
@@ -344,7 +381,7 @@ static int run_range(nts_plan *pl, NtsMoveMode mode, const void *const *layer_pt
     DeviceGuard guard(ctx->device);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     // a launch covers at most chunk-limit fragments; the whole stream may need several
-    const int64_t lim = int64_t(1) << 30;
+    const int64_t lim = nts_max_frags_per_launch(pl);
     char *lin = static_cast<char *>(linear);
     for (int64_t done = 0; done < n_frag; done += lim) {
         const int64_t n = n_frag - done < lim ? n_frag - done : lim;
@@ -417,24 +454,15 @@ int nts_run_migrate(nts_plan *pl, const void *const *src_layer_ptrs, void *const
     }
 
     DeviceGuard guard(ctx->device);
-    hipStream_t a = static_cast<hipStream_t>(hip_stream), b = ctx->aux;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char *buf[2] = {static_cast<char *>(staging), static_cast<char *>(staging) + buf_stride};
-    NTS_HIP(ctx, hipEventRecord(ctx->ev_fork, a));
-    NTS_HIP(ctx, hipStreamWaitEvent(b, ctx->ev_fork, 0));
-    for (int64_t k = 0; k < pl->n_chunks; ++k) {
-        const int s = int(k & 1);
-        int64_t q0, nf;
-        chunk_range(pl, k, &q0, &nf);
-        if (k >= 2) NTS_HIP(ctx, hipStreamWaitEvent(a, ctx->ev_unpacked[s], 0));   // buffer s is free again
-        NTS_HIP(ctx, nts_launch_move(NTS_MOVE_PACK, pl, q0, nf, stab, buf[s], a));
-        NTS_HIP(ctx, hipEventRecord(ctx->ev_packed[s], a));
-        NTS_HIP(ctx, hipStreamWaitEvent(b, ctx->ev_packed[s], 0));
-        NTS_HIP(ctx, nts_launch_move(NTS_MOVE_UNPACK, pl, q0, nf, dtab, buf[s], b));
-        NTS_HIP(ctx, hipEventRecord(ctx->ev_unpacked[s], b));
+    // stage k: pack chunk k into buffer k&1 while chunk k-1 is unpacked from the other buffer
+    for (int64_t k = 0; k <= pl->n_chunks; ++k) {
+        int64_t pq = 0, pn = 0, uq = 0, un = 0;
+        if (k < pl->n_chunks) chunk_range(pl, k, &pq, &pn);
+        if (k >= 1) chunk_range(pl, k - 1, &uq, &un);
+        NTS_HIP(ctx, nts_launch_stage(pl, pq, pn, buf[k & 1], stab, uq, un, buf[(k - 1) & 1], dtab, st));
     }
-    // join: the caller's stream completes after the last unpacks
-    NTS_HIP(ctx, hipStreamWaitEvent(a, ctx->ev_unpacked[(pl->n_chunks - 1) & 1], 0));
-    if (pl->n_chunks >= 2) NTS_HIP(ctx, hipStreamWaitEvent(a, ctx->ev_unpacked[(pl->n_chunks - 2) & 1], 0));
     return NTS_OK;
 }
 

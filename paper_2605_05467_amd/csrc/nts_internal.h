@@ -12,10 +12,11 @@
 
 struct nts_ctx {
     int device = 0;
-    hipStream_t aux = nullptr;          // unpack side of the double buffer
-    hipEvent_t ev_fork = nullptr;
-    hipEvent_t ev_packed[2] = {nullptr, nullptr};
-    hipEvent_t ev_unpacked[2] = {nullptr, nullptr};
+    hipStream_t aux = nullptr;          // planning work (copies, flatten kernel)
+    void *h_pinned = nullptr;           // pinned host staging for plan metadata
+    size_t h_pinned_bytes = 0;
+    void *d_spare = nullptr;            // device block of the last freed plan, kept for reuse
+    size_t d_spare_bytes = 0;
     int n_plans = 0;
     std::string err;
 };
@@ -29,6 +30,7 @@ struct nts_plan {
     int32_t vec = 16;
     // device index arrays, one allocation
     void *d_block = nullptr;
+    size_t d_block_bytes = 0;
     int32_t *d_sslot = nullptr;
     int32_t *d_dslot = nullptr;
 };
@@ -39,33 +41,42 @@ struct NtsLayerTab {
     char *p[NTS_MAX_LAYER_PTRS];
 };
 
-// One launch of the mover covers fragments [q0, q0 + n_frag) of the stream,
-// q = (l*2+c)*T + j.
-struct NtsMoveGeom {
-    uint32_t T;         // tokens per (layer, K|V) slab
-    uint32_t lc0, j0;   // q0 split into slab index and token index
-    uint32_t n_frag;    // fragments in this launch (< 2^31)
-    uint32_t V;         // vectors per fragment
-    uint32_t lpf_log2;  // log2 of the lanes that share one fragment (<= 6)
-    uint32_t cols;      // ceil(V / lanes per fragment)
-    uint32_t tile_f;    // fragments per workgroup
-    uint64_t frag_bytes;
-};
-
-struct NtsPagedSide {
-    const int32_t *slots;  // device [T]
-    int64_t stride;        // bytes between token slots
+// One job of the mover: fragments [q0, q0 + n_frag) of the stream,
+// q = (l*2+c)*T + j, against a linear buffer that starts at fragment q0.
+// Every lane moves one vector; n_vec = n_frag * V < 2^31.
+struct NtsMoveJob {
+    const int32_t *slots;  // device [T]: slot of every migrated token on the paged side
+    char *linear;          // stream / staging side
+    int64_t stride;        // bytes between token slots of the paged side
     int64_t head_off;      // byte offset of the moved slice inside a token row
+    uint64_t T_magic;      // reciprocal of T for exact division; 0 when T == 1
+    uint64_t V_magic;      // reciprocal of V (used when V is not a power of two)
+    uint32_t T;            // tokens per (layer, K|V) slab
+    uint32_t V;            // vectors per fragment
+    int32_t v_shift;       // log2(V) if V is a power of two, else -1
+    uint32_t lc0, j0;      // q0 split into slab index and token index
+    uint32_t n_vec;        // vectors (= lanes) of this job
 };
 
 enum NtsMoveMode { NTS_MOVE_PACK = 0, NTS_MOVE_UNPACK = 1 };
 
 // nts_move.hip
+int64_t nts_max_frags_per_launch(const nts_plan *pl);
 hipError_t nts_launch_move(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int64_t n_frag,
                            const NtsLayerTab &tab, char *linear, hipStream_t st);
+// pack fragments [pack_q0, +pack_n) into pack_buf and unpack [unpack_q0, +unpack_n)
+// from unpack_buf in one launch (either count may be zero)
+hipError_t nts_launch_stage(const nts_plan *pl, int64_t pack_q0, int64_t pack_n, char *pack_buf,
+                            const NtsLayerTab &stab, int64_t unpack_q0, int64_t unpack_n,
+                            char *unpack_buf, const NtsLayerTab &dtab, hipStream_t st);
 
 // nts_plan.hip
-hipError_t nts_launch_flatten(const int32_t *d_tok_off, const int32_t *d_pg_off,
-                              const int32_t *d_pages, int n_req, uint32_t T, int p,
-                              int64_t n_pool_pages, int32_t *d_slots, uint32_t *d_bitmap,
+struct NtsFlattenSide {
+    const int32_t *pages;   // device: page ids, CSR by request
+    int32_t *slots;         // device [T]: out
+    uint32_t *bitmap;       // device, one bit per pool slot, zeroed; nullptr = no uniqueness check
+    int64_t n_pool_pages;
+};
+hipError_t nts_launch_flatten(const int32_t *d_tok_off, const int32_t *d_pg_off, int n_req, uint32_t T,
+                              int p, const NtsFlattenSide &src, const NtsFlattenSide &dst,
                               int32_t *d_err, hipStream_t st);

@@ -2,118 +2,142 @@
 // kernel copies the scattered per-page KV regions of the moved head slice into
 // a contiguous buffer; the receiver does the reverse into its own pages).
 //
-// Both are pure byte movers bound by HBM bandwidth.  Work decomposition for
-// 64-wide wavefronts: a fragment (w*D*elem_bytes contiguous bytes) is cut into
-// V vectors of `vec` bytes.  LPF = min(64, next power of two >= V) lanes share
-// one fragment, so a wavefront covers 64/LPF fragments per row and walks a
-// fragment wider than 64 vectors in `cols` column steps.  A 256-thread
-// workgroup owns tile_f = ROWS*4*(64/LPF) consecutive fragments of the stream
-// (32..64 KiB), which makes the linear side of the copy one long contiguous
-// burst per workgroup while the paged side touches whole fragments.  Each lane
-// keeps ROWS independent vector loads in flight before the first store.
+// Both are pure byte movers bound by HBM bandwidth.  Work decomposition: the
+// stream range of a launch is cut into vectors of `vec` bytes (16 when
+// alignment allows) and every lane moves exactly one vector, so a 64-wide
+// wavefront covers 1 KiB of the stream with one load and one store, whatever
+// the fragment size: a 2 KiB fragment is two wavefronts, four 256 B fragments
+// share one.  Vector index -> (fragment, offset) and fragment -> (slab, token)
+// are exact divisions by launch constants, done with a precomputed 64-bit
+// reciprocal (Lemire's method) or a shift.  Measured on MI355X this
+// one-vector-per-lane shape (4 KiB per 256-thread workgroup, hundreds of
+// thousands of workgroups) sustains more HBM bandwidth than variants that
+// keep several loads in flight per lane or that run a persistent grid.
+//
+// nts_stage_kernel is the double buffer of Sec. 3.2.2 as one launch: its
+// workgroups alternate between packing chunk k into one staging buffer and
+// unpacking chunk k-1 from the other, so the two copies overlap and
+// consecutive launches on one stream hand the buffers over.
 #include "nts_internal.h"
 
 namespace {
 
-constexpr int kRows = 8;     // fragments rows per wavefront, all in flight at once
-constexpr int kWaves = 4;    // wavefronts per workgroup
-constexpr int kThreads = 64 * kWaves;
+constexpr int kThreads = 256;
 
 template <int BYTES> struct VecOf;
 template <> struct VecOf<16> { typedef uint32_t type __attribute__((ext_vector_type(4))); };
 template <> struct VecOf<8> { typedef uint32_t type __attribute__((ext_vector_type(2))); };
 template <> struct VecOf<4> { typedef uint32_t type; };
 
+// n / d for n < 2^32, given m = floor((2^64 - 1) / d) + 1 (exact for every 32-bit n)
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint64_t m)
+{
+    return uint32_t(__umul64hi(m, uint64_t(n)));
+}
+
 template <int BYTES, bool PACK>
-__global__ __launch_bounds__(kThreads) void nts_move_kernel(NtsMoveGeom g, NtsPagedSide pg,
-                                                            NtsLayerTab tab, char *linear)
+__device__ __forceinline__ void move_vector(const NtsMoveJob &job, const NtsLayerTab &tab, uint32_t gv)
 {
     typedef typename VecOf<BYTES>::type vec_t;
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wv = threadIdx.x >> 6;
-    const uint32_t lpf = 1u << g.lpf_log2;
-    const uint32_t fpw = 64u >> g.lpf_log2;          // fragments per wavefront row
-    const uint32_t sub = lane >> g.lpf_log2;          // which fragment of the row
-    const uint32_t vl = lane & (lpf - 1u);            // vector lane inside the fragment
-
-    const uint32_t tile0 = blockIdx.x * g.tile_f;     // first fragment of this tile, launch-local
-    // slab / token of the tile's first fragment: one division per workgroup
-    const uint32_t t0 = g.j0 + tile0;
-    const uint32_t lc_t = g.lc0 + t0 / g.T;
-    const uint32_t j_t = t0 % g.T;
-
-    const char *paged[kRows];
-    char *lin[kRows];
-    bool ok[kRows];
-#pragma unroll
-    for (int r = 0; r < kRows; ++r) {
-        const uint32_t f_tile = (uint32_t(r) * kWaves + wv) * fpw + sub;   // fragment inside the tile
-        const uint32_t fl = tile0 + f_tile;
-        ok[r] = fl < g.n_frag;
-        uint32_t lc = lc_t, j = j_t + f_tile;
-        while (j >= g.T) { j -= g.T; ++lc; }
-        int64_t slot = 0;
-        const char *base = nullptr;
-        if (ok[r]) {
-            slot = pg.slots[j];
-            base = tab.p[lc];
-        }
-        paged[r] = base + slot * pg.stride + pg.head_off;
-        lin[r] = linear + uint64_t(fl) * g.frag_bytes;
+    if (gv >= job.n_vec) return;
+    uint32_t fl, v;                                   // fragment (launch-local) and vector inside it
+    if (job.v_shift >= 0) {
+        fl = gv >> job.v_shift;
+        v = gv & (job.V - 1u);
+    } else {
+        fl = fast_div(gv, job.V_magic);
+        v = gv - fl * job.V;
     }
-
-    for (uint32_t col = 0; col < g.cols; ++col) {
-        const uint32_t v = col * lpf + vl;
-        const bool inb = v < g.V;
-        const uint64_t off = uint64_t(v) * BYTES;
-        vec_t buf[kRows];
-#pragma unroll
-        for (int r = 0; r < kRows; ++r) {
-            if (ok[r] && inb) {
-                const vec_t *s = reinterpret_cast<const vec_t *>((PACK ? paged[r] : lin[r]) + off);
-                buf[r] = __builtin_nontemporal_load(s);
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < kRows; ++r) {
-            if (ok[r] && inb) {
-                vec_t *d = reinterpret_cast<vec_t *>(const_cast<char *>(PACK ? lin[r] : paged[r]) + off);
-                __builtin_nontemporal_store(buf[r], d);
-            }
-        }
+    const uint32_t t = job.j0 + fl;
+    // slabs crossed since the launch's first one (T == 1 has no 64-bit reciprocal)
+    const uint32_t ls = job.T_magic ? fast_div(t, job.T_magic) : t;
+    const uint32_t j = t - ls * job.T;
+    const int64_t slot = job.slots[j];
+    char *paged = tab.p[job.lc0 + ls] + slot * job.stride + job.head_off + uint64_t(v) * BYTES;
+    char *lin = job.linear + uint64_t(gv) * BYTES;
+    if (PACK) {
+        const vec_t x = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(paged));
+        __builtin_nontemporal_store(x, reinterpret_cast<vec_t *>(lin));
+    } else {
+        const vec_t x = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(lin));
+        __builtin_nontemporal_store(x, reinterpret_cast<vec_t *>(paged));
     }
 }
 
+template <int BYTES, bool PACK>
+__global__ __launch_bounds__(kThreads) void nts_move_kernel(NtsMoveJob job, NtsLayerTab tab)
+{
+    move_vector<BYTES, PACK>(job, tab, blockIdx.x * kThreads + threadIdx.x);
+}
+
+// Workgroups 0, 2, 4, ... pack (job a), 1, 3, 5, ... unpack (job b) while both
+// have work left; the longer job takes the remaining workgroups.
+template <int BYTES>
+__global__ __launch_bounds__(kThreads) void nts_stage_kernel(NtsMoveJob a, NtsLayerTab atab, NtsMoveJob b,
+                                                             NtsLayerTab btab, uint32_t wg_a, uint32_t wg_b)
+{
+    const uint32_t both = wg_a < wg_b ? wg_a : wg_b;
+    const uint32_t bid = blockIdx.x;
+    bool is_a;
+    uint32_t idx;
+    if (bid < 2u * both) {
+        is_a = (bid & 1u) == 0u;
+        idx = bid >> 1;
+    } else {
+        is_a = wg_a > wg_b;
+        idx = bid - both;
+    }
+    if (is_a)
+        move_vector<BYTES, true>(a, atab, idx * kThreads + threadIdx.x);
+    else
+        move_vector<BYTES, false>(b, btab, idx * kThreads + threadIdx.x);
+}
+
+uint64_t magic_of(uint32_t d) { return d > 1 ? UINT64_MAX / d + 1 : 0; }
+
 }  // namespace
+
+// Largest fragment count one launch may cover: lanes = vectors < 2^31.
+int64_t nts_max_frags_per_launch(const nts_plan *pl)
+{
+    const int64_t V = pl->frag_bytes / pl->vec;
+    int64_t n = ((int64_t(1) << 31) - kThreads) / V;
+    return n < 1 ? 1 : n;
+}
+
+void nts_make_job(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int64_t n_frag, char *linear,
+                  NtsMoveJob *job)
+{
+    const bool pack = mode == NTS_MOVE_PACK;
+    const uint32_t V = uint32_t(pl->frag_bytes / pl->vec);
+    job->slots = pack ? pl->d_sslot : pl->d_dslot;
+    job->linear = linear;
+    job->stride = pack ? pl->src_stride : pl->dst_stride;
+    job->head_off = int64_t(pack ? pl->src_head_off : pl->dst_head_off) * pl->D * pl->e;
+    job->T = uint32_t(pl->T);
+    job->T_magic = magic_of(job->T);
+    job->V = V;
+    job->V_magic = magic_of(V);
+    job->v_shift = -1;
+    if ((V & (V - 1)) == 0) {
+        int s = 0;
+        while ((1u << s) < V) ++s;
+        job->v_shift = s;
+    }
+    job->lc0 = uint32_t(q0 / pl->T);
+    job->j0 = uint32_t(q0 % pl->T);
+    job->n_vec = uint32_t(n_frag * V);
+}
 
 hipError_t nts_launch_move(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int64_t n_frag,
                            const NtsLayerTab &tab, char *linear, hipStream_t st)
 {
     if (n_frag <= 0) return hipSuccess;
-    NtsMoveGeom g;
-    g.T = uint32_t(pl->T);
-    g.lc0 = uint32_t(q0 / pl->T);
-    g.j0 = uint32_t(q0 % pl->T);
-    g.n_frag = uint32_t(n_frag);
-    g.V = uint32_t(pl->frag_bytes / pl->vec);
-    uint32_t lg = 0;
-    while (lg < 6 && (1u << lg) < g.V) ++lg;
-    g.lpf_log2 = lg;
-    const uint32_t lpf = 1u << lg;
-    g.cols = (g.V + lpf - 1) / lpf;
-    g.tile_f = uint32_t(kRows * kWaves) * (64u >> lg);
-    g.frag_bytes = uint64_t(pl->frag_bytes);
-
-    NtsPagedSide pg;
-    const bool pack = mode == NTS_MOVE_PACK;
-    pg.slots = pack ? pl->d_sslot : pl->d_dslot;
-    pg.stride = pack ? pl->src_stride : pl->dst_stride;
-    pg.head_off = int64_t(pack ? pl->src_head_off : pl->dst_head_off) * pl->D * pl->e;
-
-    const uint64_t tiles = (uint64_t(n_frag) + g.tile_f - 1) / g.tile_f;
-    const dim3 grid((unsigned)tiles), block(kThreads);
-#define NTS_LAUNCH(B, P) hipLaunchKernelGGL((nts_move_kernel<B, P>), grid, block, 0, st, g, pg, tab, linear)
-    if (pack) {
+    NtsMoveJob job;
+    nts_make_job(mode, pl, q0, n_frag, linear, &job);
+    const dim3 grid((job.n_vec + kThreads - 1) / kThreads), block(kThreads);
+#define NTS_LAUNCH(B, P) hipLaunchKernelGGL((nts_move_kernel<B, P>), grid, block, 0, st, job, tab)
+    if (mode == NTS_MOVE_PACK) {
         if (pl->vec == 16) NTS_LAUNCH(16, true);
         else if (pl->vec == 8) NTS_LAUNCH(8, true);
         else NTS_LAUNCH(4, true);
@@ -123,5 +147,21 @@ hipError_t nts_launch_move(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int
         else NTS_LAUNCH(4, false);
     }
 #undef NTS_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t nts_launch_stage(const nts_plan *pl, int64_t pack_q0, int64_t pack_n, char *pack_buf,
+                            const NtsLayerTab &stab, int64_t unpack_q0, int64_t unpack_n,
+                            char *unpack_buf, const NtsLayerTab &dtab, hipStream_t st)
+{
+    NtsMoveJob a, b;
+    nts_make_job(NTS_MOVE_PACK, pl, pack_q0, pack_n > 0 ? pack_n : 0, pack_buf, &a);
+    nts_make_job(NTS_MOVE_UNPACK, pl, unpack_q0, unpack_n > 0 ? unpack_n : 0, unpack_buf, &b);
+    const uint32_t wg_a = (a.n_vec + kThreads - 1) / kThreads, wg_b = (b.n_vec + kThreads - 1) / kThreads;
+    if (wg_a + wg_b == 0) return hipSuccess;
+    const dim3 grid(wg_a + wg_b), block(kThreads);
+    if (pl->vec == 16) hipLaunchKernelGGL((nts_stage_kernel<16>), grid, block, 0, st, a, stab, b, dtab, wg_a, wg_b);
+    else if (pl->vec == 8) hipLaunchKernelGGL((nts_stage_kernel<8>), grid, block, 0, st, a, stab, b, dtab, wg_a, wg_b);
+    else hipLaunchKernelGGL((nts_stage_kernel<4>), grid, block, 0, st, a, stab, b, dtab, wg_a, wg_b);
     return hipGetLastError();
 }
