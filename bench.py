@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV-migration hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch: route (host),
+plan (flatten + validate on the GPU), and the double-buffered pack -> staging ->
+unpack migration, with both pools already resident in HBM.  The metric is
+fragments per second (a fragment is the contiguous head slice of one
+(token, layer, K|V)).  One JSON line is printed; `roofline` describes the
+dominant kernel (the stage kernel that packs one chunk while unpacking the
+previous one) against the 8 TB/s HBM peak, `cpu_baseline` times the CPU oracle
+on a bounded sample of the same recipe.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c3|c3b|c2|c4|c3d] [--staging-mib 64]
+  python bench.py --copy-calibration      # plain copies of known size, for scaling PMC byte counters
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+WORKLOAD_DESC = {
+    "c5": "config 5: 720896 tokens / 704 requests of 16-bit Llama-8B KV (L=32,H=8,D=128), all 8 heads, "
+          "token-granular fully fragmented pages, two 92 GiB pools, 88 GiB payload",
+    "c3": "config 3 (paper's microbenchmark top point): 40960 tokens / 40 requests, 5 GiB payload, fully fragmented",
+    "c3b": "config 3b (paper's microbenchmark bottom point): 4096 tokens, 0.5 GiB payload",
+    "c3c": "config 3c: 40960 tokens, contiguous-per-request layout",
+    "c3d": "config 3d: 40960 tokens, TP1->2 / 2->4 / 4->8 slices of 4, 2, 1 heads",
+    "c2": "config 2: 16384 tokens / 16 requests, full and half slice",
+    "c4": "config 4: 40960 tokens, Zipf(1.1) request lengths, Zipf(1.1) page runs, 4 destinations",
+}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOAD_DESC))
+    ap.add_argument("--staging-mib", type=int, default=64)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true")
+    return ap.parse_args()
+
+
+class Pair:
+    """Device state of one (source, destination) pair case."""
+
+    def __init__(self, b, torch, wdev, case, src_pool=None):
+        sh = case.shape
+        self.case, self.b = case, b
+        self.src = src_pool if src_pool is not None else torch.empty(case.pool_bytes("src"), dtype=torch.uint8, device="cuda")
+        if src_pool is None:
+            wdev.fill_tensor(self.src, case.seed_src)
+        self.dst = torch.empty(case.pool_bytes("dst"), dtype=torch.uint8, device="cuda")
+        wdev.fill_tensor(self.dst, case.seed_dst)
+        self.sp = b.layer_ptrs(self.src.data_ptr(), sh.L, case.S_src * case.Hs * sh.D * sh.e)
+        self.dp = b.layer_ptrs(self.dst.data_ptr(), sh.L, case.S_dst * case.Hd * sh.D * sh.e)
+
+    def step(self, ctx, staging, staging_bytes, hip_stream, ev=None):
+        """route + plan + migrate + plan_free; returns the plan's info."""
+        c, b, sh = self.case, self.b, self.case.shape
+        so, do, w = b.nts_route(sh.H, c.Ns, c.rs, c.Nd, c.rd)
+        plan = b.nts_plan_create(ctx, L=sh.L, D=sh.D, elem_bytes=sh.e, page_size=c.p, Hs=c.Hs, Hd=c.Hd,
+                                 src_head_off=so, dst_head_off=do, w=w, S_src=c.S_src, S_dst=c.S_dst,
+                                 ctx_len=c.ctx_len, src_pages=c.src_pages, dst_pages=c.dst_pages,
+                                 staging_bytes=staging_bytes, flags=b.NTS_VALIDATE_UNIQUE_DST)
+        info = b.nts_plan_info(plan)
+        if ev is not None:
+            ev[0].record()
+        b.nts_run_migrate(plan, self.sp, self.dp, staging.data_ptr(), hip_stream)
+        if ev is not None:
+            ev[1].record()
+        b.nts_plan_free(plan)
+        return info
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per stage-kernel launch from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", f"nts_stage_kernel_{workload}_pmc.txt")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(workload: str):
+    """The oracle's unpack-after-pack, single thread, on a 16384-token instance of the same recipe
+    (about ten seconds of single-thread work)."""
+    import numpy as np
+    from oracle import kvmig as orc
+    from workload import fill_pool_u16, make_case
+    case = make_case(workload if workload in ("c5", "c3", "c2", "c4") else "c3", tokens=16384)[0]
+    sh = case.shape
+    so, do, w = orc.route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
+    src = fill_pool_u16(case.seed_src, case.pool_elems("src")).reshape(sh.L, 2, case.S_src, case.Hs, sh.D)
+    dst = fill_pool_u16(case.seed_dst, case.pool_elems("dst")).reshape(sh.L, 2, case.S_dst, case.Hd, sh.D).copy()
+    t0 = time.perf_counter()
+    sslot = orc.flatten(case.ctx_len, case.src_pages, case.p)
+    dslot = orc.flatten(case.ctx_len, case.dst_pages, case.p)
+    orc.migrate(src, dst, sslot, dslot, so, do, w)
+    dt = time.perf_counter() - t0
+    F = case.T * sh.L * 2
+    return {"value": F / dt, "unit": "fragments/s", "cores": 1, "kind": "oracle",
+            "sample": f"{case.T} tokens of the {workload} recipe ({F} fragments of {w * sh.D * sh.e} B, "
+                      f"{F * w * sh.D * sh.e / 2**30:.2f} GiB payload), flatten + pack + unpack, {dt:.2f} s"}
+
+
+def copy_calibration(torch):
+    """Plain device-to-device copies of known size (for scaling FETCH_SIZE / WRITE_SIZE)."""
+    n = 1 << 30
+    a = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+    c = torch.empty(n, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    for _ in range(8):
+        c.copy_(a)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibration": "8 copy_ launches", "bytes_read_each": n, "bytes_written_each": n}))
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); multi-GPU runs are not part of it",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2605_05467_amd import binding as b
+    from workload import device as wdev
+    from workload import make_case
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    if args.copy_calibration:
+        copy_calibration(torch)
+        return
+
+    cases = make_case(args.workload)
+    ctx = b.nts_init(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    staging_bytes = args.staging_mib << 20
+    staging = torch.empty(2 * staging_bytes, dtype=torch.uint8, device="cuda")
+    pairs = []
+    shared_src = None
+    for case in cases:                       # config 4's destinations share one source pool
+        share = shared_src if (shared_src is not None and args.workload == "c4") else None
+        pr = Pair(b, torch, wdev, case, share)
+        shared_src = pr.src
+        pairs.append(pr)
+    torch.cuda.synchronize()
+
+    def one_step(evs=None):
+        infos = []
+        for i, pr in enumerate(pairs):
+            infos.append(pr.step(ctx, staging, staging_bytes, stream, None if evs is None else evs[i]))
+        return infos
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    evs = [[[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in pairs]
+           for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        infos = one_step(evs[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = 1e3 * (t1 - t0) / args.steps
+    F = sum(i.F for i in infos)
+    X = sum(i.X for i in infos)
+    T = sum(i.T for i in infos)
+    launches = sum(i.n_chunks + 1 for i in infos)
+    kernel_ms = sum(e[0].elapsed_time(e[1]) for step in evs for e in step) / args.steps
+    # algorithmic HBM bytes: each payload byte is read from the pool and written to staging
+    # by the pack half, read from staging and written to the pool by the unpack half
+    alg_bytes_per_launch = 4.0 * X / launches
+    avg_launch_ms = kernel_ms / launches
+    achieved = alg_bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
+    traffic = measured_traffic(args.workload)
+
+    out = {
+        "metric": "hot-path items/sec on 1 MI355X (fragments/s through route+plan+pack+staging+unpack)",
+        "value": F / (ms_per_step * 1e-3),
+        "unit": "fragments/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {WORKLOAD_DESC[args.workload]}",
+                   "tokens": T, "fragments": F, "fragment_bytes": infos[0].frag_bytes,
+                   "payload_bytes": X, "staging_bytes_each": infos[0].chunk_bytes,
+                   "stage_launches_per_step": launches, "pairs": len(pairs)},
+        "tokens_per_s": T / (ms_per_step * 1e-3),
+        "payload_GBps": X / (ms_per_step * 1e-3) / 1e9,
+        "roofline": {"bound": "hbm", "kernel": "nts_stage_kernel<16> (pack chunk k || unpack chunk k-1)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": alg_bytes_per_launch,
+                     "avg_launch_ms": avg_launch_ms, "launches_per_step": launches,
+                     "timing": "HIP events on the launch stream around each step's stage launches "
+                               "(includes the gaps between back-to-back launches)"},
+    }
+    del pairs, staging
+    b.nts_free(ctx)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

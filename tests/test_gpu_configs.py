@@ -1,0 +1,185 @@
+"""GPU parity at the benchmark configurations, in the launch configuration
+bench.py times (route + plan + double-buffered migrate, 64 MiB staging).
+
+Configuration 2 is compared whole.  The larger ones are compared (a) whole
+layers at a time against the oracle run on those layers (layers are independent
+in the oracle's loops), (b) on randomly sampled single elements the oracle
+locates one by one, with the value taken from the stateless fill's closed form,
+and (c) through properties that hold at any size: the source pool is unchanged
+and exactly payload-many words of the destination differ from its sentinel fill.
+"""
+import numpy as np
+import pytest
+
+from oracle import kvmig as orc
+from workload import SplitMix64, fill_words, make_case
+
+pytestmark = pytest.mark.gpu
+STAGING = 64 << 20
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2605_05467_amd import binding as b
+    from workload import device as wdev
+    ctx = b.nts_init(0)
+    staging = torch.empty(2 * STAGING, dtype=torch.uint8, device="cuda")
+    yield torch, b, wdev, ctx, staging
+    del staging
+    torch.cuda.empty_cache()
+    b.nts_free(ctx)
+
+
+def migrate_on_gpu(env, case, src_d=None):
+    from gpu_util import device_pool, make_plan, slab_bytes
+    torch, b, wdev, ctx, staging = env
+    sh = case.shape
+    if src_d is None:
+        src_d = device_pool(case, "src")
+    dst_d = device_pool(case, "dst")
+    sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+    dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
+    plan = make_plan(b, ctx, case, staging_bytes=STAGING)
+    try:
+        info = b.nts_plan_info(plan)
+        s, d = b.nts_plan_slots(plan)
+        b.nts_run_migrate(plan, sp, dp, staging.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+    finally:
+        b.nts_plan_free(plan)
+    return src_d, dst_d, info, s, d
+
+
+def check_properties(env, case, src_d, dst_d, info):
+    torch, b, wdev, ctx, _ = env
+    assert wdev.count_mismatch(src_d, case.seed_src) == 0, "source pool changed"
+    changed = wdev.count_mismatch(dst_d, case.seed_dst)
+    assert changed == info.X // 8, (changed, info.X // 8)
+
+
+def check_layers(env, case, dst_d, layers, sslot, dslot):
+    from gpu_util import host_layers
+    torch = env[0]
+    sh = case.shape
+    so, do, w = orc.route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
+    layer_bytes = 2 * case.S_dst * case.Hd * sh.D * sh.e
+    for l in layers:
+        print(f"  {case.name}: oracle on layer {l}", flush=True)
+        src_h = host_layers(case, "src", [l])
+        want = host_layers(case, "dst", [l]).copy()
+        orc.migrate(src_h, want, sslot, dslot, so, do, w)
+        got = dst_d[l * layer_bytes:(l + 1) * layer_bytes].cpu().numpy()
+        assert got.tobytes() == want.tobytes(), (case.name, l)
+        del src_h, want, got
+
+
+def _fill_elem(seed, lin):
+    word = int(fill_words(seed, lin // 4, 1)[0])
+    return (word >> (16 * (lin % 4))) & 0xFFFF
+
+
+def check_samples(env, case, dst_d, sslot, dslot, n=400, seed=99):
+    torch = env[0]
+    sh = case.shape
+    assert sh.e == 2
+    so, do, w = orc.route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
+    rng = SplitMix64(seed)
+    j_of = {int(s): j for j, s in enumerate(dslot)}
+    used = np.zeros(case.S_dst, bool)
+    used[dslot] = True
+    free = np.nonzero(~used)[0]
+    coords = []
+    for k in range(n):
+        l = int(rng.integers(0, sh.L - 1, 1)[0])
+        c = int(rng.integers(0, 1, 1)[0])
+        if k % 3 != 2 or len(free) == 0:
+            slot = int(dslot[int(rng.integers(0, len(dslot) - 1, 1)[0])])
+        else:
+            slot = int(free[int(rng.integers(0, len(free) - 1, 1)[0])])
+        h = int(rng.integers(0, case.Hd - 1, 1)[0])
+        x = int(rng.integers(0, sh.D - 1, 1)[0])
+        coords.append((l, c, slot, h, x))
+    lin_dst = np.array([((((l * 2 + c) * case.S_dst + s) * case.Hd + h) * sh.D + x) for l, c, s, h, x in coords], np.int64)
+    got = dst_d.view(torch.int16)[torch.from_numpy(lin_dst).cuda()].cpu().numpy().view(np.uint16)
+    for k, (l, c, slot, h, x) in enumerate(coords):
+        srcpos = orc.migrated_element_source(j_of, sslot, slot, h, so, do, w)
+        if srcpos is None:
+            want = _fill_elem(case.seed_dst, int(lin_dst[k]))
+        else:
+            s_slot, s_head = srcpos
+            want = _fill_elem(case.seed_src, (((l * 2 + c) * case.S_src + s_slot) * case.Hs + s_head) * sh.D + x)
+        assert int(got[k]) == want, (case.name, coords[k])
+
+
+def test_config2_whole_outputs(env):
+    from gpu_util import host_layers, oracle_slots
+    for case in make_case("c2"):
+        print(f"  {case.name}", flush=True)
+        sh = case.shape
+        src_d, dst_d, info, s, d = migrate_on_gpu(env, case)
+        es, ed = oracle_slots(case)
+        assert np.array_equal(s, es) and np.array_equal(d, ed)
+        assert info.F == case.T * sh.L * 2
+        check_properties(env, case, src_d, dst_d, info)
+        so, do, w = orc.route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
+        src_h = host_layers(case, "src", range(sh.L))
+        want = host_layers(case, "dst", range(sh.L)).copy()
+        orc.migrate(src_h, want, es, ed, so, do, w)
+        assert dst_d.cpu().numpy().tobytes() == want.tobytes()
+        del src_h, want, src_d, dst_d
+
+
+@pytest.mark.parametrize("name", ["c3", "c3b", "c3c", "c3d"])
+def test_config3_headline_and_companions(env, name):
+    from gpu_util import oracle_slots
+    for case in make_case(name):
+        src_d, dst_d, info, s, d = migrate_on_gpu(env, case)
+        es, ed = oracle_slots(case)
+        assert np.array_equal(s, es) and np.array_equal(d, ed)
+        if name == "c3":
+            assert info.X == 5 * 2 ** 30 and info.F == 2621440 and info.n_chunks == 80
+        if name == "c3b":
+            assert info.X == 2 ** 29
+        check_properties(env, case, src_d, dst_d, info)
+        check_layers(env, case, dst_d, [0, 31] if name == "c3" else [17], es, ed)
+        check_samples(env, case, dst_d, es, ed)
+        del src_d, dst_d
+
+
+def test_config4_skewed_four_destinations(env):
+    from gpu_util import oracle_slots
+    cases = make_case("c4")
+    src_d = None
+    total_F = 0
+    for case in cases:
+        src_d, dst_d, info, s, d = migrate_on_gpu(env, case, src_d)
+        es, ed = oracle_slots(case)
+        assert np.array_equal(s, es) and np.array_equal(d, ed)
+        total_F += info.F
+        check_properties(env, case, src_d, dst_d, info)
+        check_layers(env, case, dst_d, [5], es, ed)
+        check_samples(env, case, dst_d, es, ed, n=200)
+        del dst_d
+    assert total_F == 2621440
+
+
+def test_config5_roofline_size(env):
+    """Two 92 GiB pools, 88 GiB payload: one whole layer, sampled elements, and
+    the any-size properties."""
+    from gpu_util import oracle_slots
+    torch = env[0]
+    free, total = torch.cuda.mem_get_info()
+    case = make_case("c5")[0]
+    need = case.pool_bytes("src") + case.pool_bytes("dst") + (1 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of free HBM, {free >> 30} GiB available")
+    src_d, dst_d, info, s, d = migrate_on_gpu(env, case)
+    es, ed = oracle_slots(case)
+    assert np.array_equal(s, es) and np.array_equal(d, ed)
+    assert info.F == 46137344 and info.X == 88 * 2 ** 30
+    check_properties(env, case, src_d, dst_d, info)
+    check_samples(env, case, dst_d, es, ed, n=600)
+    check_layers(env, case, dst_d, [19], es, ed)
+    del src_d, dst_d
+    torch.cuda.empty_cache()
