@@ -48,6 +48,10 @@ def parse_args():
     ap.add_argument("--staging-mib", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true")
+    ap.add_argument("--strategies", action="store_true",
+                    help="latency of four migration strategies on the paper's payload sizes, one JSON line each")
+    ap.add_argument("--full-memcpy", action="store_true",
+                    help="with --strategies: run the per-fragment memcpy baseline at 40960 tokens too (tens of seconds)")
     return ap.parse_args()
 
 
@@ -130,6 +134,65 @@ def copy_calibration(torch):
     print(json.dumps({"calibration": "8 copy_ launches", "bytes_read_each": n, "bytes_written_each": n}))
 
 
+def strategies(args, torch, b, wdev, make_case):
+    """The paper's three-strategy comparison (Sec. 3.2.2, Fig. "KV-Migration Latency
+    Comparison") on one MI355X, wire left out, plus the pool-to-pool kernel:
+    per-fragment memcpy, aggregate-then-scatter without pipelining, the
+    double-buffered pipeline, and the direct kernel; fragmented and contiguous layouts."""
+    ctx = b.nts_init(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    staging_bytes = args.staging_mib << 20
+    staging = torch.empty(2 * staging_bytes, dtype=torch.uint8, device="cuda")
+
+    def timed(fn, iters):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(iters):
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - t0)
+        return 1e3 * sorted(ts)[len(ts) // 2]
+
+    for tokens in (4096, 40960):
+        for layout, name in (("fragmented", "c3"), ("contiguous", "c3c")):
+            case = make_case(name, tokens=tokens)[0]
+            pr = Pair(b, torch, wdev, case)
+            sh = case.shape
+            so, do, w = b.nts_route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
+            plan = b.nts_plan_create(ctx, L=sh.L, D=sh.D, elem_bytes=sh.e, page_size=case.p, Hs=case.Hs, Hd=case.Hd,
+                                     src_head_off=so, dst_head_off=do, w=w, S_src=case.S_src, S_dst=case.S_dst,
+                                     ctx_len=case.ctx_len, src_pages=case.src_pages, dst_pages=case.dst_pages,
+                                     staging_bytes=staging_bytes, flags=b.NTS_VALIDATE_UNIQUE_DST)
+            info = b.nts_plan_info(plan)
+            whole = torch.empty(info.X, dtype=torch.uint8, device="cuda")
+            res = {"strategies": True, "tokens": tokens, "layout": layout, "payload_bytes": info.X,
+                   "fragments": info.F, "unit": "ms (median, host clock around enqueue + synchronise)"}
+            n_copies = [0]
+
+            def memcpy_run():
+                n_copies[0] = b.nts_run_memcpy_baseline(plan, pr.sp, pr.dp, layout == "contiguous", stream)
+
+            if tokens <= 4096 or args.full_memcpy or layout == "contiguous":
+                res["memcpy_per_region"] = timed(memcpy_run, 1 if tokens > 4096 and layout == "fragmented" else 3)
+                res["memcpy_calls"] = n_copies[0]
+
+            def aggregate_run():
+                b.nts_run_pack(plan, pr.sp, whole.data_ptr(), stream)
+                b.nts_run_unpack(plan, whole.data_ptr(), pr.dp, stream)
+
+            res["aggregate_unpipelined"] = timed(aggregate_run, 10)
+            res["pipelined_double_buffer"] = timed(
+                lambda: b.nts_run_migrate(plan, pr.sp, pr.dp, staging.data_ptr(), stream), 10)
+            res["direct_pool_to_pool"] = timed(lambda: b.nts_run_migrate_direct(plan, pr.sp, pr.dp, stream), 10)
+            b.nts_plan_free(plan)
+            del whole, pr
+            print(json.dumps(res), flush=True)
+    del staging
+    b.nts_free(ctx)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -147,6 +210,9 @@ def main():
     torch.cuda.set_device(0)
     if args.copy_calibration:
         copy_calibration(torch)
+        return
+    if args.strategies:
+        strategies(args, torch, b, wdev, make_case)
         return
 
     cases = make_case(args.workload)

@@ -189,6 +189,30 @@ int nts_run_unpack_chunk(nts_plan *plan, const void *chunk_in, int64_t k,
 int nts_run_migrate(nts_plan *plan, const void *const *src_layer_ptrs,
                     void *const *dst_layer_ptrs, void *staging, void *hip_stream);
 
+/*
+ * The same migration as one kernel from pool to pool, never forming the stream:
+ * dst[l][c][dslot[j]][dst_head_off+h][x] = src[l][c][sslot[j]][src_head_off+h][x].
+ * Within one address space this is what the paper's "sends it directly to the
+ * other GPUs" (Sec. 3.2.2) becomes when the destination pool is mapped into the
+ * sender; it moves each payload byte once instead of twice.  NTS_EALIAS if the
+ * pools overlap.
+ */
+int nts_run_migrate_direct(nts_plan *plan, const void *const *src_layer_ptrs,
+                           void *const *dst_layer_ptrs, void *hip_stream);
+
+/*
+ * Comparison baseline of the paper's microbenchmark (Sec. 3.2.2, Fig.
+ * "KV-Migration Latency Comparison"): one asynchronous device-to-device memcpy
+ * per fragmented region, issued by the host.  With merge_runs != 0, tokens that
+ * sit in neighbouring slots on both sides and whose fragment is a whole row are
+ * copied as one region (the "contiguous per-request layout" case).  The first
+ * call on a plan copies the slot lists to the host (synchronises once).
+ * *n_copies (may be NULL) receives the number of memcpy calls issued.
+ */
+int nts_run_memcpy_baseline(nts_plan *plan, const void *const *src_layer_ptrs,
+                            void *const *dst_layer_ptrs, int merge_runs, void *hip_stream,
+                            int64_t *n_copies);
+
 #ifdef __cplusplus
 }
 #endif

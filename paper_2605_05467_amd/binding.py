@@ -41,7 +41,7 @@ EXPORTS = (
     "nts_init", "nts_free", "nts_last_error", "nts_strerror", "nts_route",
     "nts_plan_create", "nts_plan_free", "nts_plan_info", "nts_plan_slots",
     "nts_run_pack", "nts_run_pack_chunk", "nts_run_unpack", "nts_run_unpack_chunk",
-    "nts_run_migrate",
+    "nts_run_migrate", "nts_run_migrate_direct", "nts_run_memcpy_baseline",
 )
 
 
@@ -83,6 +83,8 @@ _lib.nts_run_pack_chunk.argtypes = [_vp, _vp, _i64, _vp, _vp]
 _lib.nts_run_unpack.argtypes = [_vp, _vp, _vp, _vp]
 _lib.nts_run_unpack_chunk.argtypes = [_vp, _vp, _i64, _vp, _vp]
 _lib.nts_run_migrate.argtypes = [_vp, _vp, _vp, _vp, _vp]
+_lib.nts_run_migrate_direct.argtypes = [_vp, _vp, _vp, _vp]
+_lib.nts_run_memcpy_baseline.argtypes = [_vp, _vp, _vp, _i, _vp, ctypes.POINTER(_i64)]
 for _name in EXPORTS:
     if _name not in ("nts_last_error", "nts_strerror"):
         getattr(_lib, _name).restype = _i
@@ -202,3 +204,15 @@ def nts_run_unpack_chunk(plan: int, chunk_in: int, k: int, dst_layer_ptrs, hip_s
 
 def nts_run_migrate(plan: int, src_layer_ptrs, dst_layer_ptrs, staging: int, hip_stream: int = 0) -> None:
     _run(_lib.nts_run_migrate(plan, _tab(src_layer_ptrs), _tab(dst_layer_ptrs), staging, hip_stream))
+
+
+def nts_run_migrate_direct(plan: int, src_layer_ptrs, dst_layer_ptrs, hip_stream: int = 0) -> None:
+    _run(_lib.nts_run_migrate_direct(plan, _tab(src_layer_ptrs), _tab(dst_layer_ptrs), hip_stream))
+
+
+def nts_run_memcpy_baseline(plan: int, src_layer_ptrs, dst_layer_ptrs, merge_runs: bool = False,
+                            hip_stream: int = 0) -> int:
+    n = _i64(0)
+    _run(_lib.nts_run_memcpy_baseline(plan, _tab(src_layer_ptrs), _tab(dst_layer_ptrs),
+                                      1 if merge_runs else 0, hip_stream, ctypes.byref(n)))
+    return n.value

@@ -426,6 +426,23 @@ int nts_run_unpack_chunk(nts_plan *pl, const void *chunk_in, int64_t k, void *co
     return run_range(pl, NTS_MOVE_UNPACK, dst_layer_ptrs, q0, n, const_cast<void *>(chunk_in), hip_stream);
 }
 
+static int check_pools(nts_plan *pl, const void *const *src_layer_ptrs, void *const *dst_layer_ptrs,
+                       NtsLayerTab &stab, NtsLayerTab &dtab)
+{
+    nts_ctx *ctx = pl->ctx;
+    if (!src_layer_ptrs || !dst_layer_ptrs) return fail(ctx, NTS_EINVAL, "null layer pointer table");
+    if (fill_tab(pl, src_layer_ptrs, stab) != NTS_OK ||
+        fill_tab(pl, reinterpret_cast<const void *const *>(dst_layer_ptrs), dtab) != NTS_OK)
+        return fail(ctx, NTS_EINVAL, "null or misaligned layer pointer");
+    const int64_t src_span = pl->S_src * pl->src_stride, dst_span = pl->S_dst * pl->dst_stride;
+    const int n = 2 * pl->L;
+    for (int i = 0; i < n; ++i)
+        for (int k = 0; k < n; ++k)
+            if (overlaps(stab.p[i], src_span, dtab.p[k], dst_span))
+                return fail(ctx, NTS_EALIAS, "source and destination pools overlap");
+    return NTS_OK;
+}
+
 int nts_run_migrate(nts_plan *pl, const void *const *src_layer_ptrs, void *const *dst_layer_ptrs,
                     void *staging, void *hip_stream)
 {
@@ -433,25 +450,18 @@ int nts_run_migrate(nts_plan *pl, const void *const *src_layer_ptrs, void *const
     nts_ctx *ctx = pl->ctx;
     if (!src_layer_ptrs || !dst_layer_ptrs) return fail(ctx, NTS_EINVAL, "null layer pointer table");
     if (pl->F == 0) return NTS_OK;
+    NtsLayerTab stab, dtab;
+    const int rc = check_pools(pl, src_layer_ptrs, dst_layer_ptrs, stab, dtab);
+    if (rc != NTS_OK) return rc;
     if (!staging) return fail(ctx, NTS_EINVAL, "null staging area");
     if (reinterpret_cast<uintptr_t>(staging) % uintptr_t(pl->vec)) return fail(ctx, NTS_EINVAL, "staging area misaligned");
-    NtsLayerTab stab, dtab;
-    if (fill_tab(pl, src_layer_ptrs, stab) != NTS_OK || fill_tab(pl, reinterpret_cast<const void *const *>(dst_layer_ptrs), dtab) != NTS_OK)
-        return fail(ctx, NTS_EINVAL, "null or misaligned layer pointer");
-    // byte ranges: source layers vs destination layers vs staging
-    const int64_t src_span = pl->S_src * pl->src_stride, dst_span = pl->S_dst * pl->dst_stride;
     // chunk_bytes is a multiple of the vector width, so the second buffer stays aligned
     const int64_t buf_stride = pl->chunk_bytes;
     const char *stg = static_cast<const char *>(staging);
-    const int64_t stg_span = 2 * pl->chunk_bytes;
-    const int n = 2 * pl->L;
-    for (int i = 0; i < n; ++i) {
-        if (overlaps(stab.p[i], src_span, stg, stg_span) || overlaps(dtab.p[i], dst_span, stg, stg_span))
+    const int64_t src_span = pl->S_src * pl->src_stride, dst_span = pl->S_dst * pl->dst_stride;
+    for (int i = 0; i < 2 * pl->L; ++i)
+        if (overlaps(stab.p[i], src_span, stg, 2 * pl->chunk_bytes) || overlaps(dtab.p[i], dst_span, stg, 2 * pl->chunk_bytes))
             return fail(ctx, NTS_EALIAS, "staging area overlaps a pool");
-        for (int k = 0; k < n; ++k)
-            if (overlaps(stab.p[i], src_span, dtab.p[k], dst_span))
-                return fail(ctx, NTS_EALIAS, "source and destination pools overlap");
-    }
 
     DeviceGuard guard(ctx->device);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -463,6 +473,72 @@ int nts_run_migrate(nts_plan *pl, const void *const *src_layer_ptrs, void *const
         if (k >= 1) chunk_range(pl, k - 1, &uq, &un);
         NTS_HIP(ctx, nts_launch_stage(pl, pq, pn, buf[k & 1], stab, uq, un, buf[(k - 1) & 1], dtab, st));
     }
+    return NTS_OK;
+}
+
+int nts_run_migrate_direct(nts_plan *pl, const void *const *src_layer_ptrs, void *const *dst_layer_ptrs,
+                           void *hip_stream)
+{
+    if (!pl) return NTS_EINVAL;
+    nts_ctx *ctx = pl->ctx;
+    if (!src_layer_ptrs || !dst_layer_ptrs) return fail(ctx, NTS_EINVAL, "null layer pointer table");
+    if (pl->F == 0) return NTS_OK;
+    NtsLayerTab stab, dtab;
+    const int rc = check_pools(pl, src_layer_ptrs, dst_layer_ptrs, stab, dtab);
+    if (rc != NTS_OK) return rc;
+    DeviceGuard guard(ctx->device);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int64_t lim = nts_max_frags_per_launch(pl);
+    for (int64_t done = 0; done < pl->F; done += lim) {
+        const int64_t n = pl->F - done < lim ? pl->F - done : lim;
+        NTS_HIP(ctx, nts_launch_direct(pl, done, n, stab, dtab, st));
+    }
+    return NTS_OK;
+}
+
+int nts_run_memcpy_baseline(nts_plan *pl, const void *const *src_layer_ptrs, void *const *dst_layer_ptrs,
+                            int merge_runs, void *hip_stream, int64_t *n_copies)
+{
+    if (!pl) return NTS_EINVAL;
+    nts_ctx *ctx = pl->ctx;
+    if (n_copies) *n_copies = 0;
+    if (!src_layer_ptrs || !dst_layer_ptrs) return fail(ctx, NTS_EINVAL, "null layer pointer table");
+    if (pl->F == 0) return NTS_OK;
+    NtsLayerTab stab, dtab;
+    const int rc = check_pools(pl, src_layer_ptrs, dst_layer_ptrs, stab, dtab);
+    if (rc != NTS_OK) return rc;
+    DeviceGuard guard(ctx->device);
+    if (pl->h_sslot.empty()) {
+        try {
+            pl->h_sslot.resize(size_t(pl->T));
+            pl->h_dslot.resize(size_t(pl->T));
+        } catch (...) {
+            return fail(ctx, NTS_ENOMEM, "host allocation failed");
+        }
+        NTS_HIP(ctx, hipMemcpy(pl->h_sslot.data(), pl->d_sslot, size_t(pl->T) * 4, hipMemcpyDeviceToHost));
+        NTS_HIP(ctx, hipMemcpy(pl->h_dslot.data(), pl->d_dslot, size_t(pl->T) * 4, hipMemcpyDeviceToHost));
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int64_t so = int64_t(pl->src_head_off) * pl->D * pl->e, dof = int64_t(pl->dst_head_off) * pl->D * pl->e;
+    // a run of tokens in neighbouring slots on both sides is one region when a fragment is a whole row
+    const bool can_merge = merge_runs && pl->frag_bytes == pl->src_stride && pl->frag_bytes == pl->dst_stride;
+    int64_t copies = 0;
+    for (int lc = 0; lc < 2 * pl->L; ++lc) {
+        int64_t j = 0;
+        while (j < pl->T) {
+            int64_t len = 1;
+            if (can_merge)
+                while (j + len < pl->T && pl->h_sslot[j + len] == pl->h_sslot[j] + len &&
+                       pl->h_dslot[j + len] == pl->h_dslot[j] + len)
+                    ++len;
+            const char *s = stab.p[lc] + int64_t(pl->h_sslot[j]) * pl->src_stride + so;
+            char *d = dtab.p[lc] + int64_t(pl->h_dslot[j]) * pl->dst_stride + dof;
+            NTS_HIP(ctx, hipMemcpyAsync(d, s, size_t(len * pl->frag_bytes), hipMemcpyDeviceToDevice, st));
+            ++copies;
+            j += len;
+        }
+    }
+    if (n_copies) *n_copies = copies;
     return NTS_OK;
 }
 

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include <string>
+#include <vector>
 
 #include "nitsum_kvmig.h"
 
@@ -33,6 +34,8 @@ struct nts_plan {
     size_t d_block_bytes = 0;
     int32_t *d_sslot = nullptr;
     int32_t *d_dslot = nullptr;
+    // host copies of the slot lists, fetched on first use by the per-fragment memcpy baseline
+    std::vector<int32_t> h_sslot, h_dslot;
 };
 
 // Base pointers of the 2L per-(layer, K|V) arrays of one pool; passed by value
@@ -69,6 +72,9 @@ hipError_t nts_launch_move(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int
 hipError_t nts_launch_stage(const nts_plan *pl, int64_t pack_q0, int64_t pack_n, char *pack_buf,
                             const NtsLayerTab &stab, int64_t unpack_q0, int64_t unpack_n,
                             char *unpack_buf, const NtsLayerTab &dtab, hipStream_t st);
+// pool-to-pool move of fragments [q0, q0 + n_frag) with no stream in between
+hipError_t nts_launch_direct(const nts_plan *pl, int64_t q0, int64_t n_frag, const NtsLayerTab &stab,
+                             const NtsLayerTab &dtab, hipStream_t st);
 
 // nts_plan.hip
 struct NtsFlattenSide {

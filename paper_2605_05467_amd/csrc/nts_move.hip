@@ -93,6 +93,35 @@ __global__ __launch_bounds__(kThreads) void nts_stage_kernel(NtsMoveJob a, NtsLa
         move_vector<BYTES, false>(b, btab, idx * kThreads + threadIdx.x);
 }
 
+// Pool-to-pool variant: the same lane decomposition with a paged address on both
+// sides (job a describes the source side, job b the destination side; their
+// linear pointers are unused).  This is what a kernel that stores straight into
+// a peer-mapped destination pool would look like within one address space.
+template <int BYTES>
+__global__ __launch_bounds__(kThreads) void nts_direct_kernel(NtsMoveJob a, NtsLayerTab atab, NtsMoveJob b,
+                                                              NtsLayerTab btab)
+{
+    typedef typename VecOf<BYTES>::type vec_t;
+    const uint32_t gv = blockIdx.x * kThreads + threadIdx.x;
+    if (gv >= a.n_vec) return;
+    uint32_t fl, v;
+    if (a.v_shift >= 0) {
+        fl = gv >> a.v_shift;
+        v = gv & (a.V - 1u);
+    } else {
+        fl = fast_div(gv, a.V_magic);
+        v = gv - fl * a.V;
+    }
+    const uint32_t t = a.j0 + fl;
+    const uint32_t ls = a.T_magic ? fast_div(t, a.T_magic) : t;
+    const uint32_t j = t - ls * a.T;
+    const int64_t ss = a.slots[j], ds = b.slots[j];
+    const char *src = atab.p[a.lc0 + ls] + ss * a.stride + a.head_off + uint64_t(v) * BYTES;
+    char *dst = btab.p[a.lc0 + ls] + ds * b.stride + b.head_off + uint64_t(v) * BYTES;
+    const vec_t x = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(src));
+    __builtin_nontemporal_store(x, reinterpret_cast<vec_t *>(dst));
+}
+
 uint64_t magic_of(uint32_t d) { return d > 1 ? UINT64_MAX / d + 1 : 0; }
 
 }  // namespace
@@ -163,5 +192,19 @@ hipError_t nts_launch_stage(const nts_plan *pl, int64_t pack_q0, int64_t pack_n,
     if (pl->vec == 16) hipLaunchKernelGGL((nts_stage_kernel<16>), grid, block, 0, st, a, stab, b, dtab, wg_a, wg_b);
     else if (pl->vec == 8) hipLaunchKernelGGL((nts_stage_kernel<8>), grid, block, 0, st, a, stab, b, dtab, wg_a, wg_b);
     else hipLaunchKernelGGL((nts_stage_kernel<4>), grid, block, 0, st, a, stab, b, dtab, wg_a, wg_b);
+    return hipGetLastError();
+}
+
+hipError_t nts_launch_direct(const nts_plan *pl, int64_t q0, int64_t n_frag, const NtsLayerTab &stab,
+                             const NtsLayerTab &dtab, hipStream_t st)
+{
+    if (n_frag <= 0) return hipSuccess;
+    NtsMoveJob a, b;
+    nts_make_job(NTS_MOVE_PACK, pl, q0, n_frag, nullptr, &a);
+    nts_make_job(NTS_MOVE_UNPACK, pl, q0, n_frag, nullptr, &b);
+    const dim3 grid((a.n_vec + kThreads - 1) / kThreads), block(kThreads);
+    if (pl->vec == 16) hipLaunchKernelGGL((nts_direct_kernel<16>), grid, block, 0, st, a, stab, b, dtab);
+    else if (pl->vec == 8) hipLaunchKernelGGL((nts_direct_kernel<8>), grid, block, 0, st, a, stab, b, dtab);
+    else hipLaunchKernelGGL((nts_direct_kernel<4>), grid, block, 0, st, a, stab, b, dtab);
     return hipGetLastError();
 }

@@ -280,3 +280,67 @@ def test_error_paths_and_empty_plans(b, ctx, torch):
     assert ei.value.status == b.NTS_EINVAL
     b.nts_plan_free(plan)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("idx", [0, 1, 3, 4])
+def test_direct_and_memcpy_baseline_match_oracle(b, ctx, torch, idx):
+    """The pool-to-pool kernel and the per-fragment memcpy baseline produce the
+    oracle's direct migration (config 1 shapes, whole pools)."""
+    from gpu_util import device_pool, host_layers, make_plan, oracle_slots, slab_bytes, to_host
+    case = make_case("c1")[idx]
+    sh = case.shape
+    so, do, w = orc.route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
+    src_h = host_layers(case, "src", range(sh.L))
+    want = host_layers(case, "dst", range(sh.L)).copy()
+    sslot, dslot = oracle_slots(case)
+    orc.migrate_direct(src_h, want, sslot, dslot, so, do, w)
+    src_d = device_pool(case, "src")
+    sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+    plan = make_plan(b, ctx, case)
+    try:
+        st = torch.cuda.current_stream().cuda_stream
+        dst_d = device_pool(case, "dst")
+        b.nts_run_migrate_direct(plan, sp, b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst")), st)
+        torch.cuda.synchronize()
+        assert to_host(dst_d).tobytes() == want.tobytes()
+        for merge in (False, True):
+            dst_d = device_pool(case, "dst")
+            n = b.nts_run_memcpy_baseline(plan, sp, b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst")),
+                                          merge, st)
+            torch.cuda.synchronize()
+            assert to_host(dst_d).tobytes() == want.tobytes()
+            assert n == case.T * sh.L * 2          # fully fragmented: nothing to merge
+        with pytest.raises(b.NtsError) as ei:
+            b.nts_run_migrate_direct(plan, sp, sp, st)
+        assert ei.value.status in (b.NTS_EALIAS, b.NTS_EINVAL)
+    finally:
+        b.nts_plan_free(plan)
+
+
+def test_memcpy_baseline_merges_contiguous_runs(b, ctx, torch):
+    from gpu_util import device_pool, host_layers, make_plan, oracle_slots, slab_bytes, to_host
+    rng = SplitMix64(31)
+    ctx_len = np.array([40, 1, 25], np.int32)
+    S = 128
+    case = PairCase(name="runs", shape=ModelShape(L=2, H=8, D=128, e=2), p=1, Ns=1, rs=0, Nd=1, rd=0,
+                    S_src=S, S_dst=S, ctx_len=ctx_len,
+                    src_pages=random_pages(rng, ctx_len, 1, S, "contiguous"),
+                    dst_pages=random_pages(rng, ctx_len, 1, S, "contiguous"), seed_src=7, seed_dst=8)
+    sh = case.shape
+    src_h = host_layers(case, "src", range(sh.L))
+    want = host_layers(case, "dst", range(sh.L)).copy()
+    sslot, dslot = oracle_slots(case)
+    orc.migrate_direct(src_h, want, sslot, dslot, 0, 0, 8)
+    src_d, dst_d = device_pool(case, "src"), device_pool(case, "dst")
+    plan = make_plan(b, ctx, case)
+    try:
+        n = b.nts_run_memcpy_baseline(plan, b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src")),
+                                      b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst")), True,
+                                      torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+    finally:
+        b.nts_plan_free(plan)
+    assert to_host(dst_d).tobytes() == want.tobytes()
+    # runs break where either side's slots stop being consecutive: count them on the host
+    runs = 1 + int(np.sum((np.diff(sslot) != 1) | (np.diff(dslot) != 1)))
+    assert n == runs * sh.L * 2 and runs <= 5
