@@ -36,7 +36,21 @@ WORKLOAD_DESC = {
     "c3d": "config 3d: 40960 tokens, TP1->2 / 2->4 / 4->8 slices of 4, 2, 1 heads",
     "c2": "config 2: 16384 tokens / 16 requests, full and half slice",
     "c4": "config 4: 40960 tokens, Zipf(1.1) request lengths, Zipf(1.1) page runs, 4 destinations",
+    "c3_p16": "config 3 with 16-token pages (fragmented at page granularity)",
+    "c3_fp8": "config 3 with 1-byte KV elements (1 KiB fragments, 2.5 GiB payload)",
+    "c3_70b": "16384 tokens of a 70B-class geometry (L=80, 8 KV heads, D=128, 16-bit): 5 GiB payload",
 }
+
+# other KV geometries: (base recipe, model shape, page size, tokens)
+def _variant_cases(name):
+    from workload import make_case, ModelShape, M8B
+    if name == "c3_p16":
+        return make_case("c3", shape=M8B, p=16)
+    if name == "c3_fp8":
+        return make_case("c3", shape=ModelShape(L=32, H=8, D=128, e=1))
+    if name == "c3_70b":
+        return make_case("c3", shape=ModelShape(L=80, H=8, D=128, e=2), tokens=16384)
+    return make_case(name)
 
 
 def parse_args():
@@ -215,7 +229,7 @@ def main():
         strategies(args, torch, b, wdev, make_case)
         return
 
-    cases = make_case(args.workload)
+    cases = _variant_cases(args.workload)
     ctx = b.nts_init(0)
     stream = torch.cuda.current_stream().cuda_stream
     staging_bytes = args.staging_mib << 20

@@ -60,6 +60,14 @@ int fill_tab(const nts_plan *pl, const void *const *ptrs, NtsLayerTab &tab)
     return NTS_OK;
 }
 
+// Remember that `pl` has work on `st`: nts_plan_free orders that work before any reuse of the plan's block.
+void note_stream(nts_plan *pl, hipStream_t st)
+{
+    for (hipStream_t s : pl->used_streams)
+        if (s == st) return;
+    pl->used_streams.push_back(st);
+}
+
 bool overlaps(const char *a, int64_t na, const char *b, int64_t nb)
 {
     return a < b + nb && b < a + na;
@@ -100,6 +108,7 @@ int nts_init(int device_id, nts_ctx **out)
     DeviceGuard guard(device_id);
     hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_retire, hipEventDisableTiming);
     if (e != hipSuccess) {
         nts_free(ctx);
         (void)hipGetLastError();
@@ -118,6 +127,7 @@ int nts_free(nts_ctx *ctx)
         (void)hipStreamSynchronize(ctx->aux);
         (void)hipStreamDestroy(ctx->aux);
     }
+    if (ctx->ev_retire) (void)hipEventDestroy(ctx->ev_retire);
     if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
     if (ctx->d_spare) (void)hipFree(ctx->d_spare);
     delete ctx;
@@ -324,6 +334,19 @@ int nts_plan_free(nts_plan *pl)
     nts_ctx *ctx = pl->ctx;
     int rc = NTS_OK;
     if (pl->d_block) {
+        DeviceGuard guard(ctx->device);
+        // Kernels of this plan may still be running and they index through d_block.  All later
+        // writes to a recycled block happen on ctx->aux (nts_plan_create), so make that stream
+        // wait for every stream the plan has launched on before the block changes hands.
+        hipError_t e = hipSuccess;
+        for (hipStream_t s : pl->used_streams) {
+            if ((e = hipEventRecord(ctx->ev_retire, s)) != hipSuccess) break;
+            if ((e = hipStreamWaitEvent(ctx->aux, ctx->ev_retire, 0)) != hipSuccess) break;
+        }
+        if (e != hipSuccess) {                       // cannot order it: wait for the device instead
+            (void)hipGetLastError();
+            (void)hipDeviceSynchronize();
+        }
         // the larger of (this block, the context's spare) is kept for the next plan
         void *drop = pl->d_block;
         if (pl->d_block_bytes > ctx->d_spare_bytes) {
@@ -332,8 +355,9 @@ int nts_plan_free(nts_plan *pl)
             ctx->d_spare_bytes = pl->d_block_bytes;
         }
         if (drop) {
-            DeviceGuard guard(ctx->device);
-            hipError_t e = hipFree(drop);
+            // a block handed back to the allocator must be idle: aux is ordered after its users
+            e = hipStreamSynchronize(ctx->aux);
+            if (e == hipSuccess) e = hipFree(drop);
             if (e != hipSuccess) rc = fail_hip(ctx, e, "hipFree");
         }
     }
@@ -380,6 +404,7 @@ static int run_range(nts_plan *pl, NtsMoveMode mode, const void *const *layer_pt
     if (fill_tab(pl, layer_ptrs, tab) != NTS_OK) return fail(ctx, NTS_EINVAL, "null or misaligned layer pointer");
     DeviceGuard guard(ctx->device);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    note_stream(pl, st);
     // a launch covers at most chunk-limit fragments; the whole stream may need several
     const int64_t lim = nts_max_frags_per_launch(pl);
     char *lin = static_cast<char *>(linear);
@@ -465,6 +490,7 @@ int nts_run_migrate(nts_plan *pl, const void *const *src_layer_ptrs, void *const
 
     DeviceGuard guard(ctx->device);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    note_stream(pl, st);
     char *buf[2] = {static_cast<char *>(staging), static_cast<char *>(staging) + buf_stride};
     // stage k: pack chunk k into buffer k&1 while chunk k-1 is unpacked from the other buffer
     for (int64_t k = 0; k <= pl->n_chunks; ++k) {
@@ -488,6 +514,7 @@ int nts_run_migrate_direct(nts_plan *pl, const void *const *src_layer_ptrs, void
     if (rc != NTS_OK) return rc;
     DeviceGuard guard(ctx->device);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    note_stream(pl, st);
     const int64_t lim = nts_max_frags_per_launch(pl);
     for (int64_t done = 0; done < pl->F; done += lim) {
         const int64_t n = pl->F - done < lim ? pl->F - done : lim;

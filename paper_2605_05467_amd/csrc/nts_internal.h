@@ -18,6 +18,7 @@ struct nts_ctx {
     size_t h_pinned_bytes = 0;
     void *d_spare = nullptr;            // device block of the last freed plan, kept for reuse
     size_t d_spare_bytes = 0;
+    hipEvent_t ev_retire = nullptr;     // orders a retired plan's pending kernels before `aux` work
     int n_plans = 0;
     std::string err;
 };
@@ -36,6 +37,8 @@ struct nts_plan {
     int32_t *d_dslot = nullptr;
     // host copies of the slot lists, fetched on first use by the per-fragment memcpy baseline
     std::vector<int32_t> h_sslot, h_dslot;
+    // streams this plan's run calls have launched on; their pending work reads d_block
+    std::vector<hipStream_t> used_streams;
 };
 
 // Base pointers of the 2L per-(layer, K|V) arrays of one pool; passed by value

@@ -22,7 +22,7 @@
 
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 64;   // one wavefront per workgroup measured best (finer retirement)
 
 template <int BYTES> struct VecOf;
 template <> struct VecOf<16> { typedef uint32_t type __attribute__((ext_vector_type(4))); };

@@ -183,3 +183,54 @@ def test_config5_roofline_size(env):
     check_layers(env, case, dst_d, [19], es, ed)
     del src_d, dst_d
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("variant", ["p16", "fp8", "70b"])
+def test_other_kv_geometries_at_size(env, variant):
+    """16-token pages, 1-byte elements and an 80-layer model at 8192 tokens."""
+    from gpu_util import oracle_slots
+    from workload import M8B, ModelShape
+    if variant == "p16":
+        case = make_case("c3", shape=M8B, p=16, tokens=8192)[0]
+    elif variant == "fp8":
+        case = make_case("c3", shape=ModelShape(L=32, H=8, D=128, e=1), tokens=8192)[0]
+    else:
+        case = make_case("c3", shape=ModelShape(L=80, H=8, D=128, e=2), tokens=8192)[0]
+    src_d, dst_d, info, s, d = migrate_on_gpu(env, case)
+    es, ed = oracle_slots(case)
+    assert np.array_equal(s, es) and np.array_equal(d, ed)
+    check_properties(env, case, src_d, dst_d, info)
+    check_layers(env, case, dst_d, [case.shape.L - 1], es, ed)
+    if case.shape.e == 2:
+        check_samples(env, case, dst_d, es, ed, n=200)
+
+
+def test_back_to_back_pairs_without_synchronising(env):
+    """Plans of different sizes created, run and freed back to back with no
+    synchronisation in between (what bench.py does for configuration 4): a freed
+    plan's device block is recycled by the next plan only after the kernels
+    that still read it have finished."""
+    from gpu_util import device_pool, make_plan, oracle_slots, slab_bytes
+    torch, b, wdev, ctx, staging = env
+    cases = make_case("c4", tokens=8192)
+    assert len({c.T for c in cases}) > 1
+    sh = cases[0].shape
+    src_d = device_pool(cases[0], "src")
+    sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(cases[0], "src"))
+    dsts = [device_pool(c, "dst") for c in cases]
+    stream = torch.cuda.current_stream().cuda_stream
+    infos = []
+    for _ in range(3):
+        infos = []
+        for case, dst_d in zip(cases, dsts):
+            plan = make_plan(b, ctx, case, staging_bytes=STAGING)
+            infos.append(b.nts_plan_info(plan))
+            b.nts_run_migrate(plan, sp, b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst")),
+                              staging.data_ptr(), stream)
+            b.nts_plan_free(plan)
+    torch.cuda.synchronize()
+    for case, dst_d, info in zip(cases, dsts, infos):
+        es, ed = oracle_slots(case)
+        check_properties(env, case, src_d, dst_d, info)
+        check_layers(env, case, dst_d, [11], es, ed)
+        check_samples(env, case, dst_d, es, ed, n=100)

@@ -256,6 +256,10 @@ _TRANSITIONS = {
 }
 
 
+def _round_up(x: int, m: int) -> int:
+    return -(-x // m) * m
+
+
 def _pair(name, shape, p, tr, S_src, S_dst, ctx_len, layout, rng, seed, notes="") -> PairCase:
     Ns, rs, Nd, rd = _TRANSITIONS[tr]
     src_pages = random_pages(rng, ctx_len, p, S_src // p, layout)
@@ -286,14 +290,14 @@ def make_case(name: str, shape: ModelShape = M8B, p: int = 1, tokens: int | None
         rng = SplitMix64(0)
         T = tokens or 160
         ctx = lengths_uniform(rng, 8, 1, 40, T)
-        S = max(256, (T * 8) // 5)
+        S = _round_up(max(256, (T * 8) // 5), p)
         return [_pair(f"c1_{tr}", shape, p, tr, S, S, ctx, "fragmented", rng, 0)
                 for tr in ("1to2", "1to1", "2to4", "4to8", "8to4", "4to2", "2to1")]
     if name == "c2":
         rng = SplitMix64(1)
         T = tokens or 16384
         ctx = lengths_uniform(rng, 16, 512, 1536, T)
-        S = (T * 5) // 4
+        S = _round_up((T * 5) // 4, p)
         return [_pair(f"c2_{tr}", shape, p, tr, S, S, ctx, "fragmented", rng, 1)
                 for tr in ("1to1", "1to2")]
     if name in ("c3", "c3b", "c3c", "c3d"):
@@ -301,7 +305,7 @@ def make_case(name: str, shape: ModelShape = M8B, p: int = 1, tokens: int | None
         T = tokens or (4096 if name == "c3b" else 40960)
         n_req = max(1, T // 1024)
         ctx = lengths_uniform(rng, n_req, 512, 1536, T)
-        S = (T * 6) // 5
+        S = _round_up((T * 6) // 5, p)
         if name == "c3c":
             return [_pair("c3c_1to1", shape, p, "1to1", S, S, ctx, "contiguous", rng, 2)]
         if name == "c3d":
@@ -313,7 +317,7 @@ def make_case(name: str, shape: ModelShape = M8B, p: int = 1, tokens: int | None
         T = tokens or 40960
         n_req = 512 if T >= 4096 else max(4, T // 8)
         ctx = lengths_zipf(rng, n_req, 1.1, T)
-        S = (T * 6) // 5
+        S = _round_up((T * 6) // 5, p)
         src_pages_all = slots_zipf_runs(rng, ctx, p, S // p)
         # destinations: requests dealt out so that token shares follow Zipf(1.1) over 4 ranks
         share = 1.0 / np.arange(1, 5, dtype=np.float64) ** 1.1
@@ -345,6 +349,6 @@ def make_case(name: str, shape: ModelShape = M8B, p: int = 1, tokens: int | None
         T = tokens or 720896
         n_req = max(1, T // 1024)
         ctx = lengths_uniform(rng, n_req, 512, 1536, T)
-        S = (T * 23) // 22
+        S = _round_up((T * 23) // 22, p)
         return [_pair("c5_1to1", shape, p, "1to1", S, S, ctx, "fragmented", rng, 4)]
     raise ValueError(f"unknown configuration {name!r}")
