@@ -64,6 +64,8 @@ def parse_args():
     ap.add_argument("--copy-calibration", action="store_true")
     ap.add_argument("--strategies", action="store_true",
                     help="latency of four migration strategies on the paper's payload sizes, one JSON line each")
+    ap.add_argument("--no-memcpy", action="store_true",
+                    help="with --strategies: skip the per-region memcpy baseline (keeps a profiler trace short)")
     ap.add_argument("--full-memcpy", action="store_true",
                     help="with --strategies: run the per-fragment memcpy baseline at 40960 tokens too (tens of seconds)")
     return ap.parse_args()
@@ -188,7 +190,7 @@ def strategies(args, torch, b, wdev, make_case):
             def memcpy_run():
                 n_copies[0] = b.nts_run_memcpy_baseline(plan, pr.sp, pr.dp, layout == "contiguous", stream)
 
-            if tokens <= 4096 or args.full_memcpy or layout == "contiguous":
+            if not args.no_memcpy and (tokens <= 4096 or args.full_memcpy or layout == "contiguous"):
                 res["memcpy_per_region"] = timed(memcpy_run, 1 if tokens > 4096 and layout == "fragmented" else 3)
                 res["memcpy_calls"] = n_copies[0]
 

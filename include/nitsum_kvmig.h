@@ -20,7 +20,7 @@
  *   - run calls only enqueue work on the given HIP stream (a hipStream_t passed
  *     as void*, NULL = the default stream), allocate nothing and never block
  *     the host.  A context and its plans may be used by one host thread at a time.
- *     A context keeps a pinned host buffer and one spare device block between
+ *     A context keeps a pinned host buffer and up to three spare device blocks between
  *     plans so that planning in a steady loop allocates nothing.
  *
  * Data layout (the paper fixes none; this is the layout of this library)

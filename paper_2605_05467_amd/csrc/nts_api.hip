@@ -108,7 +108,8 @@ int nts_init(int device_id, nts_ctx **out)
     DeviceGuard guard(device_id);
     hipError_t e = guard.ok ? hipSuccess : hipErrorInvalidDevice;
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_retire, hipEventDisableTiming);
+    for (int i = 0; i < nts_ctx::kSpares && e == hipSuccess; ++i)
+        e = hipEventCreateWithFlags(&ctx->spare[i].ev, hipEventDisableTiming);
     if (e != hipSuccess) {
         nts_free(ctx);
         (void)hipGetLastError();
@@ -127,9 +128,12 @@ int nts_free(nts_ctx *ctx)
         (void)hipStreamSynchronize(ctx->aux);
         (void)hipStreamDestroy(ctx->aux);
     }
-    if (ctx->ev_retire) (void)hipEventDestroy(ctx->ev_retire);
+    (void)hipDeviceSynchronize();
+    for (int i = 0; i < nts_ctx::kSpares; ++i) {
+        if (ctx->spare[i].ptr) (void)hipFree(ctx->spare[i].ptr);
+        if (ctx->spare[i].ev) (void)hipEventDestroy(ctx->spare[i].ev);
+    }
     if (ctx->h_pinned) (void)hipHostFree(ctx->h_pinned);
-    if (ctx->d_spare) (void)hipFree(ctx->d_spare);
     delete ctx;
     return NTS_OK;
 }
@@ -267,11 +271,37 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     }
     char *blk = nullptr;
     size_t blk_bytes = 0;
-    if (ctx->d_spare && ctx->d_spare_bytes >= size_t(total)) {      // reuse the last freed plan's block
-        blk = static_cast<char *>(ctx->d_spare);
-        blk_bytes = ctx->d_spare_bytes;
-        ctx->d_spare = nullptr;
-        ctx->d_spare_bytes = 0;
+    int take = -1;                                   // oldest spare block that is large enough
+    for (int i = 0; i < nts_ctx::kSpares; ++i)
+        if (ctx->spare[i].ptr && ctx->spare[i].bytes >= size_t(total) &&
+            (take < 0 || ctx->spare[i].age < ctx->spare[take].age))
+            take = i;
+    if (take >= 0 && ctx->spare[take].pending) {
+        // still read by its previous owner's kernels?  Then rather start another block while a
+        // slot is free, so that a loop of plans rotates through idle blocks and never waits.
+        if (hipEventQuery(ctx->spare[take].ev) == hipSuccess) {
+            ctx->spare[take].pending = false;
+        } else {
+            (void)hipGetLastError();
+            for (int i = 0; i < nts_ctx::kSpares; ++i)
+                if (!ctx->spare[i].ptr) {
+                    take = -1;
+                    break;
+                }
+        }
+    }
+    if (take >= 0) {
+        nts_ctx::Spare &sp = ctx->spare[take];
+        // kernels of the plan that owned the block must finish before it is overwritten
+        if (sp.pending && (e = hipStreamWaitEvent(ctx->aux, sp.ev, 0)) != hipSuccess) {
+            delete pl;
+            return fail_hip(ctx, e, "hipStreamWaitEvent");
+        }
+        blk = static_cast<char *>(sp.ptr);
+        blk_bytes = sp.bytes;
+        sp.ptr = nullptr;
+        sp.bytes = 0;
+        sp.pending = false;
     } else {
         e = hipMalloc(reinterpret_cast<void **>(&blk), size_t(total));
         if (e != hipSuccess) {
@@ -335,31 +365,45 @@ int nts_plan_free(nts_plan *pl)
     int rc = NTS_OK;
     if (pl->d_block) {
         DeviceGuard guard(ctx->device);
-        // Kernels of this plan may still be running and they index through d_block.  All later
-        // writes to a recycled block happen on ctx->aux (nts_plan_create), so make that stream
-        // wait for every stream the plan has launched on before the block changes hands.
+        // Kernels of this plan may still be running and they index through d_block.  The block
+        // goes to a spare slot together with an event recorded behind that work; the plan that
+        // reuses it makes its own writes wait for the event.
+        int slot = -1;
+        for (int i = 0; i < nts_ctx::kSpares && slot < 0; ++i)
+            if (!ctx->spare[i].ptr) slot = i;
+        if (slot < 0) {                              // all slots taken: give the smallest block back
+            slot = 0;
+            for (int i = 1; i < nts_ctx::kSpares; ++i)
+                if (ctx->spare[i].bytes < ctx->spare[slot].bytes) slot = i;
+            if (ctx->spare[slot].bytes >= pl->d_block_bytes) slot = -1;   // this one is the smallest
+        }
         hipError_t e = hipSuccess;
-        for (hipStream_t s : pl->used_streams) {
-            if ((e = hipEventRecord(ctx->ev_retire, s)) != hipSuccess) break;
-            if ((e = hipStreamWaitEvent(ctx->aux, ctx->ev_retire, 0)) != hipSuccess) break;
+        if (slot >= 0 && pl->used_streams.size() <= 1) {
+            nts_ctx::Spare &sp = ctx->spare[slot];
+            if (sp.ptr) {                            // evict: the block must be idle before hipFree
+                if (sp.pending) e = hipEventSynchronize(sp.ev);
+                if (e == hipSuccess) e = hipFree(sp.ptr);
+                sp.ptr = nullptr;
+                sp.bytes = 0;
+                sp.pending = false;
+            }
+            if (e == hipSuccess && !pl->used_streams.empty()) {
+                e = hipEventRecord(sp.ev, pl->used_streams[0]);
+                sp.pending = e == hipSuccess;
+            }
+            if (e == hipSuccess) {
+                sp.ptr = pl->d_block;
+                sp.bytes = pl->d_block_bytes;
+                sp.age = ++ctx->free_count;
+                pl->d_block = nullptr;
+            }
         }
-        if (e != hipSuccess) {                       // cannot order it: wait for the device instead
+        if (pl->d_block) {                           // not kept (or several streams): wait, then free
             (void)hipGetLastError();
-            (void)hipDeviceSynchronize();
+            for (hipStream_t s : pl->used_streams) (void)hipStreamSynchronize(s);
+            e = hipFree(pl->d_block);
         }
-        // the larger of (this block, the context's spare) is kept for the next plan
-        void *drop = pl->d_block;
-        if (pl->d_block_bytes > ctx->d_spare_bytes) {
-            drop = ctx->d_spare;
-            ctx->d_spare = pl->d_block;
-            ctx->d_spare_bytes = pl->d_block_bytes;
-        }
-        if (drop) {
-            // a block handed back to the allocator must be idle: aux is ordered after its users
-            e = hipStreamSynchronize(ctx->aux);
-            if (e == hipSuccess) e = hipFree(drop);
-            if (e != hipSuccess) rc = fail_hip(ctx, e, "hipFree");
-        }
+        if (e != hipSuccess) rc = fail_hip(ctx, e, "nts_plan_free");
     }
     --ctx->n_plans;
     delete pl;

@@ -16,9 +16,19 @@ struct nts_ctx {
     hipStream_t aux = nullptr;          // planning work (copies, flatten kernel)
     void *h_pinned = nullptr;           // pinned host staging for plan metadata
     size_t h_pinned_bytes = 0;
-    void *d_spare = nullptr;            // device block of the last freed plan, kept for reuse
-    size_t d_spare_bytes = 0;
-    hipEvent_t ev_retire = nullptr;     // orders a retired plan's pending kernels before `aux` work
+    // Device blocks of freed plans, kept for reuse.  A block may still be read by kernels of
+    // the plan that owned it; `ev` (recorded when it was freed) orders them before reuse.
+    // Blocks are reused oldest first, so in a steady loop the wait is already over.
+    struct Spare {
+        void *ptr = nullptr;
+        size_t bytes = 0;
+        hipEvent_t ev = nullptr;
+        bool pending = false;           // ev was recorded and has not been waited on by `aux`
+        uint64_t age = 0;               // order of freeing
+    };
+    static constexpr int kSpares = 3;
+    Spare spare[kSpares];
+    uint64_t free_count = 0;
     int n_plans = 0;
     std::string err;
 };
