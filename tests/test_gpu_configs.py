@@ -181,6 +181,37 @@ def test_config5_roofline_size(env):
     check_properties(env, case, src_d, dst_d, info)
     check_samples(env, case, dst_d, es, ed, n=600)
     check_layers(env, case, dst_d, [19], es, ed)
+    # the pool-to-pool kernel at this size needs three launches (fewer than 2^31 lanes each)
+    from gpu_util import slab_bytes
+    from workload import device as wdev
+    b, ctx = env[1], env[3]
+    wdev.fill_tensor(dst_d, case.seed_dst)
+    sh = case.shape
+    sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+    dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
+    from gpu_util import make_plan
+    plan = make_plan(b, ctx, case, staging_bytes=STAGING)
+    try:
+        b.nts_run_migrate_direct(plan, sp, dp, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        check_properties(env, case, src_d, dst_d, info)
+        check_samples(env, case, dst_d, es, ed, n=600, seed=7)
+        check_layers(env, case, dst_d, [31], es, ed)
+        # one chunk of the stream, far into it, against the oracle's pack of that layer
+        k = info.n_chunks - 3
+        buf = torch.empty(info.chunk_bytes, dtype=torch.uint8, device="cuda")
+        b.nts_run_pack_chunk(plan, sp, k, buf.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        q0 = k * info.chunk_frags
+        lc, j0 = divmod(q0, info.T)
+        assert j0 + info.chunk_frags <= info.T            # the chunk lies inside one (layer, K|V) slab
+        from gpu_util import host_layers
+        so, do, w = orc.route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
+        src_l = host_layers(case, "src", [lc // 2])
+        want = orc.pack(src_l, es[j0:j0 + info.chunk_frags], so, w)[0, lc % 2]
+        assert buf.cpu().numpy().tobytes() == want.tobytes()
+    finally:
+        b.nts_plan_free(plan)
     del src_d, dst_d
     torch.cuda.empty_cache()
 
