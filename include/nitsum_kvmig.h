@@ -213,6 +213,42 @@ int nts_run_memcpy_baseline(nts_plan *plan, const void *const *src_layer_ptrs,
                             void *const *dst_layer_ptrs, int merge_runs, void *hip_stream,
                             int64_t *n_copies);
 
+/* ------------------------------------------------------------------------
+ * TP-shard-selecting linear layer (paper Sec. 3.2.1, "Zero-Overhead TP Weight
+ * Switching"): each GPU keeps one full copy of a weight matrix W[n_out][n_in]
+ * (row-major, 16-bit) and rank `rank` of a group at TP level `tp` computes with
+ * its 1/tp of it, selected at execution time; nothing is copied or reloaded
+ * when tp changes.
+ *   NTS_SPLIT_OUT  Y[M][n_out/tp] = X[M][n_in]    . W[rank*n_out/tp : +n_out/tp, :]^T
+ *   NTS_SPLIT_IN   Y[M][n_out]    = X[M][n_in/tp] . W[:, rank*n_in/tp : +n_in/tp]^T
+ *                  (a partial sum; the all-reduce over ranks is the caller's)
+ * X, W, Y: device, bfloat16; products are accumulated in fp32 and Y is rounded
+ * to nearest even once.  ldx / ldw / ldy: row strides in elements, 0 = dense
+ * (n_in or n_in/tp for X, n_in for W, the output width for Y); all strides
+ * multiples of 8, all pointers 16-byte aligned.  The shard's reduction length
+ * (n_in or n_in/tp) must be a multiple of 64.  workspace: device scratch of at
+ * least nts_shard_linear_workspace() bytes (may be NULL when that is 0); it
+ * holds fp32 partial sums when the reduction is split over workgroups, which
+ * are then added in a fixed order, so results are reproducible.
+ * Errors: NTS_EINVAL (null pointer, bad split / rank / sizes / alignment,
+ * workspace too small), NTS_EHIP.
+ */
+enum { NTS_SPLIT_OUT = 0, NTS_SPLIT_IN = 1 };
+
+typedef struct nts_linear_desc {
+    int32_t M;      /* rows of X: tokens in the batch, >= 1 */
+    int32_t n_out;  /* rows of the FULL weight matrix */
+    int32_t n_in;   /* columns of the FULL weight matrix */
+    int32_t tp;     /* TP level N */
+    int32_t rank;   /* this GPU's rank in its TP group */
+    int32_t split;  /* NTS_SPLIT_OUT or NTS_SPLIT_IN */
+    int64_t ldx, ldw, ldy;
+} nts_linear_desc;
+
+int nts_shard_linear_workspace(const nts_linear_desc *d, size_t *bytes);
+int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, const void *W_full,
+                     void *Y, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -42,7 +42,9 @@ EXPORTS = (
     "nts_plan_create", "nts_plan_free", "nts_plan_info", "nts_plan_slots",
     "nts_run_pack", "nts_run_pack_chunk", "nts_run_unpack", "nts_run_unpack_chunk",
     "nts_run_migrate", "nts_run_migrate_direct", "nts_run_memcpy_baseline",
+    "nts_shard_linear", "nts_shard_linear_workspace",
 )
+NTS_SPLIT_OUT, NTS_SPLIT_IN = 0, 1
 
 
 class nts_desc(ctypes.Structure):
@@ -54,6 +56,14 @@ class nts_desc(ctypes.Structure):
         ("ctx_len", ctypes.c_void_p), ("src_pages", ctypes.c_void_p), ("dst_pages", ctypes.c_void_p),
         ("src_token_stride", ctypes.c_int64), ("dst_token_stride", ctypes.c_int64),
         ("staging_bytes", ctypes.c_int64), ("flags", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+    ]
+
+
+class nts_linear_desc(ctypes.Structure):
+    _fields_ = [
+        ("M", ctypes.c_int32), ("n_out", ctypes.c_int32), ("n_in", ctypes.c_int32), ("tp", ctypes.c_int32),
+        ("rank", ctypes.c_int32), ("split", ctypes.c_int32),
+        ("ldx", ctypes.c_int64), ("ldw", ctypes.c_int64), ("ldy", ctypes.c_int64),
     ]
 
 
@@ -85,6 +95,8 @@ _lib.nts_run_unpack_chunk.argtypes = [_vp, _vp, _i64, _vp, _vp]
 _lib.nts_run_migrate.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.nts_run_migrate_direct.argtypes = [_vp, _vp, _vp, _vp]
 _lib.nts_run_memcpy_baseline.argtypes = [_vp, _vp, _vp, _i, _vp, ctypes.POINTER(_i64)]
+_lib.nts_shard_linear_workspace.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(ctypes.c_size_t)]
+_lib.nts_shard_linear.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 for _name in EXPORTS:
     if _name not in ("nts_last_error", "nts_strerror"):
         getattr(_lib, _name).restype = _i
@@ -216,3 +228,24 @@ def nts_run_memcpy_baseline(plan: int, src_layer_ptrs, dst_layer_ptrs, merge_run
     _run(_lib.nts_run_memcpy_baseline(plan, _tab(src_layer_ptrs), _tab(dst_layer_ptrs),
                                       1 if merge_runs else 0, hip_stream, ctypes.byref(n)))
     return n.value
+
+
+def _linear_desc(M, n_out, n_in, tp, rank, split, ldx=0, ldw=0, ldy=0) -> nts_linear_desc:
+    return nts_linear_desc(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=rank, split=split, ldx=ldx, ldw=ldw, ldy=ldy)
+
+
+def nts_shard_linear_workspace(*, M: int, n_out: int, n_in: int, tp: int, rank: int, split: int,
+                               ldx: int = 0, ldw: int = 0, ldy: int = 0) -> int:
+    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy)
+    n = ctypes.c_size_t(0)
+    st = _lib.nts_shard_linear_workspace(ctypes.byref(d), ctypes.byref(n))
+    if st != NTS_OK:
+        raise NtsError(st, "nts_shard_linear_workspace")
+    return n.value
+
+
+def nts_shard_linear(ctx: int, X: int, W_full: int, Y: int, *, M: int, n_out: int, n_in: int, tp: int,
+                     rank: int, split: int, ldx: int = 0, ldw: int = 0, ldy: int = 0,
+                     workspace: int = 0, workspace_bytes: int = 0, hip_stream: int = 0) -> None:
+    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy)
+    _check(_lib.nts_shard_linear(ctx, ctypes.byref(d), X, W_full, Y, workspace, workspace_bytes, hip_stream), ctx)

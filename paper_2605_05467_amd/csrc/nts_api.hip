@@ -613,4 +613,71 @@ int nts_run_memcpy_baseline(nts_plan *pl, const void *const *src_layer_ptrs, voi
     return NTS_OK;
 }
 
+namespace {
+struct LinearGeom {
+    int M, Nn, K;
+    int64_t ldx, lda, ldy, a_off;   // a_off: element offset of the shard inside W
+    int splits;                      // skinny path: K splits (0 on the tiled path)
+};
+
+int linear_geom(const nts_linear_desc *d, LinearGeom *g)
+{
+    if (!d || d->M < 1 || d->n_out < 1 || d->n_in < 1 || d->tp < 1 || d->rank < 0 || d->rank >= d->tp) return NTS_EINVAL;
+    if (d->split != NTS_SPLIT_OUT && d->split != NTS_SPLIT_IN) return NTS_EINVAL;
+    const int64_t ldw = d->ldw ? d->ldw : d->n_in;
+    if (ldw < d->n_in) return NTS_EINVAL;
+    if (d->split == NTS_SPLIT_OUT) {
+        if (d->n_out % d->tp) return NTS_EINVAL;
+        g->Nn = d->n_out / d->tp;
+        g->K = d->n_in;
+        g->a_off = int64_t(d->rank) * g->Nn * ldw;
+    } else {
+        if (d->n_in % d->tp) return NTS_EINVAL;
+        g->Nn = d->n_out;
+        g->K = d->n_in / d->tp;
+        g->a_off = int64_t(d->rank) * g->K;
+    }
+    g->M = d->M;
+    g->lda = ldw;
+    g->ldx = d->ldx ? d->ldx : g->K;
+    g->ldy = d->ldy ? d->ldy : g->Nn;
+    if (g->K % 64 || g->ldx < g->K || g->ldy < g->Nn) return NTS_EINVAL;
+    if (g->ldx % 8 || g->lda % 8 || g->ldy % 8 || g->a_off % 8) return NTS_EINVAL;
+    g->splits = g->M <= 64 ? nts_linear_skinny_splits(g->Nn, g->K) : 0;
+    return NTS_OK;
+}
+}  // namespace
+
+int nts_shard_linear_workspace(const nts_linear_desc *d, size_t *bytes)
+{
+    LinearGeom g;
+    if (!bytes || linear_geom(d, &g) != NTS_OK) return NTS_EINVAL;
+    *bytes = g.splits > 1 ? size_t(g.splits) * g.M * g.Nn * sizeof(float) : 0;
+    return NTS_OK;
+}
+
+int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, const void *W_full, void *Y,
+                     void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!ctx) return NTS_EINVAL;
+    LinearGeom g;
+    if (linear_geom(d, &g) != NTS_OK) return fail(ctx, NTS_EINVAL, "bad linear-layer descriptor");
+    if (!X || !W_full || !Y) return fail(ctx, NTS_EINVAL, "null operand");
+    if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W_full) | reinterpret_cast<uintptr_t>(Y)) % 16)
+        return fail(ctx, NTS_EINVAL, "operands must be 16-byte aligned");
+    const size_t need = g.splits > 1 ? size_t(g.splits) * g.M * g.Nn * sizeof(float) : 0;
+    if (need && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16))
+        return fail(ctx, NTS_EINVAL, "workspace missing, misaligned or too small");
+    DeviceGuard guard(ctx->device);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const uint16_t *A = static_cast<const uint16_t *>(W_full) + g.a_off;
+    if (g.M <= 64) {
+        NTS_HIP(ctx, nts_launch_linear_skinny(static_cast<const uint16_t *>(X), g.ldx, A, g.lda,
+                                              static_cast<uint16_t *>(Y), g.ldy, static_cast<float *>(workspace),
+                                              g.splits, g.M, g.Nn, g.K, st));
+        return NTS_OK;
+    }
+    return fail(ctx, NTS_EINVAL, "batches above 64 rows are not supported yet");
+}
+
 }  // extern "C"

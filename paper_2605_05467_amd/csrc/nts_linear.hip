@@ -1,0 +1,165 @@
+// TP-shard-selecting linear layer (paper Sec. 3.2.1: one full weight copy per
+// GPU, the rank's 1/N shard picked at execution time).  The shard is never
+// copied: a column-parallel shard is a row block of the [n_out][n_in] weight,
+// a row-parallel shard a column block, so both are a base offset plus the full
+// matrix's row stride, and every kernel here computes
+//     Y[M][Nn] = X[M][K] . A[Nn][K]^T        (A = the shard, row stride lda)
+// with bf16 inputs, fp32 accumulation on the matrix cores and bf16 output.
+//
+// Small batches (M <= 64, decode): the weight shard is read exactly once and
+// the kernel is bound by HBM bandwidth.  A wavefront owns 16 weight rows and a
+// K slice; weight rows are the A operand of v_mfma_f32_16x16x32_bf16 and go
+// from global memory straight into registers (no LDS: no reuse), the batch is
+// the B operand and sits in LDS.  Lane (i = lane%16, g = lane/16) of the MFMA
+// holds 8 consecutive k of row i; which k they are is free as long as both
+// operands agree, so inside a 64-wide k block lane group g takes k = 16g+8s+e
+// for the block's two MFMAs s = 0,1: each lane then reads 32 contiguous bytes
+// and the four lanes of a row cover one full 128-byte line.
+#include "nts_internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kSkinnyWaves = 4;            // 16 weight rows each
+constexpr int kSkinnyChunk = 256;          // k per LDS refill: four 64-wide blocks
+constexpr int kLdsRow = kSkinnyChunk * 2 + 16;   // bytes per batch row in LDS (padded)
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return uint16_t((u >> 16) | 0x40u);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return uint16_t(u >> 16);
+}
+
+// MT = number of 16-row batch tiles (M <= 16*MT)
+template <int MT>
+__global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
+    const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
+    uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ part, int M, int Nn, int K,
+    int chunks_per_split)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char xs[16 * MT * kLdsRow];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int n0 = (blockIdx.x * kSkinnyWaves + wv) * 16;          // first weight row of this wavefront
+    const int split = blockIdx.y;
+    const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
+    const int c_lo = split * chunks_per_split;
+    const int c_hi = min(n_chunks, c_lo + chunks_per_split);
+    const int row = min(n0 + i, Nn - 1);                            // clamp: rows past the end are computed, not stored
+    const unsigned char *arow = reinterpret_cast<const unsigned char *>(A + int64_t(row) * lda);
+
+    f32x4 acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int c = c_lo; c < c_hi; ++c) {
+        const int k0 = c * kSkinnyChunk;
+        const int nblk = min(4, (K - k0) / 64);                     // K is a multiple of 64
+        // weight loads first: 2 x 16 B per 64-wide block, all in flight while X is staged
+        u32x4 wreg[8];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            if (b < nblk) {
+                const unsigned char *p = arow + (int64_t(k0) + b * 64 + g * 16) * 2;
+                wreg[2 * b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+                wreg[2 * b + 1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + 16));
+            }
+        }
+        __syncthreads();                                            // previous chunk's LDS reads are done
+        // stage X[0:16*MT][k0 : k0+256] (rows >= M and k >= K as zeros)
+        for (int v = threadIdx.x; v < 16 * MT * (kSkinnyChunk / 8); v += kSkinnyWaves * 64) {
+            const int r = v / (kSkinnyChunk / 8), kv = v % (kSkinnyChunk / 8);
+            u32x4 x = {0u, 0u, 0u, 0u};
+            if (r < M && k0 + kv * 8 < K)
+                x = *reinterpret_cast<const u32x4 *>(X + int64_t(r) * ldx + k0 + kv * 8);
+            *reinterpret_cast<u32x4 *>(xs + r * kLdsRow + kv * 16) = x;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            if (b < nblk) {
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, wreg[2 * b + s]);
+#pragma unroll
+                    for (int t = 0; t < MT; ++t) {
+                        const u32x4 xb = *reinterpret_cast<const u32x4 *>(
+                            xs + (t * 16 + i) * kLdsRow + (b * 64 + g * 16 + s * 8) * 2);
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, xb), acc[t], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    // D[row = g*4+v][col = i]: weight row n0 + g*4 + v, batch row t*16 + i
+    const int nb = n0 + g * 4;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const int m = t * 16 + i;
+        if (m < M) {
+            if (part) {
+                float *dst = part + (int64_t(split) * M + m) * Nn + nb;
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (nb + v < Nn) dst[v] = acc[t][v];
+            } else {
+                uint16_t *dst = Y + int64_t(m) * ldy + nb;
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (nb + v < Nn) dst[v] = f32_to_bf16_rne(acc[t][v]);
+            }
+        }
+    }
+}
+
+// Y[m][n] = bf16(sum over splits, in split order)
+__global__ __launch_bounds__(256) void nts_linear_reduce_kernel(const float *__restrict__ part, int splits,
+                                                                int M, int Nn, uint16_t *__restrict__ Y,
+                                                                int64_t ldy)
+{
+    const int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= int64_t(M) * Nn) return;
+    float s = 0.f;
+    for (int k = 0; k < splits; ++k) s += part[int64_t(k) * M * Nn + idx];
+    Y[(idx / Nn) * ldy + idx % Nn] = f32_to_bf16_rne(s);
+}
+
+}  // namespace
+
+int nts_linear_skinny_splits(int Nn, int K)
+{
+    const int waves = (Nn + 15) / 16;
+    const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
+    int splits = (4096 + waves - 1) / waves;          // aim at >= 16 wavefronts per compute unit
+    if (splits > n_chunks) splits = n_chunks;
+    if (splits < 1) splits = 1;
+    const int cps = (n_chunks + splits - 1) / splits;
+    return (n_chunks + cps - 1) / cps;                // no empty split
+}
+
+hipError_t nts_launch_linear_skinny(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
+                                    uint16_t *Y, int64_t ldy, float *part, int splits, int M, int Nn,
+                                    int K, hipStream_t st)
+{
+    const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
+    const int cps = (n_chunks + splits - 1) / splits;
+    const dim3 grid((Nn + 16 * kSkinnyWaves - 1) / (16 * kSkinnyWaves), splits), block(kSkinnyWaves * 64);
+    float *p = splits > 1 ? part : nullptr;
+    const int mt = (M + 15) / 16;
+#define NTS_SK(MT) hipLaunchKernelGGL((nts_linear_skinny_kernel<MT>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps)
+    if (mt == 1) NTS_SK(1);
+    else if (mt == 2) NTS_SK(2);
+    else if (mt == 3) NTS_SK(3);
+    else NTS_SK(4);
+#undef NTS_SK
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splits <= 1) return e;
+    const int64_t n = int64_t(M) * Nn;
+    hipLaunchKernelGGL(nts_linear_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, splits, M, Nn, Y, ldy);
+    return hipGetLastError();
+}

@@ -1,0 +1,84 @@
+"""GPU parity of the TP-shard-selecting linear layer against its fp64 oracle.
+Tolerance (derived in oracle.shard_linear.tolerance): fp32 accumulation of K
+products in any order plus one rounding to bfloat16."""
+import numpy as np
+import pytest
+
+from oracle import shard_linear as osl
+from workload.linear import LAYERS, linear_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2605_05467_amd import binding as b
+    ctx = b.nts_init(0)
+    yield torch, b, ctx
+    b.nts_free(ctx)
+
+
+def run_case(env, M, n_out, n_in, tp, rank, split, seed=1, pad=0):
+    torch, b, ctx = env
+    k = n_in if split == "out" else n_in // tp
+    nn = n_out // tp if split == "out" else n_out
+    Xh, Wh = linear_inputs(seed, M, n_out, n_in, x_cols=k)
+    ldx, ldw, ldy = k + pad, n_in + pad, nn + pad
+    Xp = np.zeros((M, ldx), np.uint16); Xp[:, :k] = Xh
+    Wp = np.zeros((n_out, ldw), np.uint16); Wp[:, :n_in] = Wh
+    Xd = torch.from_numpy(Xp.view(np.int16)).cuda()
+    Wd = torch.from_numpy(Wp.view(np.int16)).cuda()
+    Yd = torch.full((M, ldy), 12345, dtype=torch.int16, device="cuda")
+    sp = b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN
+    kw = dict(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=rank, split=sp, ldx=ldx, ldw=ldw, ldy=ldy)
+    ws_bytes = b.nts_shard_linear_workspace(**kw)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    b.nts_shard_linear(ctx, Xd.data_ptr(), Wd.data_ptr(), Yd.data_ptr(), workspace=ws.data_ptr(),
+                       workspace_bytes=ws_bytes, hip_stream=torch.cuda.current_stream().cuda_stream, **kw)
+    torch.cuda.synchronize()
+    Yg = Yd.cpu().numpy().view(np.uint16)
+    want, bound = osl.shard_linear(osl.bf16_to_f64(Xh), osl.bf16_to_f64(Wh), tp, rank, split)
+    got = osl.bf16_to_f64(Yg[:, :nn])
+    tol = osl.tolerance(want, bound, k)
+    err = np.abs(got - want)
+    assert np.all(err <= tol), (float((err / tol).max()), np.unravel_index(np.argmax(err / tol), err.shape))
+    if pad:
+        assert np.all(Yg[:, nn:] == 12345)                     # nothing written past the output width
+    return float((err / tol).max())
+
+
+@pytest.mark.parametrize("M", [1, 7, 16, 33, 64])
+@pytest.mark.parametrize("split", ["out", "in"])
+def test_small_batches_ragged_shapes(env, M, split):
+    run_case(env, M, 96, 512, 2, 1, split, seed=M)
+    run_case(env, M, 208, 1024 + 64, 1, 0, split, seed=M + 100, pad=8)
+    run_case(env, M, 96, 4096, 4, 3, split, seed=M + 200)
+
+
+@pytest.mark.parametrize("layer", sorted(LAYERS))
+def test_decoder_layer_shapes_decode_batch(env, layer):
+    n_out, n_in, split = LAYERS[layer]
+    run_case(env, 8, n_out, n_in, 4, 2, split, seed=5)
+
+
+def test_argument_errors(env):
+    torch, b, ctx = env
+    z = torch.zeros(64 * 64, dtype=torch.int16, device="cuda")
+    ok = dict(M=4, n_out=64, n_in=64, tp=1, rank=0, split=b.NTS_SPLIT_OUT)
+
+    def status(**over):
+        try:
+            b.nts_shard_linear(ctx, z.data_ptr(), z.data_ptr(), z.data_ptr(), **{**ok, **over})
+        except b.NtsError as e:
+            return e.status
+        return 0
+
+    assert status() == 0
+    assert status(tp=3) == b.NTS_EINVAL
+    assert status(rank=1) == b.NTS_EINVAL
+    assert status(n_in=72) == b.NTS_EINVAL            # reduction length not a multiple of 64
+    assert status(split=7) == b.NTS_EINVAL
+    assert status(ldw=60) == b.NTS_EINVAL
+    assert status(M=0) == b.NTS_EINVAL
+    torch.cuda.synchronize()
