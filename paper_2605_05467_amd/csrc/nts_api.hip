@@ -677,7 +677,9 @@ int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, cons
                                               g.splits, g.M, g.Nn, g.K, st));
         return NTS_OK;
     }
-    return fail(ctx, NTS_EINVAL, "batches above 64 rows are not supported yet");
+    NTS_HIP(ctx, nts_launch_linear_tiled(static_cast<const uint16_t *>(X), g.ldx, A, g.lda,
+                                         static_cast<uint16_t *>(Y), g.ldy, g.M, g.Nn, g.K, st));
+    return NTS_OK;
 }
 
 }  // extern "C"

@@ -105,3 +105,5 @@ int nts_linear_skinny_splits(int Nn, int K);
 hipError_t nts_launch_linear_skinny(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
                                     uint16_t *Y, int64_t ldy, float *part, int splits, int M, int Nn,
                                     int K, hipStream_t st);
+hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
+                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, hipStream_t st);

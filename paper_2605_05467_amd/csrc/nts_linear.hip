@@ -129,6 +129,109 @@ __global__ __launch_bounds__(256) void nts_linear_reduce_kernel(const float *__r
     Y[(idx / Nn) * ldy + idx % Nn] = f32_to_bf16_rne(s);
 }
 
+
+// ---------------------------------------------------------------------------
+// Large batches (M > 64, prefill): bound by the matrix cores.  A 256-thread
+// workgroup computes a 256 x 256 tile of Y; each of its four wavefronts owns a
+// 128 x 128 quadrant as 4 x 4 tiles of v_mfma_f32_32x32x16_bf16 (256 fp32
+// accumulators per lane, one wavefront per SIMD).  X and weight rows are both
+// contiguous along k, so both operands are staged the same way: 64-wide k
+// slabs go global -> registers -> LDS (row pitch 144 B, which spreads the 32
+// rows a ds_read_b128 touches over all banks), and the loads of slab k+1 are
+// issued before the MFMAs of slab k.
+constexpr int kTileM = 256, kTileN = 256, kTileK = 64;
+constexpr int kPitch = kTileK * 2 + 16;                 // bytes per LDS row
+constexpr int kTileLds = (kTileM + kTileN) * kPitch;    // 73728 B, dynamic LDS
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
+    const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
+    uint16_t *__restrict__ Y, int64_t ldy, int M, int Nn, int K)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    unsigned char *xs = lds, *as = lds + kTileM * kPitch;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int wm = wv >> 1, wn = wv & 1;                // quadrant of this wavefront
+    const int m0 = blockIdx.y * kTileM, n0 = blockIdx.x * kTileN;
+
+    // staging map: 256 rows x 8 vectors of 16 B per operand and slab; thread t takes
+    // vector (t & 7) of rows (t >> 3) + 32 * q, q = 0..7: eight lanes read one 128 B line
+    const int sv = tid & 7, sr = tid >> 3;
+    const unsigned char *xg[8], *ag[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int r = sr + 32 * q;
+        xg[q] = reinterpret_cast<const unsigned char *>(X + int64_t(min(m0 + r, M - 1)) * ldx) + sv * 16;
+        ag[q] = reinterpret_cast<const unsigned char *>(A + int64_t(min(n0 + r, Nn - 1)) * lda) + sv * 16;
+    }
+    u32x4 xr[8], ar[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        xr[q] = *reinterpret_cast<const u32x4 *>(xg[q]);
+        ar[q] = *reinterpret_cast<const u32x4 *>(ag[q]);
+    }
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    const int fr = lane & 31, fg = lane >> 5;           // fragment row and k group of this lane
+    const int n_slabs = K / kTileK;
+    for (int s = 0; s < n_slabs; ++s) {
+        __syncthreads();                                // the previous slab's LDS reads are done
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            *reinterpret_cast<u32x4 *>(xs + (sr + 32 * q) * kPitch + sv * 16) = xr[q];
+            *reinterpret_cast<u32x4 *>(as + (sr + 32 * q) * kPitch + sv * 16) = ar[q];
+        }
+        __syncthreads();
+        if (s + 1 < n_slabs) {                          // next slab's loads fly during the MFMAs
+            const int64_t off = int64_t(s + 1) * kTileK * 2;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                xr[q] = *reinterpret_cast<const u32x4 *>(xg[q] + off);
+                ar[q] = *reinterpret_cast<const u32x4 *>(ag[q] + off);
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < kTileK / 16; ++kk) {
+            bf16x8 xf[4], af[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                xf[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(
+                    xs + (wm * 128 + a * 32 + fr) * kPitch + (kk * 16 + fg * 8) * 2));
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                af[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(
+                    as + (wn * 128 + b * 32 + fr) * kPitch + (kk * 16 + fg * 8) * 2));
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[a], af[b], acc[a][b], 0, 0, 0);
+        }
+    }
+    // D[i = (v/4)*8 + (lane/32)*4 + v%4][j = lane%32]: batch row i, weight row j
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int n = n0 + wn * 128 + b * 32 + fr;
+            if (n < Nn) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm * 128 + a * 32 + (v / 4) * 8 + fg * 4 + (v % 4);
+                    if (m < M) Y[int64_t(m) * ldy + n] = f32_to_bf16_rne(acc[a][b][v]);
+                }
+            }
+        }
+}
+
 }  // namespace
 
 int nts_linear_skinny_splits(int Nn, int K)
@@ -161,5 +264,20 @@ hipError_t nts_launch_linear_skinny(const uint16_t *X, int64_t ldx, const uint16
     if (e != hipSuccess || splits <= 1) return e;
     const int64_t n = int64_t(M) * Nn;
     hipLaunchKernelGGL(nts_linear_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, splits, M, Nn, Y, ldy);
+    return hipGetLastError();
+}
+
+hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
+                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, hipStream_t st)
+{
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_tiled_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const dim3 grid((Nn + kTileN - 1) / kTileN, (M + kTileM - 1) / kTileM), block(256);
+    hipLaunchKernelGGL(nts_linear_tiled_kernel, grid, block, kTileLds, st, X, ldx, A, lda, Y, ldy, M, Nn, K);
     return hipGetLastError();
 }

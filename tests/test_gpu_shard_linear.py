@@ -82,3 +82,19 @@ def test_argument_errors(env):
     assert status(ldw=60) == b.NTS_EINVAL
     assert status(M=0) == b.NTS_EINVAL
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("M", [65, 200, 256, 300, 777])
+@pytest.mark.parametrize("split", ["out", "in"])
+def test_large_batches_tile_edges(env, M, split):
+    """Prefill-size batches: the 256 x 256 tiled matrix-core kernel with ragged
+    edges in both output dimensions."""
+    run_case(env, M, 96, 512, 2, 1, split, seed=M)
+    run_case(env, M, 528, 1024 + 64, 1, 0, split, seed=M + 100, pad=8)
+    run_case(env, M, 1024, 2048, 4, 3, split, seed=M + 200)
+
+
+@pytest.mark.parametrize("layer", ["8b_qkv", "8b_down", "14b_o"])
+def test_decoder_layer_shapes_prefill_batch(env, layer):
+    n_out, n_in, split = LAYERS[layer]
+    run_case(env, 1024, n_out, n_in, 2, 1, split, seed=9)
