@@ -137,11 +137,13 @@ __global__ __launch_bounds__(256) void nts_linear_reduce_kernel(const float *__r
 // accumulators per lane, one wavefront per SIMD).  X and weight rows are both
 // contiguous along k, so both operands are staged the same way: 64-wide k
 // slabs go global -> registers -> LDS (row pitch 144 B, which spreads the 32
-// rows a ds_read_b128 touches over all banks), and the loads of slab k+1 are
-// issued before the MFMAs of slab k.
+// rows a ds_read_b128 touches over all banks).  LDS holds two slabs: while the
+// MFMAs of slab s read one buffer, slab s+1 is written into the other and the
+// global loads of slab s+2 are in flight; one barrier per slab.
 constexpr int kTileM = 256, kTileN = 256, kTileK = 64;
+constexpr int kSupM = 4, kSupN = 8;                     // tiles per XCD-resident block
 constexpr int kPitch = kTileK * 2 + 16;                 // bytes per LDS row
-constexpr int kTileLds = (kTileM + kTileN) * kPitch;    // 73728 B, dynamic LDS
+constexpr int kTileLds = (kTileM + kTileN) * kPitch;    // 73728 B per buffer, two buffers of dynamic LDS
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -150,27 +152,32 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     uint16_t *__restrict__ Y, int64_t ldy, int M, int Nn, int K)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    unsigned char *xs = lds, *as = lds + kTileM * kPitch;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv >> 1, wn = wv & 1;                // quadrant of this wavefront
-    const int m0 = blockIdx.y * kTileM, n0 = blockIdx.x * kTileN;
+    // Workgroup -> tile.  Consecutive workgroup ids go to the 8 XCDs in turn and each XCD has
+    // its own L2, so the 32 workgroups that run together on one XCD are given a 4 x 8 block of
+    // tiles: every X slab is then fetched into that L2 once for 8 tiles and every weight slab
+    // once for 4, instead of each workgroup streaming a weight tile of its own.
+    const int tiles_m = (M + kTileM - 1) / kTileM, tiles_n = (Nn + kTileN - 1) / kTileN;
+    const int sup_n = (tiles_n + kSupN - 1) / kSupN;
+    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int sup = (seq / (kSupM * kSupN)) * 8 + xcd, in_sup = seq % (kSupM * kSupN);
+    const int tm = (sup / sup_n) * kSupM + in_sup / kSupN, tn = (sup % sup_n) * kSupN + in_sup % kSupN;
+    if (tm >= tiles_m || tn >= tiles_n) return;         // whole workgroup leaves before any barrier
+    const int m0 = tm * kTileM, n0 = tn * kTileN;
 
     // staging map: 256 rows x 8 vectors of 16 B per operand and slab; thread t takes
-    // vector (t & 7) of rows (t >> 3) + 32 * q, q = 0..7: eight lanes read one 128 B line
+    // vector (t & 7) of rows (t >> 3) + 32 * q, q = 0..7: eight lanes read one 128 B line.
+    // Row offsets are kept as 32-bit counts of 16-byte units from the operand's base.
     const int sv = tid & 7, sr = tid >> 3;
-    const unsigned char *xg[8], *ag[8];
+    uint32_t xo[8], ao[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
         const int r = sr + 32 * q;
-        xg[q] = reinterpret_cast<const unsigned char *>(X + int64_t(min(m0 + r, M - 1)) * ldx) + sv * 16;
-        ag[q] = reinterpret_cast<const unsigned char *>(A + int64_t(min(n0 + r, Nn - 1)) * lda) + sv * 16;
+        xo[q] = uint32_t((int64_t(min(m0 + r, M - 1)) * ldx) >> 3) + sv;
+        ao[q] = uint32_t((int64_t(min(n0 + r, Nn - 1)) * lda) >> 3) + sv;
     }
-    u32x4 xr[8], ar[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        xr[q] = *reinterpret_cast<const u32x4 *>(xg[q]);
-        ar[q] = *reinterpret_cast<const u32x4 *>(ag[q]);
-    }
+    const u32x4 *xb = reinterpret_cast<const u32x4 *>(X), *ab = reinterpret_cast<const u32x4 *>(A);
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -182,40 +189,70 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 
     const int fr = lane & 31, fg = lane >> 5;           // fragment row and k group of this lane
     const int n_slabs = K / kTileK;
-    for (int s = 0; s < n_slabs; ++s) {
-        __syncthreads();                                // the previous slab's LDS reads are done
+    const int st_off = sr * kPitch + sv * 16;           // where this thread's staged vectors go
+
+    // prologue: slab 0 into LDS buffer 0, slab 1 into registers
+    u32x4 xr[8], ar[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        xr[q] = xb[xo[q]];
+        ar[q] = ab[ao[q]];
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        *reinterpret_cast<u32x4 *>(lds + st_off + 32 * q * kPitch) = xr[q];
+        *reinterpret_cast<u32x4 *>(lds + kTileM * kPitch + st_off + 32 * q * kPitch) = ar[q];
+    }
+    if (n_slabs > 1) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            *reinterpret_cast<u32x4 *>(xs + (sr + 32 * q) * kPitch + sv * 16) = xr[q];
-            *reinterpret_cast<u32x4 *>(as + (sr + 32 * q) * kPitch + sv * 16) = ar[q];
-        }
-        __syncthreads();
-        if (s + 1 < n_slabs) {                          // next slab's loads fly during the MFMAs
-            const int64_t off = int64_t(s + 1) * kTileK * 2;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                xr[q] = *reinterpret_cast<const u32x4 *>(xg[q] + off);
-                ar[q] = *reinterpret_cast<const u32x4 *>(ag[q] + off);
-            }
-        }
-#pragma unroll
-        for (int kk = 0; kk < kTileK / 16; ++kk) {
-            bf16x8 xf[4], af[4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-                xf[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(
-                    xs + (wm * 128 + a * 32 + fr) * kPitch + (kk * 16 + fg * 8) * 2));
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-                af[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(
-                    as + (wn * 128 + b * 32 + fr) * kPitch + (kk * 16 + fg * 8) * 2));
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[a], af[b], acc[a][b], 0, 0, 0);
+            xr[q] = xb[xo[q] + kTileK * 2 / 16];
+            ar[q] = ab[ao[q] + kTileK * 2 / 16];
         }
     }
+    __syncthreads();
+
+#define NTS_TILE_STEP(kk)                                                                              \
+    {                                                                                                  \
+        bf16x8 xf[4], af[4];                                                                           \
+        _Pragma("unroll") for (int a = 0; a < 4; ++a)                                                  \
+            xf[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(                       \
+                xs + (wm * 128 + a * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));                   \
+        _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                  \
+            af[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(                       \
+                as + (wn * 128 + b * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));                   \
+        _Pragma("unroll") for (int a = 0; a < 4; ++a)                                                  \
+            _Pragma("unroll") for (int b = 0; b < 4; ++b)                                              \
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[a], af[b], acc[a][b], 0, 0, 0); \
+    }
+
+    for (int s = 0; s < n_slabs; ++s) {
+        const unsigned char *xs = lds + (s & 1) * kTileLds, *as = xs + kTileM * kPitch;
+        unsigned char *nx = lds + ((s + 1) & 1) * kTileLds;
+        // the first k step's MFMAs keep the matrix cores busy while the wait for slab s+1's
+        // global loads, its LDS stores and the loads of slab s+2 are issued
+        NTS_TILE_STEP(0)
+        if (s + 1 < n_slabs) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                *reinterpret_cast<u32x4 *>(nx + st_off + 32 * q * kPitch) = xr[q];
+                *reinterpret_cast<u32x4 *>(nx + kTileM * kPitch + st_off + 32 * q * kPitch) = ar[q];
+            }
+            if (s + 2 < n_slabs) {
+                const uint32_t off = uint32_t(s + 2) * (kTileK * 2 / 16);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    xr[q] = xb[xo[q] + off];
+                    ar[q] = ab[ao[q] + off];
+                }
+            }
+        }
+        NTS_TILE_STEP(1)
+        NTS_TILE_STEP(2)
+        NTS_TILE_STEP(3)
+        __syncthreads();                                // buffer s&1 is free, buffer (s+1)&1 is complete
+    }
+#undef NTS_TILE_STEP
     // D[i = (v/4)*8 + (lane/32)*4 + v%4][j = lane%32]: batch row i, weight row j
 #pragma unroll
     for (int a = 0; a < 4; ++a)
@@ -273,11 +310,13 @@ hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_tiled_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kTileLds);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    const dim3 grid((Nn + kTileN - 1) / kTileN, (M + kTileM - 1) / kTileM), block(256);
-    hipLaunchKernelGGL(nts_linear_tiled_kernel, grid, block, kTileLds, st, X, ldx, A, lda, Y, ldy, M, Nn, K);
+    const int tiles_m = (M + kTileM - 1) / kTileM, tiles_n = (Nn + kTileN - 1) / kTileN;
+    const int sups = ((tiles_m + kSupM - 1) / kSupM) * ((tiles_n + kSupN - 1) / kSupN);
+    const dim3 grid(unsigned((sups + 7) / 8) * 8u * kSupM * kSupN), block(256);
+    hipLaunchKernelGGL(nts_linear_tiled_kernel, grid, block, 2 * kTileLds, st, X, ldx, A, lda, Y, ldy, M, Nn, K);
     return hipGetLastError();
 }
