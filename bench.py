@@ -62,6 +62,9 @@ def parse_args():
     ap.add_argument("--staging-mib", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true")
+    ap.add_argument("--linear", action="store_true",
+                    help="TP-shard-selecting linear layer (Sec. 3.2.1): decode and prefill batches of the "
+                         "8B model's four layers at TP 1/2/4/8, one JSON line each")
     ap.add_argument("--strategies", action="store_true",
                     help="latency of four migration strategies on the paper's payload sizes, one JSON line each")
     ap.add_argument("--no-memcpy", action="store_true",
@@ -209,6 +212,68 @@ def strategies(args, torch, b, wdev, make_case):
     b.nts_free(ctx)
 
 
+def linear_bench(args, torch, b):
+    """Shard-selecting linear layer: rank tp-1 of each TP level computes with its 1/tp of the
+    full weight.  Decode batches (M <= 64) are HBM-bound: bytes = the shard read once (+X, +Y).
+    Prefill batches are matrix-core-bound: 2*M*Nn*K flops against 2.5 PFLOP/s (bf16, dense).
+    Launches are captured into a HIP graph that walks through more than 3 GiB of distinct
+    weight copies, so no shard is served from a cache and launch gaps do not hide the kernels."""
+    from workload.linear import LAYERS
+    ctx = b.nts_init(0)
+    for layer in ("8b_qkv", "8b_o", "8b_gate_up", "8b_down"):
+        n_out, n_in, split = LAYERS[layer]
+        wbytes = n_out * n_in * 2
+        copies = max(2, (3 << 30) // wbytes + 1)
+        W = (torch.rand(copies, n_out, n_in, device="cuda") * 0.08 - 0.04).to(torch.bfloat16)
+        for tp in (1, 2, 4, 8):
+            for M in (1, 16, 64, 4096):
+                k = n_in if split == "out" else n_in // tp
+                nn = n_out // tp if split == "out" else n_out
+                X = (torch.rand(M, k, device="cuda") * 4 - 2).to(torch.bfloat16)
+                Y = torch.empty(M, nn, device="cuda", dtype=torch.bfloat16)
+                kw = dict(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=tp - 1,
+                          split=b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN)
+                wsb = b.nts_shard_linear_workspace(**kw)
+                ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+
+                def launch(i):
+                    b.nts_shard_linear(ctx, X.data_ptr(), W[i % copies].data_ptr(), Y.data_ptr(),
+                                       workspace=ws.data_ptr(), workspace_bytes=wsb,
+                                       hip_stream=torch.cuda.current_stream().cuda_stream, **kw)
+
+                n_launch = copies * 2 if M <= 64 else max(4, copies)
+                launch(0)
+                torch.cuda.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    for i in range(n_launch):
+                        launch(i)
+                graph.replay()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                ts = []
+                for _ in range(5):
+                    e0.record()
+                    graph.replay()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ts.append(e0.elapsed_time(e1) * 1e3 / n_launch)
+                us = sorted(ts)[2]
+                shard_bytes = nn * k * 2
+                if M <= 64:
+                    ach = (shard_bytes + M * k * 2 + M * nn * 2) / us / 1e3
+                    roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS}
+                else:
+                    ach = 2.0 * M * nn * k / us / 1e6
+                    roof = {"bound": "mfma", "achieved": ach, "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0}
+                print(json.dumps({"linear": layer, "split": split, "tp": tp, "rank": tp - 1, "M": M, "Nn": nn, "K": k,
+                                  "shard_MiB": shard_bytes / 2**20, "us_per_call": us, "dtype": "bf16",
+                                  "k_splits": wsb // (4 * M * nn) if wsb else 1, "roofline": roof}), flush=True)
+                del graph
+        del W
+    b.nts_free(ctx)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -229,6 +294,9 @@ def main():
         return
     if args.strategies:
         strategies(args, torch, b, wdev, make_case)
+        return
+    if args.linear:
+        linear_bench(args, torch, b)
         return
 
     cases = _variant_cases(args.workload)

@@ -643,7 +643,7 @@ int linear_geom(const nts_linear_desc *d, LinearGeom *g)
     g->ldy = d->ldy ? d->ldy : g->Nn;
     if (g->K % 64 || g->ldx < g->K || g->ldy < g->Nn) return NTS_EINVAL;
     if (g->ldx % 8 || g->lda % 8 || g->ldy % 8 || g->a_off % 8) return NTS_EINVAL;
-    g->splits = g->M <= 64 ? nts_linear_skinny_splits(g->Nn, g->K) : 0;
+    g->splits = g->M <= 64 ? nts_linear_skinny_splits(g->M, g->Nn, g->K) : 0;
     return NTS_OK;
 }
 }  // namespace

@@ -101,7 +101,7 @@ hipError_t nts_launch_flatten(const int32_t *d_tok_off, const int32_t *d_pg_off,
                               int32_t *d_err, hipStream_t st);
 
 // nts_linear.hip: Y[M][Nn] = X[M][K] . A[Nn][K]^T, bf16 in, fp32 accumulate, bf16 out
-int nts_linear_skinny_splits(int Nn, int K);
+int nts_linear_skinny_splits(int M, int Nn, int K);
 hipError_t nts_launch_linear_skinny(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
                                     uint16_t *Y, int64_t ldy, float *part, int splits, int M, int Nn,
                                     int K, hipStream_t st);

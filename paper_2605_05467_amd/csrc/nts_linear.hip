@@ -15,6 +15,8 @@
 // operands agree, so inside a 64-wide k block lane group g takes k = 16g+8s+e
 // for the block's two MFMAs s = 0,1: each lane then reads 32 contiguous bytes
 // and the four lanes of a row cover one full 128-byte line.
+#include <algorithm>
+
 #include "nts_internal.h"
 
 namespace {
@@ -35,8 +37,10 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return uint16_t(u >> 16);
 }
 
-// MT = number of 16-row batch tiles (M <= 16*MT)
-template <int MT>
+// MT = number of 16-row batch tiles (M <= 16*MT); RT = 16-row weight tiles per wavefront.
+// A larger RT reuses every staged X chunk and every X fragment for more weight rows, which
+// is what matters once the batch is wide (MT 3..4); RT = 1 keeps more wavefronts in flight.
+template <int MT, int RT>
 __global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
     const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
     uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ part, int M, int Nn, int K,
@@ -45,31 +49,37 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
     __shared__ __attribute__((aligned(16))) unsigned char xs[16 * MT * kLdsRow];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int i = lane & 15, g = lane >> 4;
-    const int n0 = (blockIdx.x * kSkinnyWaves + wv) * 16;          // first weight row of this wavefront
+    const int n0 = (blockIdx.x * kSkinnyWaves + wv) * 16 * RT;     // first weight row of this wavefront
     const int split = blockIdx.y;
     const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
     const int c_lo = split * chunks_per_split;
     const int c_hi = min(n_chunks, c_lo + chunks_per_split);
-    const int row = min(n0 + i, Nn - 1);                            // clamp: rows past the end are computed, not stored
-    const unsigned char *arow = reinterpret_cast<const unsigned char *>(A + int64_t(row) * lda);
-
-    f32x4 acc[MT];
+    const unsigned char *arow[RT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < RT; ++r)                                    // clamp: rows past the end are computed, not stored
+        arow[r] = reinterpret_cast<const unsigned char *>(A + int64_t(min(n0 + r * 16 + i, Nn - 1)) * lda);
+
+    f32x4 acc[RT][MT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     for (int c = c_lo; c < c_hi; ++c) {
         const int k0 = c * kSkinnyChunk;
         const int nblk = min(4, (K - k0) / 64);                     // K is a multiple of 64
         // weight loads first: 2 x 16 B per 64-wide block, all in flight while X is staged
-        u32x4 wreg[8];
+        u32x4 wreg[RT][8];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            if (b < nblk) {
-                const unsigned char *p = arow + (int64_t(k0) + b * 64 + g * 16) * 2;
-                wreg[2 * b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-                wreg[2 * b + 1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + 16));
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (b < nblk) {
+                    const unsigned char *p = arow[r] + (int64_t(k0) + b * 64 + g * 16) * 2;
+                    wreg[r][2 * b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+                    wreg[r][2 * b + 1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + 16));
+                }
             }
-        }
         __syncthreads();                                            // previous chunk's LDS reads are done
         // stage X[0:16*MT][k0 : k0+256] (rows >= M and k >= K as zeros)
         for (int v = threadIdx.x; v < 16 * MT * (kSkinnyChunk / 8); v += kSkinnyWaves * 64) {
@@ -85,33 +95,38 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
             if (b < nblk) {
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, wreg[2 * b + s]);
 #pragma unroll
                     for (int t = 0; t < MT; ++t) {
-                        const u32x4 xb = *reinterpret_cast<const u32x4 *>(
-                            xs + (t * 16 + i) * kLdsRow + (b * 64 + g * 16 + s * 8) * 2);
-                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, xb), acc[t], 0, 0, 0);
+                        const bf16x8 xb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(
+                            xs + (t * 16 + i) * kLdsRow + (b * 64 + g * 16 + s * 8) * 2));
+#pragma unroll
+                        for (int r = 0; r < RT; ++r)
+                            acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8, wreg[r][2 * b + s]), xb, acc[r][t], 0, 0, 0);
                     }
                 }
             }
         }
     }
-    // D[row = g*4+v][col = i]: weight row n0 + g*4 + v, batch row t*16 + i
-    const int nb = n0 + g * 4;
+    // D[row = g*4+v][col = i]: weight row n0 + r*16 + g*4 + v, batch row t*16 + i
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        const int m = t * 16 + i;
-        if (m < M) {
-            if (part) {
-                float *dst = part + (int64_t(split) * M + m) * Nn + nb;
+    for (int r = 0; r < RT; ++r) {
+        const int nb = n0 + r * 16 + g * 4;
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (nb + v < Nn) dst[v] = acc[t][v];
-            } else {
-                uint16_t *dst = Y + int64_t(m) * ldy + nb;
+        for (int t = 0; t < MT; ++t) {
+            const int m = t * 16 + i;
+            if (m < M) {
+                if (part) {
+                    float *dst = part + (int64_t(split) * M + m) * Nn + nb;
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (nb + v < Nn) dst[v] = f32_to_bf16_rne(acc[t][v]);
+                    for (int v = 0; v < 4; ++v)
+                        if (nb + v < Nn) dst[v] = acc[r][t][v];
+                } else {
+                    uint16_t *dst = Y + int64_t(m) * ldy + nb;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (nb + v < Nn) dst[v] = f32_to_bf16_rne(acc[r][t][v]);
+                }
             }
         }
     }
@@ -271,11 +286,18 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 
 }  // namespace
 
-int nts_linear_skinny_splits(int Nn, int K)
+static int skinny_row_tiles(int M) { return M > 32 ? 2 : 1; }
+
+int nts_linear_skinny_splits(int M, int Nn, int K)
 {
-    const int waves = (Nn + 15) / 16;
+    const int waves = (Nn + 16 * skinny_row_tiles(M) - 1) / (16 * skinny_row_tiles(M));
     const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
     int splits = (4096 + waves - 1) / waves;          // aim at >= 16 wavefronts per compute unit
+    // the fp32 partial sums are written and read back by the reduction: keep that traffic
+    // (splits * M * Nn * 8 bytes) under a fifth of the weight bytes, or 16 MiB if that is more
+    const int64_t budget = std::max<int64_t>(int64_t(Nn) * K * 2 / 5, int64_t(16) << 20);
+    const int64_t cap = budget / (int64_t(M) * Nn * 8);
+    if (splits > cap) splits = int(cap);
     if (splits > n_chunks) splits = n_chunks;
     if (splits < 1) splits = 1;
     const int cps = (n_chunks + splits - 1) / splits;
@@ -288,14 +310,15 @@ hipError_t nts_launch_linear_skinny(const uint16_t *X, int64_t ldx, const uint16
 {
     const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
     const int cps = (n_chunks + splits - 1) / splits;
-    const dim3 grid((Nn + 16 * kSkinnyWaves - 1) / (16 * kSkinnyWaves), splits), block(kSkinnyWaves * 64);
+    const int rows_per_wg = 16 * skinny_row_tiles(M) * kSkinnyWaves;
+    const dim3 grid((Nn + rows_per_wg - 1) / rows_per_wg, splits), block(kSkinnyWaves * 64);
     float *p = splits > 1 ? part : nullptr;
     const int mt = (M + 15) / 16;
-#define NTS_SK(MT) hipLaunchKernelGGL((nts_linear_skinny_kernel<MT>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps)
-    if (mt == 1) NTS_SK(1);
-    else if (mt == 2) NTS_SK(2);
-    else if (mt == 3) NTS_SK(3);
-    else NTS_SK(4);
+#define NTS_SK(MT, RT) hipLaunchKernelGGL((nts_linear_skinny_kernel<MT, RT>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps)
+    if (mt == 1) NTS_SK(1, 1);
+    else if (mt == 2) NTS_SK(2, 1);
+    else if (mt == 3) NTS_SK(3, 2);
+    else NTS_SK(4, 2);
 #undef NTS_SK
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits <= 1) return e;
