@@ -65,6 +65,8 @@ def parse_args():
     ap.add_argument("--linear", action="store_true",
                     help="TP-shard-selecting linear layer (Sec. 3.2.1): decode and prefill batches of the "
                          "8B model's four layers at TP 1/2/4/8, one JSON line each")
+    ap.add_argument("--planner", action="store_true",
+                    help="goodput-efficiency planner (Sec. 3.3.1): planning time at 128 GPUs x 4 tiers (host only)")
     ap.add_argument("--strategies", action="store_true",
                     help="latency of four migration strategies on the paper's payload sizes, one JSON line each")
     ap.add_argument("--no-memcpy", action="store_true",
@@ -274,8 +276,37 @@ def linear_bench(args, torch, b):
     b.nts_free(ctx)
 
 
+def planner_bench():
+    """Planning time of one control window at the size the paper quotes (128 GPUs,
+    four request groups; Sec. 4.2.3), on synthetic capacity tables; host code only."""
+    from oracle import planner as op
+    from paper_2605_05467_amd import binding as b
+    from workload.planner import synthetic_tiers
+    for n_gpus, n_tiers in ((128, 4), (1024, 8)):
+        tiers = synthetic_tiers(2024, n_tiers, rps_scale=100.0 * n_gpus / 32)
+        reps = 2000
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            allocs, left = b.nts_plan_cluster(n_gpus, tiers)
+        dt = (time.perf_counter() - t0) / reps
+        t0 = time.perf_counter()
+        want, wleft = op.plan(n_gpus, [op.Tier(*t) for t in tiers])
+        dt_oracle = time.perf_counter() - t0
+        same = [(a.tier, a.tp_prefill, a.tp_decode, a.P, a.D) for a in allocs] == \
+               [(a.tier, a.tp_prefill, a.tp_decode, a.P, a.D) for a in want] and left == wleft
+        print(json.dumps({"planner": True, "n_gpus": n_gpus, "n_tiers": n_tiers, "configs_enumerated": n_tiers * 16,
+                          "greedy_steps": len(allocs), "gpus_left": left, "us_per_plan": dt * 1e6,
+                          "includes": "ctypes marshalling of tiers and results", "threads": 1,
+                          "matches_oracle": same,
+                          "cpu_baseline": {"value": dt_oracle * 1e6, "unit": "us per plan", "kind": "oracle", "cores": 1},
+                          "paper_context": "2.49 ms average at 128 GPUs x 4 groups, multi-threaded Rust, other hardware"}))
+
+
 def main():
     args = parse_args()
+    if args.planner:
+        planner_bench()
+        return
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); multi-GPU runs are not part of it",
               file=sys.stderr)

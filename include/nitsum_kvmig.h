@@ -249,6 +249,43 @@ int nts_shard_linear_workspace(const nts_linear_desc *d, size_t *bytes);
 int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, const void *W_full,
                      void *Y, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ------------------------------------------------------------------------
+ * Goodput-efficiency planner (paper Sec. 3.3.1; host only, no GPU needed).
+ * For SLO tier k, thp[i] / thd[i] are the profiled maximum prefill / decode
+ * request rates (req/s) of ONE instance at TP level {1,2,4,8}[i] under the
+ * tier's TTFT / TPOT SLO; 0 marks a level that cannot meet the SLO.  A
+ * configuration (tier, prefill TP, decode TP) is scored on a balanced block of
+ * P prefill and D decode instances (P*THP ~ D*THD) with the paper's Eq. 1,
+ *     GE = min(P*THP, rps) / (P*TPi + D*TPj),
+ * and nts_plan_cluster assigns the pool greedily by GE * rps / served_rps.
+ * Where the paper is silent: a block is the (P, D) in 1..max_inst with the
+ * smallest |P*THP - D*THD| / max (ties: fewer instances, then smaller P) and
+ * serves min(P*THP, D*THD); Eq. 1 uses the tier's unmet rate; a tier served
+ * nothing yet outranks the others; ties: larger GE, then lower tier, prefill
+ * TP, decode TP; one block per step until no demand is unmet or nothing fits.
+ * out: host array of max_out entries in assignment order; *n_out is the number
+ * of steps taken (NTS_ERANGE if it exceeds max_out; the first max_out are
+ * valid), *gpus_left the GPUs no block could use.
+ */
+enum { NTS_TP_LEVELS = 4 };
+
+typedef struct nts_tier {
+    double rps;                 /* incoming request rate of the tier in the last window */
+    double thp[NTS_TP_LEVELS];  /* prefill req/s of one instance at TP 1, 2, 4, 8 */
+    double thd[NTS_TP_LEVELS];  /* decode req/s of one instance at TP 1, 2, 4, 8 */
+} nts_tier;
+
+typedef struct nts_alloc {
+    int32_t tier, tp_prefill, tp_decode, P, D, gpus;
+    double served_rps;          /* goodput this block adds to its tier */
+} nts_alloc;
+
+int nts_balanced_block(double thp, double thd, int max_inst, int *P, int *D);
+int nts_goodput_efficiency(double thp, int tpi, double thd, int tpj, int P, int D, double rps,
+                           double *ge);
+int nts_plan_cluster(int n_gpus, int n_tiers, const nts_tier *tiers, int max_inst, nts_alloc *out,
+                     int max_out, int *n_out, int *gpus_left);
+
 #ifdef __cplusplus
 }
 #endif

@@ -43,7 +43,9 @@ EXPORTS = (
     "nts_run_pack", "nts_run_pack_chunk", "nts_run_unpack", "nts_run_unpack_chunk",
     "nts_run_migrate", "nts_run_migrate_direct", "nts_run_memcpy_baseline",
     "nts_shard_linear", "nts_shard_linear_workspace",
+    "nts_balanced_block", "nts_goodput_efficiency", "nts_plan_cluster",
 )
+NTS_TP_LEVELS = 4
 NTS_SPLIT_OUT, NTS_SPLIT_IN = 0, 1
 
 
@@ -65,6 +67,16 @@ class nts_linear_desc(ctypes.Structure):
         ("rank", ctypes.c_int32), ("split", ctypes.c_int32),
         ("ldx", ctypes.c_int64), ("ldw", ctypes.c_int64), ("ldy", ctypes.c_int64),
     ]
+
+
+class nts_tier(ctypes.Structure):
+    _fields_ = [("rps", ctypes.c_double), ("thp", ctypes.c_double * 4), ("thd", ctypes.c_double * 4)]
+
+
+class nts_alloc(ctypes.Structure):
+    _fields_ = [("tier", ctypes.c_int32), ("tp_prefill", ctypes.c_int32), ("tp_decode", ctypes.c_int32),
+                ("P", ctypes.c_int32), ("D", ctypes.c_int32), ("gpus", ctypes.c_int32),
+                ("served_rps", ctypes.c_double)]
 
 
 class nts_info(ctypes.Structure):
@@ -97,6 +109,10 @@ _lib.nts_run_migrate_direct.argtypes = [_vp, _vp, _vp, _vp]
 _lib.nts_run_memcpy_baseline.argtypes = [_vp, _vp, _vp, _i, _vp, ctypes.POINTER(_i64)]
 _lib.nts_shard_linear_workspace.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(ctypes.c_size_t)]
 _lib.nts_shard_linear.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_d = ctypes.c_double
+_lib.nts_balanced_block.argtypes = [_d, _d, _i, _pi, _pi]
+_lib.nts_goodput_efficiency.argtypes = [_d, _i, _d, _i, _i, _i, _d, ctypes.POINTER(_d)]
+_lib.nts_plan_cluster.argtypes = [_i, _i, ctypes.POINTER(nts_tier), _i, ctypes.POINTER(nts_alloc), _i, _pi, _pi]
 for _name in EXPORTS:
     if _name not in ("nts_last_error", "nts_strerror"):
         getattr(_lib, _name).restype = _i
@@ -249,3 +265,36 @@ def nts_shard_linear(ctx: int, X: int, W_full: int, Y: int, *, M: int, n_out: in
                      workspace: int = 0, workspace_bytes: int = 0, hip_stream: int = 0) -> None:
     d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy)
     _check(_lib.nts_shard_linear(ctx, ctypes.byref(d), X, W_full, Y, workspace, workspace_bytes, hip_stream), ctx)
+
+
+def nts_balanced_block(thp: float, thd: float, max_inst: int = 8) -> Tuple[int, int]:
+    P, D = ctypes.c_int(), ctypes.c_int()
+    st = _lib.nts_balanced_block(thp, thd, max_inst, ctypes.byref(P), ctypes.byref(D))
+    if st != NTS_OK:
+        raise NtsError(st, "nts_balanced_block")
+    return P.value, D.value
+
+
+def nts_goodput_efficiency(thp: float, tpi: int, thd: float, tpj: int, P: int, D: int, rps: float) -> float:
+    ge = ctypes.c_double()
+    st = _lib.nts_goodput_efficiency(thp, tpi, thd, tpj, P, D, rps, ctypes.byref(ge))
+    if st != NTS_OK:
+        raise NtsError(st, "nts_goodput_efficiency")
+    return ge.value
+
+
+def nts_plan_cluster(n_gpus: int, tiers: Sequence[Tuple[float, Sequence[float], Sequence[float]]],
+                     max_inst: int = 8, max_out: int = 4096):
+    """tiers: (rps, thp[4], thd[4]) per tier.  Returns (list of nts_alloc, gpus_left)."""
+    arr = (nts_tier * max(1, len(tiers)))()
+    for k, (rps, thp, thd) in enumerate(tiers):
+        arr[k].rps = rps
+        for i in range(4):
+            arr[k].thp[i] = thp[i]
+            arr[k].thd[i] = thd[i]
+    out = (nts_alloc * max_out)()
+    n, left = ctypes.c_int(), ctypes.c_int()
+    st = _lib.nts_plan_cluster(n_gpus, len(tiers), arr, max_inst, out, max_out, ctypes.byref(n), ctypes.byref(left))
+    if st != NTS_OK:
+        raise NtsError(st, "nts_plan_cluster")
+    return [out[i] for i in range(n.value)], left.value

@@ -1,0 +1,67 @@
+"""The library's goodput planner (host-only C ABI calls) against its oracle:
+identical blocks and assignment order, identical rates (same double
+arithmetic on both sides, so the comparison is exact)."""
+import itertools
+
+import pytest
+
+from oracle import planner as op
+from workload.planner import synthetic_tiers
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2605_05467_amd import binding
+    return binding
+
+
+def as_tuple(a):
+    return (a.tier, a.tp_prefill, a.tp_decode, a.P, a.D, a.gpus)
+
+
+def test_block_and_eq1_match(b):
+    for thp, thd in itertools.product([1.0, 2.5, 3.0, 7.0, 10.0, 13.7], repeat=2):
+        for m in (1, 4, 8):
+            assert b.nts_balanced_block(thp, thd, m) == op.balanced_block(thp, thd, m)
+        P, D = op.balanced_block(thp, thd)
+        for rps in (0.5, 5.0, 1e6):
+            assert b.nts_goodput_efficiency(thp, 2, thd, 4, P, D, rps) == op.goodput_efficiency(thp, 2, thd, 4, P, D, rps)
+    with pytest.raises(b.NtsError):
+        b.nts_balanced_block(0.0, 1.0)
+    with pytest.raises(b.NtsError):
+        b.nts_goodput_efficiency(1.0, 0, 1.0, 1, 1, 1, 1.0)
+
+
+def test_hand_worked_run(b):
+    tiers = [(10.0, [4, 10, 0, 0], [4, 10, 0, 0]), (2.0, [2, 0, 0, 0], [2, 0, 0, 0])]
+    allocs, left = b.nts_plan_cluster(8, tiers)
+    assert [as_tuple(a) + (a.served_rps,) for a in allocs] == [(0, 2, 2, 1, 1, 4, 10.0), (1, 1, 1, 1, 1, 2, 2.0)]
+    assert left == 2
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_instances_match_oracle(b, seed):
+    n_tiers = 1 + seed % 5
+    tiers = synthetic_tiers(seed, n_tiers)
+    for G in (0, 3, 8, 16, 64, 128):
+        got, left = b.nts_plan_cluster(G, tiers)
+        want, wleft = op.plan(G, [op.Tier(*t) for t in tiers])
+        assert left == wleft
+        assert [as_tuple(a) for a in got] == [(a.tier, a.tp_prefill, a.tp_decode, a.P, a.D, a.gpus) for a in want]
+        assert [a.served_rps for a in got] == [a.served for a in want]
+
+
+def test_paper_scale_instance_and_errors(b):
+    """128 GPUs and four request groups (the size of the paper's planning-time figure)."""
+    tiers = synthetic_tiers(2024, 4, rps_scale=400.0)
+    got, left = b.nts_plan_cluster(128, tiers)
+    want, wleft = op.plan(128, [op.Tier(*t) for t in tiers])
+    assert [as_tuple(a) for a in got] == [(a.tier, a.tp_prefill, a.tp_decode, a.P, a.D, a.gpus) for a in want]
+    assert left == wleft and sum(a.gpus for a in got) + left == 128 and len(got) > 4
+    with pytest.raises(b.NtsError) as ei:
+        b.nts_plan_cluster(128, tiers, max_out=2)
+    assert ei.value.status == b.NTS_ERANGE
+    with pytest.raises(b.NtsError):
+        b.nts_plan_cluster(-1, tiers)
+    with pytest.raises(b.NtsError):
+        b.nts_plan_cluster(8, [(-1.0, [1, 1, 1, 1], [1, 1, 1, 1])])
