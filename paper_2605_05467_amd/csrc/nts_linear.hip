@@ -292,7 +292,7 @@ int nts_linear_skinny_splits(int M, int Nn, int K)
 {
     const int waves = (Nn + 16 * skinny_row_tiles(M) - 1) / (16 * skinny_row_tiles(M));
     const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
-    int splits = (4096 + waves - 1) / waves;          // aim at >= 16 wavefronts per compute unit
+    int splits = (2048 + waves - 1) / waves;          // aim at >= 8 wavefronts per compute unit (swept: 512..8192)
     // the fp32 partial sums are written and read back by the reduction: keep that traffic
     // (splits * M * Nn * 8 bytes) under a fifth of the weight bytes, or 16 MiB if that is more
     const int64_t budget = std::max<int64_t>(int64_t(Nn) * K * 2 / 5, int64_t(16) << 20);

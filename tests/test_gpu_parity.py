@@ -344,3 +344,41 @@ def test_memcpy_baseline_merges_contiguous_runs(b, ctx, torch):
     # runs break where either side's slots stop being consecutive: count them on the host
     runs = 1 + int(np.sum((np.diff(sslot) != 1) | (np.diff(dslot) != 1)))
     assert n == runs * sh.L * 2 and runs <= 5
+
+
+def test_migrate_can_be_captured_in_a_hip_graph(b, ctx, torch):
+    """run calls allocate nothing and never synchronise, so a caller may record
+    them into a HIP graph: several replays, with eager work in between, all
+    give the eager result."""
+    from gpu_util import device_pool, make_plan, slab_bytes, to_host
+    from workload import device as wdev
+    case = make_case("c1")[0]
+    sh = case.shape
+    _, _, dst_h = _expected_full(case, sh.L, sh.D)
+    src_d, dst_d = device_pool(case, "src"), device_pool(case, "dst")
+    sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+    dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
+    plan = make_plan(b, ctx, case, staging_bytes=1 << 20)
+    try:
+        info = b.nts_plan_info(plan)
+        staging = torch.empty(2 * info.chunk_bytes, dtype=torch.uint8, device="cuda")
+
+        def run():
+            b.nts_run_migrate(plan, sp, dp, staging.data_ptr(), torch.cuda.current_stream().cuda_stream)
+
+        run()
+        torch.cuda.synchronize()
+        assert to_host(dst_d).tobytes() == dst_h.tobytes()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run()
+        for _ in range(3):
+            wdev.fill_tensor(dst_d, case.seed_dst)          # eager work between replays
+            staging.fill_(0x5A)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert to_host(dst_d).tobytes() == dst_h.tobytes()
+        del graph
+    finally:
+        b.nts_plan_free(plan)
