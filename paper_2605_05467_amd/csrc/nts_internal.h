@@ -72,6 +72,7 @@ struct NtsMoveJob {
     int32_t v_shift;       // log2(V) if V is a power of two, else -1
     uint32_t lc0, j0;      // q0 split into slab index and token index
     uint32_t n_vec;        // vectors (= lanes) of this job
+    uint32_t wave_in_frag; // 1 when V is a multiple of 64: a wavefront never straddles fragments
 };
 
 enum NtsMoveMode { NTS_MOVE_PACK = 0, NTS_MOVE_UNPACK = 1 };
