@@ -227,26 +227,32 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     }
     __syncthreads();
 
-#define NTS_TILE_STEP(kk)                                                                              \
+    // fragments of k step kk+1 are read from LDS while the MFMAs of step kk run
+#define NTS_LOAD_FRAGS(kk, XF, AF)                                                                     \
     {                                                                                                  \
-        bf16x8 xf[4], af[4];                                                                           \
         _Pragma("unroll") for (int a = 0; a < 4; ++a)                                                  \
-            xf[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(                       \
+            XF[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(                       \
                 xs + (wm * 128 + a * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));                   \
         _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                  \
-            af[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(                       \
+            AF[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(                       \
                 as + (wn * 128 + b * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));                   \
+    }
+#define NTS_MFMAS(XF, AF)                                                                              \
+    {                                                                                                  \
         _Pragma("unroll") for (int a = 0; a < 4; ++a)                                                  \
             _Pragma("unroll") for (int b = 0; b < 4; ++b)                                              \
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[a], af[b], acc[a][b], 0, 0, 0); \
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(XF[a], AF[b], acc[a][b], 0, 0, 0); \
     }
 
     for (int s = 0; s < n_slabs; ++s) {
         const unsigned char *xs = lds + (s & 1) * kTileLds, *as = xs + kTileM * kPitch;
         unsigned char *nx = lds + ((s + 1) & 1) * kTileLds;
-        // the first k step's MFMAs keep the matrix cores busy while the wait for slab s+1's
-        // global loads, its LDS stores and the loads of slab s+2 are issued
-        NTS_TILE_STEP(0)
+        bf16x8 xf0[4], af0[4], xf1[4], af1[4];
+        NTS_LOAD_FRAGS(0, xf0, af0)
+        NTS_LOAD_FRAGS(1, xf1, af1)
+        NTS_MFMAS(xf0, af0)
+        // slab s+1 (in registers) goes to the other LDS buffer and the loads of slab s+2 start
+        // while the matrix cores work on the first k step
         if (s + 1 < n_slabs) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
@@ -262,12 +268,15 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
                 }
             }
         }
-        NTS_TILE_STEP(1)
-        NTS_TILE_STEP(2)
-        NTS_TILE_STEP(3)
+        NTS_LOAD_FRAGS(2, xf0, af0)
+        NTS_MFMAS(xf1, af1)
+        NTS_LOAD_FRAGS(3, xf1, af1)
+        NTS_MFMAS(xf0, af0)
+        NTS_MFMAS(xf1, af1)
         __syncthreads();                                // buffer s&1 is free, buffer (s+1)&1 is complete
     }
-#undef NTS_TILE_STEP
+#undef NTS_LOAD_FRAGS
+#undef NTS_MFMAS
     // D[i = (v/4)*8 + (lane/32)*4 + v%4][j = lane%32]: batch row i, weight row j
 #pragma unroll
     for (int a = 0; a < 4; ++a)
