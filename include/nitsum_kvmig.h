@@ -222,8 +222,8 @@ int nts_run_memcpy_baseline(nts_plan *plan, const void *const *src_layer_ptrs,
  *   NTS_SPLIT_OUT  Y[M][n_out/tp] = X[M][n_in]    . W[rank*n_out/tp : +n_out/tp, :]^T
  *   NTS_SPLIT_IN   Y[M][n_out]    = X[M][n_in/tp] . W[:, rank*n_in/tp : +n_in/tp]^T
  *                  (a partial sum; the all-reduce over ranks is the caller's)
- * X, W, Y: device, bfloat16; products are accumulated in fp32 and Y is rounded
- * to nearest even once.  ldx / ldw / ldy: row strides in elements, 0 = dense
+ * X, W, Y: device, all bfloat16 (NTS_BF16) or all IEEE float16 (NTS_F16);
+ * products are accumulated in fp32 and Y is rounded to nearest even once.  ldx / ldw / ldy: row strides in elements, 0 = dense
  * (n_in or n_in/tp for X, n_in for W, the output width for Y); all strides
  * multiples of 8, all pointers 16-byte aligned.  The shard's reduction length
  * (n_in or n_in/tp) must be a multiple of 64.  workspace: device scratch of at
@@ -234,6 +234,7 @@ int nts_run_memcpy_baseline(nts_plan *plan, const void *const *src_layer_ptrs,
  * workspace too small), NTS_EHIP.
  */
 enum { NTS_SPLIT_OUT = 0, NTS_SPLIT_IN = 1 };
+enum { NTS_BF16 = 0, NTS_F16 = 1 };
 
 typedef struct nts_linear_desc {
     int32_t M;      /* rows of X: tokens in the batch, >= 1 */
@@ -242,6 +243,8 @@ typedef struct nts_linear_desc {
     int32_t tp;     /* TP level N */
     int32_t rank;   /* this GPU's rank in its TP group */
     int32_t split;  /* NTS_SPLIT_OUT or NTS_SPLIT_IN */
+    int32_t dtype;  /* NTS_BF16 or NTS_F16 */
+    int32_t reserved;
     int64_t ldx, ldw, ldy;
 } nts_linear_desc;
 

@@ -47,6 +47,7 @@ EXPORTS = (
 )
 NTS_TP_LEVELS = 4
 NTS_SPLIT_OUT, NTS_SPLIT_IN = 0, 1
+NTS_BF16, NTS_F16 = 0, 1
 
 
 class nts_desc(ctypes.Structure):
@@ -64,7 +65,7 @@ class nts_desc(ctypes.Structure):
 class nts_linear_desc(ctypes.Structure):
     _fields_ = [
         ("M", ctypes.c_int32), ("n_out", ctypes.c_int32), ("n_in", ctypes.c_int32), ("tp", ctypes.c_int32),
-        ("rank", ctypes.c_int32), ("split", ctypes.c_int32),
+        ("rank", ctypes.c_int32), ("split", ctypes.c_int32), ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
         ("ldx", ctypes.c_int64), ("ldw", ctypes.c_int64), ("ldy", ctypes.c_int64),
     ]
 
@@ -246,13 +247,14 @@ def nts_run_memcpy_baseline(plan: int, src_layer_ptrs, dst_layer_ptrs, merge_run
     return n.value
 
 
-def _linear_desc(M, n_out, n_in, tp, rank, split, ldx=0, ldw=0, ldy=0) -> nts_linear_desc:
-    return nts_linear_desc(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=rank, split=split, ldx=ldx, ldw=ldw, ldy=ldy)
+def _linear_desc(M, n_out, n_in, tp, rank, split, ldx=0, ldw=0, ldy=0, dtype=0) -> nts_linear_desc:
+    return nts_linear_desc(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=rank, split=split, dtype=dtype,
+                           ldx=ldx, ldw=ldw, ldy=ldy)
 
 
 def nts_shard_linear_workspace(*, M: int, n_out: int, n_in: int, tp: int, rank: int, split: int,
-                               ldx: int = 0, ldw: int = 0, ldy: int = 0) -> int:
-    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy)
+                               ldx: int = 0, ldw: int = 0, ldy: int = 0, dtype: int = 0) -> int:
+    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy, dtype)
     n = ctypes.c_size_t(0)
     st = _lib.nts_shard_linear_workspace(ctypes.byref(d), ctypes.byref(n))
     if st != NTS_OK:
@@ -261,9 +263,9 @@ def nts_shard_linear_workspace(*, M: int, n_out: int, n_in: int, tp: int, rank: 
 
 
 def nts_shard_linear(ctx: int, X: int, W_full: int, Y: int, *, M: int, n_out: int, n_in: int, tp: int,
-                     rank: int, split: int, ldx: int = 0, ldw: int = 0, ldy: int = 0,
+                     rank: int, split: int, ldx: int = 0, ldw: int = 0, ldy: int = 0, dtype: int = 0,
                      workspace: int = 0, workspace_bytes: int = 0, hip_stream: int = 0) -> None:
-    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy)
+    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy, dtype)
     _check(_lib.nts_shard_linear(ctx, ctypes.byref(d), X, W_full, Y, workspace, workspace_bytes, hip_stream), ctx)
 
 

@@ -624,6 +624,7 @@ int linear_geom(const nts_linear_desc *d, LinearGeom *g)
 {
     if (!d || d->M < 1 || d->n_out < 1 || d->n_in < 1 || d->tp < 1 || d->rank < 0 || d->rank >= d->tp) return NTS_EINVAL;
     if (d->split != NTS_SPLIT_OUT && d->split != NTS_SPLIT_IN) return NTS_EINVAL;
+    if (d->dtype != NTS_BF16 && d->dtype != NTS_F16) return NTS_EINVAL;
     const int64_t ldw = d->ldw ? d->ldw : d->n_in;
     if (ldw < d->n_in) return NTS_EINVAL;
     if (d->split == NTS_SPLIT_OUT) {
@@ -674,11 +675,11 @@ int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, cons
     if (g.M <= 64) {
         NTS_HIP(ctx, nts_launch_linear_skinny(static_cast<const uint16_t *>(X), g.ldx, A, g.lda,
                                               static_cast<uint16_t *>(Y), g.ldy, static_cast<float *>(workspace),
-                                              g.splits, g.M, g.Nn, g.K, st));
+                                              g.splits, g.M, g.Nn, g.K, d->dtype == NTS_F16, st));
         return NTS_OK;
     }
     NTS_HIP(ctx, nts_launch_linear_tiled(static_cast<const uint16_t *>(X), g.ldx, A, g.lda,
-                                         static_cast<uint16_t *>(Y), g.ldy, g.M, g.Nn, g.K, st));
+                                         static_cast<uint16_t *>(Y), g.ldy, g.M, g.Nn, g.K, d->dtype == NTS_F16, st));
     return NTS_OK;
 }
 

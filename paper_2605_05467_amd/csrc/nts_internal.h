@@ -101,10 +101,10 @@ hipError_t nts_launch_flatten(const int32_t *d_tok_off, const int32_t *d_pg_off,
                               int p, const NtsFlattenSide &src, const NtsFlattenSide &dst,
                               int32_t *d_err, hipStream_t st);
 
-// nts_linear.hip: Y[M][Nn] = X[M][K] . A[Nn][K]^T, bf16 in, fp32 accumulate, bf16 out
+// nts_linear.hip: Y[M][Nn] = X[M][K] . A[Nn][K]^T, bf16 or f16 in, fp32 accumulate, same format out
 int nts_linear_skinny_splits(int M, int Nn, int K);
 hipError_t nts_launch_linear_skinny(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
                                     uint16_t *Y, int64_t ldy, float *part, int splits, int M, int Nn,
-                                    int K, hipStream_t st);
+                                    int K, bool f16, hipStream_t st);
 hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
-                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, hipStream_t st);
+                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, bool f16, hipStream_t st);

@@ -4,7 +4,8 @@
 // a row-parallel shard a column block, so both are a base offset plus the full
 // matrix's row stride, and every kernel here computes
 //     Y[M][Nn] = X[M][K] . A[Nn][K]^T        (A = the shard, row stride lda)
-// with bf16 inputs, fp32 accumulation on the matrix cores and bf16 output.
+// with 16-bit inputs (bfloat16 or float16), fp32 accumulation on the matrix cores and
+// one rounding to the input format.
 //
 // Small batches (M <= 64, decode): the weight shard is read exactly once and
 // the kernel is bound by HBM bandwidth.  A wavefront owns 16 weight rows and a
@@ -37,10 +38,33 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return uint16_t(u >> 16);
 }
 
+__device__ __forceinline__ uint16_t f32_to_f16_rne(float f)
+{
+    const _Float16 h = static_cast<_Float16>(f);      // v_cvt_f16_f32: round to nearest even
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// The two 16-bit element formats: matrix-core instructions and the final rounding.
+struct Bf16 {
+    typedef bf16x8 vec8;
+    static __device__ __forceinline__ f32x4 mfma16(vec8 a, vec8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ f32x16 mfma32(vec8 a, vec8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ uint16_t round(float f) { return f32_to_bf16_rne(f); }
+};
+struct F16 {
+    typedef f16x8 vec8;
+    static __device__ __forceinline__ f32x4 mfma16(vec8 a, vec8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ f32x16 mfma32(vec8 a, vec8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ uint16_t round(float f) { return f32_to_f16_rne(f); }
+};
+
 // MT = number of 16-row batch tiles (M <= 16*MT); RT = 16-row weight tiles per wavefront.
 // A larger RT reuses every staged X chunk and every X fragment for more weight rows, which
 // is what matters once the batch is wide (MT 3..4); RT = 1 keeps more wavefronts in flight.
-template <int MT, int RT>
+template <class E, int MT, int RT>
 __global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
     const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
     uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ part, int M, int Nn, int K,
@@ -97,12 +121,12 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
                 for (int s = 0; s < 2; ++s) {
 #pragma unroll
                     for (int t = 0; t < MT; ++t) {
-                        const bf16x8 xb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(
+                        typedef typename E::vec8 vec8;
+                        const vec8 xb = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(
                             xs + (t * 16 + i) * kLdsRow + (b * 64 + g * 16 + s * 8) * 2));
 #pragma unroll
                         for (int r = 0; r < RT; ++r)
-                            acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                __builtin_bit_cast(bf16x8, wreg[r][2 * b + s]), xb, acc[r][t], 0, 0, 0);
+                            acc[r][t] = E::mfma16(__builtin_bit_cast(vec8, wreg[r][2 * b + s]), xb, acc[r][t]);
                     }
                 }
             }
@@ -125,7 +149,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
                     uint16_t *dst = Y + int64_t(m) * ldy + nb;
 #pragma unroll
                     for (int v = 0; v < 4; ++v)
-                        if (nb + v < Nn) dst[v] = f32_to_bf16_rne(acc[r][t][v]);
+                        if (nb + v < Nn) dst[v] = E::round(acc[r][t][v]);
                 }
             }
         }
@@ -133,6 +157,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
 }
 
 // Y[m][n] = bf16(sum over splits, in split order)
+template <class E>
 __global__ __launch_bounds__(256) void nts_linear_reduce_kernel(const float *__restrict__ part, int splits,
                                                                 int M, int Nn, uint16_t *__restrict__ Y,
                                                                 int64_t ldy)
@@ -141,7 +166,7 @@ __global__ __launch_bounds__(256) void nts_linear_reduce_kernel(const float *__r
     if (idx >= int64_t(M) * Nn) return;
     float s = 0.f;
     for (int k = 0; k < splits; ++k) s += part[int64_t(k) * M * Nn + idx];
-    Y[(idx / Nn) * ldy + idx % Nn] = f32_to_bf16_rne(s);
+    Y[(idx / Nn) * ldy + idx % Nn] = E::round(s);
 }
 
 
@@ -160,8 +185,7 @@ constexpr int kSupM = 4, kSupN = 8;                     // tiles per XCD-residen
 constexpr int kPitch = kTileK * 2 + 16;                 // bytes per LDS row
 constexpr int kTileLds = (kTileM + kTileN) * kPitch;    // 73728 B per buffer, two buffers of dynamic LDS
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
+template <class E>
 __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
     uint16_t *__restrict__ Y, int64_t ldy, int M, int Nn, int K)
@@ -231,23 +255,24 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 #define NTS_LOAD_FRAGS(kk, XF, AF)                                                                     \
     {                                                                                                  \
         _Pragma("unroll") for (int a = 0; a < 4; ++a)                                                  \
-            XF[a] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(                       \
+            XF[a] = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(                       \
                 xs + (wm * 128 + a * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));                   \
         _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                  \
-            AF[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(                       \
+            AF[b] = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(                       \
                 as + (wn * 128 + b * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));                   \
     }
 #define NTS_MFMAS(XF, AF)                                                                              \
     {                                                                                                  \
         _Pragma("unroll") for (int a = 0; a < 4; ++a)                                                  \
             _Pragma("unroll") for (int b = 0; b < 4; ++b)                                              \
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(XF[a], AF[b], acc[a][b], 0, 0, 0); \
+                acc[a][b] = E::mfma32(XF[a], AF[b], acc[a][b]);                                       \
     }
 
     for (int s = 0; s < n_slabs; ++s) {
         const unsigned char *xs = lds + (s & 1) * kTileLds, *as = xs + kTileM * kPitch;
         unsigned char *nx = lds + ((s + 1) & 1) * kTileLds;
-        bf16x8 xf0[4], af0[4], xf1[4], af1[4];
+        typedef typename E::vec8 vec8;
+        vec8 xf0[4], af0[4], xf1[4], af1[4];
         NTS_LOAD_FRAGS(0, xf0, af0)
         NTS_LOAD_FRAGS(1, xf1, af1)
         NTS_MFMAS(xf0, af0)
@@ -287,7 +312,7 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + wm * 128 + a * 32 + (v / 4) * 8 + fg * 4 + (v % 4);
-                    if (m < M) Y[int64_t(m) * ldy + n] = f32_to_bf16_rne(acc[a][b][v]);
+                    if (m < M) Y[int64_t(m) * ldy + n] = E::round(acc[a][b][v]);
                 }
             }
         }
@@ -315,7 +340,7 @@ int nts_linear_skinny_splits(int M, int Nn, int K)
 
 hipError_t nts_launch_linear_skinny(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
                                     uint16_t *Y, int64_t ldy, float *part, int splits, int M, int Nn,
-                                    int K, hipStream_t st)
+                                    int K, bool f16, hipStream_t st)
 {
     const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
     const int cps = (n_chunks + splits - 1) / splits;
@@ -323,32 +348,41 @@ hipError_t nts_launch_linear_skinny(const uint16_t *X, int64_t ldx, const uint16
     const dim3 grid((Nn + rows_per_wg - 1) / rows_per_wg, splits), block(kSkinnyWaves * 64);
     float *p = splits > 1 ? part : nullptr;
     const int mt = (M + 15) / 16;
-#define NTS_SK(MT, RT) hipLaunchKernelGGL((nts_linear_skinny_kernel<MT, RT>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps)
-    if (mt == 1) NTS_SK(1, 1);
-    else if (mt == 2) NTS_SK(2, 1);
-    else if (mt == 3) NTS_SK(3, 2);
-    else NTS_SK(4, 2);
+#define NTS_SK(MT, RT)                                                                                              \
+    {                                                                                                               \
+        if (f16) hipLaunchKernelGGL((nts_linear_skinny_kernel<F16, MT, RT>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps); \
+        else hipLaunchKernelGGL((nts_linear_skinny_kernel<Bf16, MT, RT>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps);    \
+    }
+    if (mt == 1) NTS_SK(1, 1)
+    else if (mt == 2) NTS_SK(2, 1)
+    else if (mt == 3) NTS_SK(3, 2)
+    else NTS_SK(4, 2)
 #undef NTS_SK
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits <= 1) return e;
     const int64_t n = int64_t(M) * Nn;
-    hipLaunchKernelGGL(nts_linear_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, splits, M, Nn, Y, ldy);
+    if (f16) hipLaunchKernelGGL(nts_linear_reduce_kernel<F16>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, splits, M, Nn, Y, ldy);
+    else hipLaunchKernelGGL(nts_linear_reduce_kernel<Bf16>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, splits, M, Nn, Y, ldy);
     return hipGetLastError();
 }
 
 hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
-                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, hipStream_t st)
+                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, bool f16, hipStream_t st)
 {
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_tiled_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_tiled_kernel<Bf16>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kTileLds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_tiled_kernel<F16>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kTileLds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int tiles_m = (M + kTileM - 1) / kTileM, tiles_n = (Nn + kTileN - 1) / kTileN;
     const int sups = ((tiles_m + kSupM - 1) / kSupM) * ((tiles_n + kSupN - 1) / kSupN);
     const dim3 grid(unsigned((sups + 7) / 8) * 8u * kSupM * kSupN), block(256);
-    hipLaunchKernelGGL(nts_linear_tiled_kernel, grid, block, 2 * kTileLds, st, X, ldx, A, lda, Y, ldy, M, Nn, K);
+    if (f16) hipLaunchKernelGGL(nts_linear_tiled_kernel<F16>, grid, block, 2 * kTileLds, st, X, ldx, A, lda, Y, ldy, M, Nn, K);
+    else hipLaunchKernelGGL(nts_linear_tiled_kernel<Bf16>, grid, block, 2 * kTileLds, st, X, ldx, A, lda, Y, ldy, M, Nn, K);
     return hipGetLastError();
 }

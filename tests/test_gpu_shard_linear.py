@@ -19,11 +19,12 @@ def env():
     b.nts_free(ctx)
 
 
-def run_case(env, M, n_out, n_in, tp, rank, split, seed=1, pad=0):
+def run_case(env, M, n_out, n_in, tp, rank, split, seed=1, pad=0, dtype="bf16"):
     torch, b, ctx = env
     k = n_in if split == "out" else n_in // tp
     nn = n_out // tp if split == "out" else n_out
-    Xh, Wh = linear_inputs(seed, M, n_out, n_in, x_cols=k)
+    Xh, Wh = linear_inputs(seed, M, n_out, n_in, x_cols=k, dtype=dtype)
+    decode = osl.bf16_to_f64 if dtype == "bf16" else osl.f16_to_f64
     ldx, ldw, ldy = k + pad, n_in + pad, nn + pad
     Xp = np.zeros((M, ldx), np.uint16); Xp[:, :k] = Xh
     Wp = np.zeros((n_out, ldw), np.uint16); Wp[:, :n_in] = Wh
@@ -31,16 +32,17 @@ def run_case(env, M, n_out, n_in, tp, rank, split, seed=1, pad=0):
     Wd = torch.from_numpy(Wp.view(np.int16)).cuda()
     Yd = torch.full((M, ldy), 12345, dtype=torch.int16, device="cuda")
     sp = b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN
-    kw = dict(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=rank, split=sp, ldx=ldx, ldw=ldw, ldy=ldy)
+    kw = dict(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=rank, split=sp, ldx=ldx, ldw=ldw, ldy=ldy,
+              dtype=b.NTS_BF16 if dtype == "bf16" else b.NTS_F16)
     ws_bytes = b.nts_shard_linear_workspace(**kw)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
     b.nts_shard_linear(ctx, Xd.data_ptr(), Wd.data_ptr(), Yd.data_ptr(), workspace=ws.data_ptr(),
                        workspace_bytes=ws_bytes, hip_stream=torch.cuda.current_stream().cuda_stream, **kw)
     torch.cuda.synchronize()
     Yg = Yd.cpu().numpy().view(np.uint16)
-    want, bound = osl.shard_linear(osl.bf16_to_f64(Xh), osl.bf16_to_f64(Wh), tp, rank, split)
-    got = osl.bf16_to_f64(Yg[:, :nn])
-    tol = osl.tolerance(want, bound, k)
+    want, bound = osl.shard_linear(decode(Xh), decode(Wh), tp, rank, split)
+    got = decode(Yg[:, :nn])
+    tol = osl.tolerance(want, bound, k, out_bits=8 if dtype == "bf16" else 11)
     err = np.abs(got - want)
     assert np.all(err <= tol), (float((err / tol).max()), np.unravel_index(np.argmax(err / tol), err.shape))
     if pad:
@@ -98,3 +100,10 @@ def test_large_batches_tile_edges(env, M, split):
 def test_decoder_layer_shapes_prefill_batch(env, layer):
     n_out, n_in, split = LAYERS[layer]
     run_case(env, 1024, n_out, n_in, 2, 1, split, seed=9)
+
+
+@pytest.mark.parametrize("M", [1, 16, 40, 64, 300])
+@pytest.mark.parametrize("split", ["out", "in"])
+def test_float16_elements(env, M, split):
+    run_case(env, M, 208, 1024 + 128, 2, 1, split, seed=M + 300, pad=8, dtype="f16")
+    run_case(env, M, 1024, 2048, 4, 3, split, seed=M + 400, dtype="f16")

@@ -28,15 +28,21 @@ def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
     return (r >> np.uint32(16)).astype(np.uint16)
 
 
-def linear_inputs(seed: int, M: int, n_out: int, n_in: int, x_cols: int | None = None):
+def f32_to_f16_bits(a: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even float32 -> IEEE float16 bit patterns."""
+    return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def linear_inputs(seed: int, M: int, n_out: int, n_in: int, x_cols: int | None = None, dtype: str = "bf16"):
     """X [M][x_cols] uniform in [-2, 2), W [n_out][n_in] uniform in [-0.04, 0.04),
-    both rounded to bfloat16; returned as uint16 arrays."""
+    both rounded to bfloat16 (or float16); returned as uint16 arrays."""
     rng = SplitMix64(seed)
     x_cols = x_cols or n_in
-    X = f32_to_bf16_bits((rng.uniform(M * x_cols) * 4.0 - 2.0).astype(np.float32)).reshape(M, x_cols)
+    f32_to_bf16_bits_ = f32_to_bf16_bits if dtype == "bf16" else f32_to_f16_bits
+    X = f32_to_bf16_bits_((rng.uniform(M * x_cols) * 4.0 - 2.0).astype(np.float32)).reshape(M, x_cols)
     W = np.empty(n_out * n_in, dtype=np.uint16)
     step = 1 << 22
     for s in range(0, W.size, step):
         n = min(step, W.size - s)
-        W[s:s + n] = f32_to_bf16_bits((rng.uniform(n) * 0.08 - 0.04).astype(np.float32))
+        W[s:s + n] = f32_to_bf16_bits_((rng.uniform(n) * 0.08 - 0.04).astype(np.float32))
     return X, W.reshape(n_out, n_in)
