@@ -26,7 +26,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kSkinnyWaves = 4;            // 16 weight rows each
 constexpr int kSkinnyChunk = 256;          // k per LDS refill: four 64-wide blocks
 constexpr int kLdsRow = kSkinnyChunk * 2 + 16;   // bytes per batch row in LDS (padded)
 
@@ -64,8 +63,8 @@ struct F16 {
 // MT = number of 16-row batch tiles (M <= 16*MT); RT = 16-row weight tiles per wavefront.
 // A larger RT reuses every staged X chunk and every X fragment for more weight rows, which
 // is what matters once the batch is wide (MT 3..4); RT = 1 keeps more wavefronts in flight.
-template <class E, int MT, int RT>
-__global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
+template <class E, int MT, int RT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void nts_linear_skinny_kernel(
     const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
     uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ part, int M, int Nn, int K,
     int chunks_per_split)
@@ -73,7 +72,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
     __shared__ __attribute__((aligned(16))) unsigned char xs[16 * MT * kLdsRow];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int i = lane & 15, g = lane >> 4;
-    const int n0 = (blockIdx.x * kSkinnyWaves + wv) * 16 * RT;     // first weight row of this wavefront
+    const int n0 = (blockIdx.x * WAVES + wv) * 16 * RT;     // first weight row of this wavefront
     const int split = blockIdx.y;
     const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
     const int c_lo = split * chunks_per_split;
@@ -89,24 +88,38 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // weight loads run one chunk ahead of the MFMAs: 2 x 16 B per lane and 64-wide block
+    u32x4 wreg[RT][8], wnext[RT][8];
+#define NTS_LOAD_W(DST, chunk)                                                                        \
+    {                                                                                                 \
+        const int k0_ = (chunk) * kSkinnyChunk;                                                       \
+        const int nblk_ = min(4, (K - k0_) / 64);                                                     \
+        _Pragma("unroll") for (int r = 0; r < RT; ++r)                                                \
+            _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                           \
+                if (b < nblk_) {                                                                      \
+                    const unsigned char *p = arow[r] + (int64_t(k0_) + b * 64 + g * 16) * 2;          \
+                    DST[r][2 * b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));   \
+                    DST[r][2 * b + 1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + 16)); \
+                }                                                                                     \
+            }                                                                                         \
+    }
+    constexpr bool kAhead = RT == 1;        // with two row tiles the second register set costs occupancy
+    if (kAhead && c_lo < c_hi) NTS_LOAD_W(wnext, c_lo)
     for (int c = c_lo; c < c_hi; ++c) {
         const int k0 = c * kSkinnyChunk;
         const int nblk = min(4, (K - k0) / 64);                     // K is a multiple of 64
-        // weight loads first: 2 x 16 B per 64-wide block, all in flight while X is staged
-        u32x4 wreg[RT][8];
+        if (kAhead) {
 #pragma unroll
-        for (int r = 0; r < RT; ++r)
+            for (int r = 0; r < RT; ++r)
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                if (b < nblk) {
-                    const unsigned char *p = arow[r] + (int64_t(k0) + b * 64 + g * 16) * 2;
-                    wreg[r][2 * b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-                    wreg[r][2 * b + 1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + 16));
-                }
-            }
+                for (int q = 0; q < 8; ++q) wreg[r][q] = wnext[r][q];
+            if (c + 1 < c_hi) NTS_LOAD_W(wnext, c + 1)
+        } else {
+            NTS_LOAD_W(wreg, c)
+        }
         __syncthreads();                                            // previous chunk's LDS reads are done
         // stage X[0:16*MT][k0 : k0+256] (rows >= M and k >= K as zeros)
-        for (int v = threadIdx.x; v < 16 * MT * (kSkinnyChunk / 8); v += kSkinnyWaves * 64) {
+        for (int v = threadIdx.x; v < 16 * MT * (kSkinnyChunk / 8); v += WAVES * 64) {
             const int r = v / (kSkinnyChunk / 8), kv = v % (kSkinnyChunk / 8);
             u32x4 x = {0u, 0u, 0u, 0u};
             if (r < M && k0 + kv * 8 < K)
@@ -156,7 +169,9 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void nts_linear_skinny_kernel(
     }
 }
 
-// Y[m][n] = bf16(sum over splits, in split order)
+#undef NTS_LOAD_W
+
+// Y[m][n] = sum over splits, in split order, rounded once
 template <class E>
 __global__ __launch_bounds__(256) void nts_linear_reduce_kernel(const float *__restrict__ part, int splits,
                                                                 int M, int Nn, uint16_t *__restrict__ Y,
@@ -321,6 +336,7 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 }  // namespace
 
 static int skinny_row_tiles(int M) { return M > 32 ? 2 : 1; }
+static int skinny_waves(int) { return 4; }   // 8 wavefronts per workgroup measured slower for wide batches
 
 int nts_linear_skinny_splits(int M, int Nn, int K)
 {
@@ -344,19 +360,19 @@ hipError_t nts_launch_linear_skinny(const uint16_t *X, int64_t ldx, const uint16
 {
     const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
     const int cps = (n_chunks + splits - 1) / splits;
-    const int rows_per_wg = 16 * skinny_row_tiles(M) * kSkinnyWaves;
-    const dim3 grid((Nn + rows_per_wg - 1) / rows_per_wg, splits), block(kSkinnyWaves * 64);
+    const int rows_per_wg = 16 * skinny_row_tiles(M) * skinny_waves(M);
+    const dim3 grid((Nn + rows_per_wg - 1) / rows_per_wg, splits), block(skinny_waves(M) * 64);
     float *p = splits > 1 ? part : nullptr;
     const int mt = (M + 15) / 16;
-#define NTS_SK(MT, RT)                                                                                              \
+#define NTS_SK(MT, RT, WV)                                                                                            \
     {                                                                                                               \
-        if (f16) hipLaunchKernelGGL((nts_linear_skinny_kernel<F16, MT, RT>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps); \
-        else hipLaunchKernelGGL((nts_linear_skinny_kernel<Bf16, MT, RT>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps);    \
+        if (f16) hipLaunchKernelGGL((nts_linear_skinny_kernel<F16, MT, RT, WV>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps); \
+        else hipLaunchKernelGGL((nts_linear_skinny_kernel<Bf16, MT, RT, WV>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps);    \
     }
-    if (mt == 1) NTS_SK(1, 1)
-    else if (mt == 2) NTS_SK(2, 1)
-    else if (mt == 3) NTS_SK(3, 2)
-    else NTS_SK(4, 2)
+    if (mt == 1) NTS_SK(1, 1, 4)
+    else if (mt == 2) NTS_SK(2, 1, 4)
+    else if (mt == 3) NTS_SK(3, 2, 4)
+    else NTS_SK(4, 2, 4)
 #undef NTS_SK
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits <= 1) return e;
