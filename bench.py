@@ -61,6 +61,8 @@ def parse_args():
     ap.add_argument("--workload", default="c5", choices=sorted(WORKLOAD_DESC))
     ap.add_argument("--staging-mib", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-batch", action="store_true",
+                    help="workloads with several pairs: one nts_run_migrate per pair instead of one batch call")
     ap.add_argument("--copy-calibration", action="store_true")
     ap.add_argument("--linear", action="store_true",
                     help="TP-shard-selecting linear layer (Sec. 3.2.1): decode and prefill batches of the "
@@ -90,14 +92,19 @@ class Pair:
         self.sp = b.layer_ptrs(self.src.data_ptr(), sh.L, case.S_src * case.Hs * sh.D * sh.e)
         self.dp = b.layer_ptrs(self.dst.data_ptr(), sh.L, case.S_dst * case.Hd * sh.D * sh.e)
 
-    def step(self, ctx, staging, staging_bytes, hip_stream, ev=None):
-        """route + plan + migrate + plan_free; returns the plan's info."""
+    def plan(self, ctx, staging_bytes):
+        """route + plan for this pair."""
         c, b, sh = self.case, self.b, self.case.shape
         so, do, w = b.nts_route(sh.H, c.Ns, c.rs, c.Nd, c.rd)
-        plan = b.nts_plan_create(ctx, L=sh.L, D=sh.D, elem_bytes=sh.e, page_size=c.p, Hs=c.Hs, Hd=c.Hd,
+        return b.nts_plan_create(ctx, L=sh.L, D=sh.D, elem_bytes=sh.e, page_size=c.p, Hs=c.Hs, Hd=c.Hd,
                                  src_head_off=so, dst_head_off=do, w=w, S_src=c.S_src, S_dst=c.S_dst,
                                  ctx_len=c.ctx_len, src_pages=c.src_pages, dst_pages=c.dst_pages,
                                  staging_bytes=staging_bytes, flags=b.NTS_VALIDATE_UNIQUE_DST)
+
+    def step(self, ctx, staging, staging_bytes, hip_stream, ev=None):
+        """route + plan + migrate + plan_free; returns the plan's info."""
+        b = self.b
+        plan = self.plan(ctx, staging_bytes)
         info = b.nts_plan_info(plan)
         if ev is not None:
             ev[0].record()
@@ -344,17 +351,29 @@ def main():
         pairs.append(pr)
     torch.cuda.synchronize()
 
+    batch = len(pairs) > 1 and not args.no_batch
+
     def one_step(evs=None):
-        infos = []
-        for i, pr in enumerate(pairs):
-            infos.append(pr.step(ctx, staging, staging_bytes, stream, None if evs is None else evs[i]))
+        if not batch:
+            return [pr.step(ctx, staging, staging_bytes, stream, None if evs is None else evs[i])
+                    for i, pr in enumerate(pairs)]
+        # several pairs: plan them all, then ONE pipeline through the two staging buffers
+        plans = [pr.plan(ctx, staging_bytes) for pr in pairs]
+        infos = [b.nts_plan_info(p) for p in plans]
+        if evs is not None:
+            evs[0][0].record()
+        b.nts_run_migrate_batch(plans, [pr.sp for pr in pairs], [pr.dp for pr in pairs], staging.data_ptr(), stream)
+        if evs is not None:
+            evs[0][1].record()
+        for p in plans:
+            b.nts_plan_free(p)
         return infos
 
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
-    evs = [[[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in pairs]
-           for _ in range(args.steps)]
+    evs = [[[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)]
+            for _ in (pairs[:1] if batch else pairs)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
@@ -366,7 +385,8 @@ def main():
     F = sum(i.F for i in infos)
     X = sum(i.X for i in infos)
     T = sum(i.T for i in infos)
-    launches = sum(i.n_chunks + 1 for i in infos)
+    # a batch chains the pairs' chunks: one launch per chunk plus one to drain the pipeline
+    launches = sum(i.n_chunks for i in infos) + 1 if batch else sum(i.n_chunks + 1 for i in infos)
     kernel_ms = sum(e[0].elapsed_time(e[1]) for step in evs for e in step) / args.steps
     # algorithmic HBM bytes: each payload byte is read from the pool and written to staging
     # by the pack half, read from staging and written to the pool by the unpack half
@@ -385,7 +405,8 @@ def main():
         "config": {"workload": f"{args.workload}: {WORKLOAD_DESC[args.workload]}",
                    "tokens": T, "fragments": F, "fragment_bytes": infos[0].frag_bytes,
                    "payload_bytes": X, "staging_bytes_each": infos[0].chunk_bytes,
-                   "stage_launches_per_step": launches, "pairs": len(pairs)},
+                   "stage_launches_per_step": launches, "pairs": len(pairs),
+                   "pairs_run_as": "one batch (nts_run_migrate_batch)" if batch else "one call per pair"},
         "tokens_per_s": T / (ms_per_step * 1e-3),
         "payload_GBps": X / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "kernel": "nts_stage_kernel<16> (pack chunk k || unpack chunk k-1)",

@@ -190,6 +190,29 @@ int nts_run_migrate(nts_plan *plan, const void *const *src_layer_ptrs,
                     void *const *dst_layer_ptrs, void *staging, void *hip_stream);
 
 /*
+ * Several (source, destination) pairs as ONE pipeline.  A TP switch moves KV
+ * from every GPU of the old group to every GPU of the new one whose head
+ * interval meets its own (Sec. 3.2.2: GPU 1 sends heads to GPU 2, GPU 3 to GPUs
+ * 1 and 2, and so on), so a switch is a list of pairs, each with its own plan.
+ * The chunks of plans[0], plans[1], ... form one chunk sequence through the two
+ * staging buffers: stage g packs chunk g of that sequence and unpacks chunk
+ * g-1, so the last unpack of a pair shares a launch with the first pack of the
+ * next pair and short pairs do not drain the pipeline.  The result equals
+ * nts_run_migrate on each plan in turn.
+ *   plans           host array of n plans of one context (zero-token plans are skipped)
+ *   src_layer_ptrs  host array of n host arrays of 2L device pointers (plan i's source pool)
+ *   dst_layer_ptrs  likewise, plan i's destination pool; several plans may share a pool
+ *   staging         device, 2 * (largest chunk_bytes among the plans)
+ * Every plan reads its source pool as it was before the call: NTS_EALIAS if any
+ * plan's destination layer range overlaps any plan's source layer range or the
+ * staging area.  Destinations of different plans that overlap each other are
+ * written in plan order.  NTS_EINVAL for n < 0, null entries or plans of
+ * different contexts.  Enqueues only; no allocation on the device.
+ */
+int nts_run_migrate_batch(int n, nts_plan *const *plans, const void *const *const *src_layer_ptrs,
+                          void *const *const *dst_layer_ptrs, void *staging, void *hip_stream);
+
+/*
  * The same migration as one kernel from pool to pool, never forming the stream:
  * dst[l][c][dslot[j]][dst_head_off+h][x] = src[l][c][sslot[j]][src_head_off+h][x].
  * Within one address space this is what the paper's "sends it directly to the

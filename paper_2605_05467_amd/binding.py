@@ -41,7 +41,7 @@ EXPORTS = (
     "nts_init", "nts_free", "nts_last_error", "nts_strerror", "nts_route",
     "nts_plan_create", "nts_plan_free", "nts_plan_info", "nts_plan_slots",
     "nts_run_pack", "nts_run_pack_chunk", "nts_run_unpack", "nts_run_unpack_chunk",
-    "nts_run_migrate", "nts_run_migrate_direct", "nts_run_memcpy_baseline",
+    "nts_run_migrate", "nts_run_migrate_batch", "nts_run_migrate_direct", "nts_run_memcpy_baseline",
     "nts_shard_linear", "nts_shard_linear_workspace",
     "nts_balanced_block", "nts_goodput_efficiency", "nts_plan_cluster",
 )
@@ -106,6 +106,7 @@ _lib.nts_run_pack_chunk.argtypes = [_vp, _vp, _i64, _vp, _vp]
 _lib.nts_run_unpack.argtypes = [_vp, _vp, _vp, _vp]
 _lib.nts_run_unpack_chunk.argtypes = [_vp, _vp, _i64, _vp, _vp]
 _lib.nts_run_migrate.argtypes = [_vp, _vp, _vp, _vp, _vp]
+_lib.nts_run_migrate_batch.argtypes = [_i, _vp, _vp, _vp, _vp, _vp]
 _lib.nts_run_migrate_direct.argtypes = [_vp, _vp, _vp, _vp]
 _lib.nts_run_memcpy_baseline.argtypes = [_vp, _vp, _vp, _i, _vp, ctypes.POINTER(_i64)]
 _lib.nts_shard_linear_workspace.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(ctypes.c_size_t)]
@@ -233,6 +234,19 @@ def nts_run_unpack_chunk(plan: int, chunk_in: int, k: int, dst_layer_ptrs, hip_s
 
 def nts_run_migrate(plan: int, src_layer_ptrs, dst_layer_ptrs, staging: int, hip_stream: int = 0) -> None:
     _run(_lib.nts_run_migrate(plan, _tab(src_layer_ptrs), _tab(dst_layer_ptrs), staging, hip_stream))
+
+
+def nts_run_migrate_batch(plans, src_layer_ptrs, dst_layer_ptrs, staging: int, hip_stream: int = 0) -> None:
+    """plans: sequence of plan handles; src/dst_layer_ptrs: one pointer table per plan."""
+    n = len(plans)
+    if len(src_layer_ptrs) != n or len(dst_layer_ptrs) != n:
+        raise ValueError("one source and one destination pointer table per plan")
+    stabs = [_tab(t) for t in src_layer_ptrs]   # kept alive until the call returns
+    dtabs = [_tab(t) for t in dst_layer_ptrs]
+    arr = ctypes.c_void_p * n
+    _run(_lib.nts_run_migrate_batch(n, arr(*[int(p) for p in plans]),
+                                    arr(*[ctypes.addressof(t) for t in stabs]),
+                                    arr(*[ctypes.addressof(t) for t in dtabs]), staging, hip_stream))
 
 
 def nts_run_migrate_direct(plan: int, src_layer_ptrs, dst_layer_ptrs, hip_stream: int = 0) -> None:

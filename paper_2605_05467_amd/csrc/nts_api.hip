@@ -2,6 +2,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -541,7 +542,98 @@ int nts_run_migrate(nts_plan *pl, const void *const *src_layer_ptrs, void *const
         int64_t pq = 0, pn = 0, uq = 0, un = 0;
         if (k < pl->n_chunks) chunk_range(pl, k, &pq, &pn);
         if (k >= 1) chunk_range(pl, k - 1, &uq, &un);
-        NTS_HIP(ctx, nts_launch_stage(pl, pq, pn, buf[k & 1], stab, uq, un, buf[(k - 1) & 1], dtab, st));
+        NTS_HIP(ctx, nts_launch_stage(pl, pq, pn, buf[k & 1], stab, pl, uq, un, buf[(k - 1) & 1], dtab, st));
+    }
+    return NTS_OK;
+}
+
+int nts_run_migrate_batch(int n, nts_plan *const *plans, const void *const *const *src_layer_ptrs,
+                          void *const *const *dst_layer_ptrs, void *staging, void *hip_stream)
+{
+    if (n < 0 || (n > 0 && (!plans || !src_layer_ptrs || !dst_layer_ptrs))) return NTS_EINVAL;
+    nts_ctx *ctx = nullptr;
+    for (int i = 0; i < n; ++i) {
+        if (!plans[i]) return ctx ? fail(ctx, NTS_EINVAL, "null plan in batch") : NTS_EINVAL;
+        if (!ctx) ctx = plans[i]->ctx;
+        if (plans[i]->ctx != ctx) return fail(ctx, NTS_EINVAL, "plans of different contexts in one batch");
+    }
+    if (!ctx) return NTS_OK;
+
+    // the pairs that move something, with their pointer tables
+    struct Item {
+        nts_plan *pl;
+        NtsLayerTab stab, dtab;
+    };
+    std::vector<Item> items;
+    struct Range {
+        const char *lo, *hi;
+        int is_dst;
+    };
+    std::vector<Range> ranges;
+    int64_t buf_stride = 0;
+    try {
+        items.reserve(size_t(n));
+        for (int i = 0; i < n; ++i) {
+            nts_plan *pl = plans[i];
+            if (pl->F == 0) continue;
+            items.emplace_back();
+            Item &it = items.back();
+            it.pl = pl;
+            const int rc = check_pools(pl, src_layer_ptrs[i], dst_layer_ptrs[i], it.stab, it.dtab);
+            if (rc != NTS_OK) return rc;
+            const int64_t src_span = pl->S_src * pl->src_stride, dst_span = pl->S_dst * pl->dst_stride;
+            for (int k = 0; k < 2 * pl->L; ++k) {
+                ranges.push_back({it.stab.p[k], it.stab.p[k] + src_span, 0});
+                ranges.push_back({it.dtab.p[k], it.dtab.p[k] + dst_span, 1});
+            }
+            if (pl->chunk_bytes > buf_stride) buf_stride = pl->chunk_bytes;
+        }
+    } catch (...) {
+        return fail(ctx, NTS_ENOMEM, "host allocation failed");
+    }
+    if (items.empty()) return NTS_OK;
+    if (!staging) return fail(ctx, NTS_EINVAL, "null staging area");
+    if (reinterpret_cast<uintptr_t>(staging) % 16u) return fail(ctx, NTS_EINVAL, "staging area misaligned");
+    buf_stride = (buf_stride + 15) / 16 * 16;   // keeps the second buffer aligned for every plan
+    char *buf[2] = {static_cast<char *>(staging), static_cast<char *>(staging) + buf_stride};
+
+    // No destination range may meet a source range of ANY plan, nor the staging area: sort
+    // by start and sweep, remembering how far the sources and the destinations seen so far reach.
+    std::sort(ranges.begin(), ranges.end(), [](const Range &x, const Range &y) { return x.lo < y.lo; });
+    const char *reach[2] = {nullptr, nullptr};
+    for (const Range &r : ranges) {
+        if (reach[1 - r.is_dst] && r.lo < reach[1 - r.is_dst])
+            return fail(ctx, NTS_EALIAS, "a destination pool of the batch overlaps a source pool of the batch");
+        if (overlaps(r.lo, r.hi - r.lo, buf[0], 2 * buf_stride))
+            return fail(ctx, NTS_EALIAS, "staging area overlaps a pool");
+        if (!reach[r.is_dst] || r.hi > reach[r.is_dst]) reach[r.is_dst] = r.hi;
+    }
+
+    DeviceGuard guard(ctx->device);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    for (Item &it : items) note_stream(it.pl, st);
+    // The chunks of all pairs form one sequence g = 0, 1, ...; stage g packs chunk g into
+    // buffer g&1 and unpacks chunk g-1 from the other buffer, across pair boundaries too.
+    size_t pi = 0;          // pair and chunk being packed
+    int64_t pk = 0;
+    const Item *ui = nullptr;   // pair and chunk packed by the previous stage
+    int64_t uk = 0;
+    for (int64_t g = 0;; ++g) {
+        const Item *ai = pi < items.size() ? &items[pi] : nullptr;
+        if (!ai && !ui) break;
+        int64_t pq = 0, pn = 0, uq = 0, un = 0;
+        if (ai) chunk_range(ai->pl, pk, &pq, &pn);
+        if (ui) chunk_range(ui->pl, uk, &uq, &un);
+        const Item *any = ai ? ai : ui;
+        NTS_HIP(ctx, nts_launch_stage(ai ? ai->pl : nullptr, pq, pn, buf[g & 1], ai ? ai->stab : any->stab,
+                                      ui ? ui->pl : nullptr, uq, un, buf[(g - 1) & 1],
+                                      ui ? ui->dtab : any->dtab, st));
+        ui = ai;
+        uk = pk;
+        if (ai && ++pk == ai->pl->n_chunks) {
+            ++pi;
+            pk = 0;
+        }
     }
     return NTS_OK;
 }

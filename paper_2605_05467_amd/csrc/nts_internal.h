@@ -26,7 +26,7 @@ struct nts_ctx {
         bool pending = false;           // ev was recorded and has not been waited on by `aux`
         uint64_t age = 0;               // order of freeing
     };
-    static constexpr int kSpares = 3;
+    static constexpr int kSpares = 16;          // a TP switch of eight GPUs has up to 15 pairs per GPU
     Spare spare[kSpares];
     uint64_t free_count = 0;
     int n_plans = 0;
@@ -81,11 +81,12 @@ enum NtsMoveMode { NTS_MOVE_PACK = 0, NTS_MOVE_UNPACK = 1 };
 int64_t nts_max_frags_per_launch(const nts_plan *pl);
 hipError_t nts_launch_move(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int64_t n_frag,
                            const NtsLayerTab &tab, char *linear, hipStream_t st);
-// pack fragments [pack_q0, +pack_n) into pack_buf and unpack [unpack_q0, +unpack_n)
-// from unpack_buf in one launch (either count may be zero)
-hipError_t nts_launch_stage(const nts_plan *pl, int64_t pack_q0, int64_t pack_n, char *pack_buf,
-                            const NtsLayerTab &stab, int64_t unpack_q0, int64_t unpack_n,
-                            char *unpack_buf, const NtsLayerTab &dtab, hipStream_t st);
+// pack fragments [pack_q0, +pack_n) of plan `ppl` into pack_buf and unpack fragments
+// [unpack_q0, +unpack_n) of plan `upl` from unpack_buf in one launch (either count may be
+// zero, and then its plan may be null; the two plans may differ)
+hipError_t nts_launch_stage(const nts_plan *ppl, int64_t pack_q0, int64_t pack_n, char *pack_buf,
+                            const NtsLayerTab &stab, const nts_plan *upl, int64_t unpack_q0,
+                            int64_t unpack_n, char *unpack_buf, const NtsLayerTab &dtab, hipStream_t st);
 // pool-to-pool move of fragments [q0, q0 + n_frag) with no stream in between
 hipError_t nts_launch_direct(const nts_plan *pl, int64_t q0, int64_t n_frag, const NtsLayerTab &stab,
                              const NtsLayerTab &dtab, hipStream_t st);

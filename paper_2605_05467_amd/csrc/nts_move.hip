@@ -211,18 +211,26 @@ hipError_t nts_launch_move(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int
     return hipGetLastError();
 }
 
-hipError_t nts_launch_stage(const nts_plan *pl, int64_t pack_q0, int64_t pack_n, char *pack_buf,
-                            const NtsLayerTab &stab, int64_t unpack_q0, int64_t unpack_n,
-                            char *unpack_buf, const NtsLayerTab &dtab, hipStream_t st)
+hipError_t nts_launch_stage(const nts_plan *ppl, int64_t pack_q0, int64_t pack_n, char *pack_buf,
+                            const NtsLayerTab &stab, const nts_plan *upl, int64_t unpack_q0,
+                            int64_t unpack_n, char *unpack_buf, const NtsLayerTab &dtab, hipStream_t st)
 {
-    NtsMoveJob a, b;
-    nts_make_job(NTS_MOVE_PACK, pl, pack_q0, pack_n > 0 ? pack_n : 0, pack_buf, &a);
-    nts_make_job(NTS_MOVE_UNPACK, pl, unpack_q0, unpack_n > 0 ? unpack_n : 0, unpack_buf, &b);
+    const bool has_a = ppl && pack_n > 0, has_b = upl && unpack_n > 0;
+    if (!has_a && !has_b) return hipSuccess;
+    if (has_a && has_b && ppl->vec != upl->vec) {
+        // two plans whose vector widths differ cannot share the kernel instance
+        const hipError_t e = nts_launch_move(NTS_MOVE_UNPACK, upl, unpack_q0, unpack_n, dtab, unpack_buf, st);
+        if (e != hipSuccess) return e;
+        return nts_launch_move(NTS_MOVE_PACK, ppl, pack_q0, pack_n, stab, pack_buf, st);
+    }
+    NtsMoveJob a = {}, b = {};   // an absent side is a job of zero vectors
+    if (has_a) nts_make_job(NTS_MOVE_PACK, ppl, pack_q0, pack_n, pack_buf, &a);
+    if (has_b) nts_make_job(NTS_MOVE_UNPACK, upl, unpack_q0, unpack_n, unpack_buf, &b);
+    const int vec = has_a ? ppl->vec : upl->vec;
     const uint32_t wg_a = (a.n_vec + kThreads - 1) / kThreads, wg_b = (b.n_vec + kThreads - 1) / kThreads;
-    if (wg_a + wg_b == 0) return hipSuccess;
     const dim3 grid(wg_a + wg_b), block(kThreads);
-    if (pl->vec == 16) hipLaunchKernelGGL((nts_stage_kernel<16>), grid, block, 0, st, a, stab, b, dtab, wg_a, wg_b);
-    else if (pl->vec == 8) hipLaunchKernelGGL((nts_stage_kernel<8>), grid, block, 0, st, a, stab, b, dtab, wg_a, wg_b);
+    if (vec == 16) hipLaunchKernelGGL((nts_stage_kernel<16>), grid, block, 0, st, a, stab, b, dtab, wg_a, wg_b);
+    else if (vec == 8) hipLaunchKernelGGL((nts_stage_kernel<8>), grid, block, 0, st, a, stab, b, dtab, wg_a, wg_b);
     else hipLaunchKernelGGL((nts_stage_kernel<4>), grid, block, 0, st, a, stab, b, dtab, wg_a, wg_b);
     return hipGetLastError();
 }
