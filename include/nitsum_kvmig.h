@@ -20,7 +20,7 @@
  *   - run calls only enqueue work on the given HIP stream (a hipStream_t passed
  *     as void*, NULL = the default stream), allocate nothing and never block
  *     the host.  A context and its plans may be used by one host thread at a time.
- *     A context keeps a pinned host buffer and up to three spare device blocks between
+ *     A context keeps a pinned host buffer and up to sixteen spare device blocks between
  *     plans so that planning in a steady loop allocates nothing.
  *
  * Data layout (the paper fixes none; this is the layout of this library)
@@ -87,7 +87,7 @@ typedef struct nts_desc {
     const int32_t *ctx_len;   /* host [n_req]: tokens of each request, >= 0 */
     const int32_t *src_pages; /* host: page ids, CSR by request, ceil(ctx_len/p) each */
     const int32_t *dst_pages; /* host: same shape; destination pages must be distinct */
-    int64_t src_token_stride; /* bytes between source slots; 0 = Hs*D*elem_bytes */
+    int64_t src_token_stride; /* bytes between source slots; 0 = Hs*D*elem_bytes; at most 2^30 */
     int64_t dst_token_stride; /* bytes between destination slots; 0 = Hd*D*elem_bytes */
     int64_t staging_bytes;    /* B: size of ONE staging buffer; 0 = 64 MiB.  Rounded
                                  down to a whole number of fragments (at least one). */
@@ -141,7 +141,8 @@ int nts_route(int H, int Ns, int rs, int Nd, int rd,
  * call synchronises with the device.  Errors: NTS_EINVAL (null pointers, w <= 0,
  * head slice outside Hs / Hd, elem_bytes not 1/2/4, fragment size or strides
  * not a multiple of 4 bytes, L > NTS_MAX_LAYERS, negative ctx_len, more than
- * 2^31-1 tokens), NTS_ERANGE, NTS_EDUP (only with NTS_VALIDATE_UNIQUE_DST),
+ * 2^31-1 tokens, D > 2^20, more than 65536 heads, a token stride above 2^30
+ * bytes), NTS_ERANGE, NTS_EDUP (only with NTS_VALIDATE_UNIQUE_DST),
  * NTS_ENOMEM, NTS_EHIP.  A plan with zero tokens is legal; its run calls do nothing.
  */
 int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out);

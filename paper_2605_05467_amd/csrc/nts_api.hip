@@ -167,6 +167,8 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     if (d->L <= 0 || d->L > NTS_MAX_LAYERS) return fail(ctx, NTS_EINVAL, "L outside 1..NTS_MAX_LAYERS");
     if (d->D <= 0 || d->page_size <= 0 || d->Hs <= 0 || d->Hd <= 0)
         return fail(ctx, NTS_EINVAL, "D, page_size, Hs and Hd must be positive");
+    if (d->D > (1 << 20) || d->Hs > (1 << 16) || d->Hd > (1 << 16))
+        return fail(ctx, NTS_EINVAL, "D above 2^20 or more than 65536 heads");
     if (d->elem_bytes != 1 && d->elem_bytes != 2 && d->elem_bytes != 4)
         return fail(ctx, NTS_EINVAL, "elem_bytes must be 1, 2 or 4");
     if (d->w <= 0) return fail(ctx, NTS_EINVAL, "w must be positive");
@@ -188,6 +190,9 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     const int64_t dst_stride = d->dst_token_stride ? d->dst_token_stride : dst_row;
     if (src_stride < src_row || dst_stride < dst_row)
         return fail(ctx, NTS_EINVAL, "token stride smaller than a token row");
+    // keeps slot * stride, the pool spans and the payload size inside 64 bits
+    if (src_stride > (int64_t(1) << 30) || dst_stride > (int64_t(1) << 30))
+        return fail(ctx, NTS_EINVAL, "token stride above 1 GiB");
     const int64_t so = head_bytes * d->src_head_off, dof = head_bytes * d->dst_head_off;
     int vec = 16;
     while (vec >= 4 && (frag % vec || src_stride % vec || dst_stride % vec || so % vec || dof % vec)) vec >>= 1;
@@ -226,6 +231,10 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     pl->T = T;
     pl->F = T * 2 * d->L;
     pl->frag_bytes = frag;
+    if (pl->F > INT64_MAX / frag) {
+        delete pl;
+        return fail(ctx, NTS_EINVAL, "payload size does not fit 64 bits");
+    }
     pl->X = pl->F * frag;
     pl->vec = vec;
     int64_t B = d->staging_bytes > 0 ? d->staging_bytes : int64_t(NTS_DEFAULT_STAGING_BYTES);

@@ -251,6 +251,11 @@ def test_error_paths_and_empty_plans(b, ctx, torch):
     assert status(ctx_len=[3, -2]) == b.NTS_EINVAL
     assert status(page_size=3) == b.NTS_EINVAL                        # pool not a multiple of p
     assert status(D=1, elem_bytes=1, w=1, src_head_off=0) == b.NTS_EINVAL   # 1-byte fragments
+    assert status(src_token_stride=(1 << 30) + 16) == b.NTS_EINVAL    # sizes that could leave 64 bits
+    assert status(dst_token_stride=1 << 31) == b.NTS_EINVAL
+    assert status(D=(1 << 20) + 4) == b.NTS_EINVAL
+    assert status(Hs=(1 << 16) + 8) == b.NTS_EINVAL
+    assert status(src_token_stride=8 * 128 * 2 + 64) == 0             # padded rows are fine
     # zero tokens: legal, run calls are no-ops
     plan = b.nts_plan_create(ctx, **{**kw, "ctx_len": [0, 0], "src_pages": [], "dst_pages": []})
     info = b.nts_plan_info(plan)
