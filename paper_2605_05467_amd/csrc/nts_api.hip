@@ -718,7 +718,8 @@ namespace {
 struct LinearGeom {
     int M, Nn, K;
     int64_t ldx, lda, ldy, a_off;   // a_off: element offset of the shard inside W
-    int splits;                      // skinny path: K splits (0 on the tiled path)
+    bool tiled;                      // 256 x 256 tiled kernel, else the weight-streaming kernel
+    NtsStreamCfg cfg;                // streaming kernel: tile, prefetch depth, K splits
 };
 
 int linear_geom(const nts_linear_desc *d, LinearGeom *g)
@@ -748,7 +749,9 @@ int linear_geom(const nts_linear_desc *d, LinearGeom *g)
     // the tiled kernel addresses operand rows with 32-bit counts of 16-byte units
     const int64_t lim = int64_t(1) << 35;
     if (int64_t(g->M) * g->ldx >= lim || int64_t(g->Nn) * g->lda >= lim) return NTS_EINVAL;
-    g->splits = g->M <= 64 ? nts_linear_skinny_splits(g->M, g->Nn, g->K) : 0;
+    g->tiled = nts_linear_use_tiled(g->M, g->Nn);
+    g->cfg = nts_linear_stream_config(g->M, g->Nn, g->K);
+    if (g->tiled) g->cfg.splits = 1;
     return NTS_OK;
 }
 }  // namespace
@@ -757,7 +760,7 @@ int nts_shard_linear_workspace(const nts_linear_desc *d, size_t *bytes)
 {
     LinearGeom g;
     if (!bytes || linear_geom(d, &g) != NTS_OK) return NTS_EINVAL;
-    *bytes = g.splits > 1 ? size_t(g.splits) * g.M * g.Nn * sizeof(float) : 0;
+    *bytes = g.cfg.splits > 1 ? size_t(g.cfg.splits) * g.M * g.Nn * sizeof(float) : 0;
     return NTS_OK;
 }
 
@@ -770,16 +773,16 @@ int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, cons
     if (!X || !W_full || !Y) return fail(ctx, NTS_EINVAL, "null operand");
     if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W_full) | reinterpret_cast<uintptr_t>(Y)) % 16)
         return fail(ctx, NTS_EINVAL, "operands must be 16-byte aligned");
-    const size_t need = g.splits > 1 ? size_t(g.splits) * g.M * g.Nn * sizeof(float) : 0;
+    const size_t need = g.cfg.splits > 1 ? size_t(g.cfg.splits) * g.M * g.Nn * sizeof(float) : 0;
     if (need && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16))
         return fail(ctx, NTS_EINVAL, "workspace missing, misaligned or too small");
     DeviceGuard guard(ctx->device);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const uint16_t *A = static_cast<const uint16_t *>(W_full) + g.a_off;
-    if (g.M <= 64) {
-        NTS_HIP(ctx, nts_launch_linear_skinny(static_cast<const uint16_t *>(X), g.ldx, A, g.lda,
+    if (!g.tiled) {
+        NTS_HIP(ctx, nts_launch_linear_stream(static_cast<const uint16_t *>(X), g.ldx, A, g.lda,
                                               static_cast<uint16_t *>(Y), g.ldy, static_cast<float *>(workspace),
-                                              g.splits, g.M, g.Nn, g.K, d->dtype == NTS_F16, st));
+                                              g.cfg, g.M, g.Nn, g.K, d->dtype == NTS_F16, st));
         return NTS_OK;
     }
     NTS_HIP(ctx, nts_launch_linear_tiled(static_cast<const uint16_t *>(X), g.ldx, A, g.lda,

@@ -103,9 +103,15 @@ hipError_t nts_launch_flatten(const int32_t *d_tok_off, const int32_t *d_pg_off,
                               int32_t *d_err, hipStream_t st);
 
 // nts_linear.hip: Y[M][Nn] = X[M][K] . A[Nn][K]^T, bf16 or f16 in, fp32 accumulate, same format out
-int nts_linear_skinny_splits(int M, int Nn, int K);
-hipError_t nts_launch_linear_skinny(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
-                                    uint16_t *Y, int64_t ldy, float *part, int splits, int M, int Nn,
-                                    int K, bool f16, hipStream_t st);
+struct NtsStreamCfg {
+    int mt = 1;       // batch rows per workgroup / 32
+    int nsets = 4;    // weight register sets in rotation (nsets - 1 slabs in flight per wavefront)
+    int splits = 1;   // K splits (> 1: fp32 partial sums in the workspace, reduced in split order)
+};
+NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K);
+bool nts_linear_use_tiled(int M, int Nn);
+hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda, uint16_t *Y,
+                                    int64_t ldy, float *part, const NtsStreamCfg &c, int M, int Nn, int K,
+                                    bool f16, hipStream_t st);
 hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
                                    uint16_t *Y, int64_t ldy, int M, int Nn, int K, bool f16, hipStream_t st);

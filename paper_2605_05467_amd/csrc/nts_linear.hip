@@ -7,15 +7,10 @@
 // with 16-bit inputs (bfloat16 or float16), fp32 accumulation on the matrix cores and
 // one rounding to the input format.
 //
-// Small batches (M <= 64, decode): the weight shard is read exactly once and
-// the kernel is bound by HBM bandwidth.  A wavefront owns 16 weight rows and a
-// K slice; weight rows are the A operand of v_mfma_f32_16x16x32_bf16 and go
-// from global memory straight into registers (no LDS: no reuse), the batch is
-// the B operand and sits in LDS.  Lane (i = lane%16, g = lane/16) of the MFMA
-// holds 8 consecutive k of row i; which k they are is free as long as both
-// operands agree, so inside a 64-wide k block lane group g takes k = 16g+8s+e
-// for the block's two MFMAs s = 0,1: each lane then reads 32 contiguous bytes
-// and the four lanes of a row cover one full 128-byte line.
+// Two kernels: a weight-streaming kernel for batches up to a few hundred rows
+// (decode and short prefill chunks; bound by reading the shard once from HBM)
+// and a 256 x 256 tiled kernel for long prefill batches (bound by the matrix
+// cores).  Both are described where they are defined.
 #include <algorithm>
 
 #include "nts_internal.h"
@@ -25,9 +20,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kSkinnyChunk = 256;          // k per LDS refill: four 64-wide blocks
-constexpr int kLdsRow = kSkinnyChunk * 2 + 16;   // bytes per batch row in LDS (padded)
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
@@ -60,117 +52,6 @@ struct F16 {
     static __device__ __forceinline__ uint16_t round(float f) { return f32_to_f16_rne(f); }
 };
 
-// MT = number of 16-row batch tiles (M <= 16*MT); RT = 16-row weight tiles per wavefront.
-// A larger RT reuses every staged X chunk and every X fragment for more weight rows, which
-// is what matters once the batch is wide (MT 3..4); RT = 1 keeps more wavefronts in flight.
-template <class E, int MT, int RT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void nts_linear_skinny_kernel(
-    const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
-    uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ part, int M, int Nn, int K,
-    int chunks_per_split)
-{
-    __shared__ __attribute__((aligned(16))) unsigned char xs[16 * MT * kLdsRow];
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int i = lane & 15, g = lane >> 4;
-    const int n0 = (blockIdx.x * WAVES + wv) * 16 * RT;     // first weight row of this wavefront
-    const int split = blockIdx.y;
-    const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
-    const int c_lo = split * chunks_per_split;
-    const int c_hi = min(n_chunks, c_lo + chunks_per_split);
-    const unsigned char *arow[RT];
-#pragma unroll
-    for (int r = 0; r < RT; ++r)                                    // clamp: rows past the end are computed, not stored
-        arow[r] = reinterpret_cast<const unsigned char *>(A + int64_t(min(n0 + r * 16 + i, Nn - 1)) * lda);
-
-    f32x4 acc[RT][MT];
-#pragma unroll
-    for (int r = 0; r < RT; ++r)
-#pragma unroll
-        for (int t = 0; t < MT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // weight loads run one chunk ahead of the MFMAs: 2 x 16 B per lane and 64-wide block
-    u32x4 wreg[RT][8], wnext[RT][8];
-#define NTS_LOAD_W(DST, chunk)                                                                        \
-    {                                                                                                 \
-        const int k0_ = (chunk) * kSkinnyChunk;                                                       \
-        const int nblk_ = min(4, (K - k0_) / 64);                                                     \
-        _Pragma("unroll") for (int r = 0; r < RT; ++r)                                                \
-            _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                           \
-                if (b < nblk_) {                                                                      \
-                    const unsigned char *p = arow[r] + (int64_t(k0_) + b * 64 + g * 16) * 2;          \
-                    DST[r][2 * b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));   \
-                    DST[r][2 * b + 1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + 16)); \
-                }                                                                                     \
-            }                                                                                         \
-    }
-    constexpr bool kAhead = RT == 1;        // with two row tiles the second register set costs occupancy
-    if (kAhead && c_lo < c_hi) NTS_LOAD_W(wnext, c_lo)
-    for (int c = c_lo; c < c_hi; ++c) {
-        const int k0 = c * kSkinnyChunk;
-        const int nblk = min(4, (K - k0) / 64);                     // K is a multiple of 64
-        if (kAhead) {
-#pragma unroll
-            for (int r = 0; r < RT; ++r)
-#pragma unroll
-                for (int q = 0; q < 8; ++q) wreg[r][q] = wnext[r][q];
-            if (c + 1 < c_hi) NTS_LOAD_W(wnext, c + 1)
-        } else {
-            NTS_LOAD_W(wreg, c)
-        }
-        __syncthreads();                                            // previous chunk's LDS reads are done
-        // stage X[0:16*MT][k0 : k0+256] (rows >= M and k >= K as zeros)
-        for (int v = threadIdx.x; v < 16 * MT * (kSkinnyChunk / 8); v += WAVES * 64) {
-            const int r = v / (kSkinnyChunk / 8), kv = v % (kSkinnyChunk / 8);
-            u32x4 x = {0u, 0u, 0u, 0u};
-            if (r < M && k0 + kv * 8 < K)
-                x = *reinterpret_cast<const u32x4 *>(X + int64_t(r) * ldx + k0 + kv * 8);
-            *reinterpret_cast<u32x4 *>(xs + r * kLdsRow + kv * 16) = x;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            if (b < nblk) {
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-#pragma unroll
-                    for (int t = 0; t < MT; ++t) {
-                        typedef typename E::vec8 vec8;
-                        const vec8 xb = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(
-                            xs + (t * 16 + i) * kLdsRow + (b * 64 + g * 16 + s * 8) * 2));
-#pragma unroll
-                        for (int r = 0; r < RT; ++r)
-                            acc[r][t] = E::mfma16(__builtin_bit_cast(vec8, wreg[r][2 * b + s]), xb, acc[r][t]);
-                    }
-                }
-            }
-        }
-    }
-    // D[row = g*4+v][col = i]: weight row n0 + r*16 + g*4 + v, batch row t*16 + i
-#pragma unroll
-    for (int r = 0; r < RT; ++r) {
-        const int nb = n0 + r * 16 + g * 4;
-#pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            const int m = t * 16 + i;
-            if (m < M) {
-                if (part) {
-                    float *dst = part + (int64_t(split) * M + m) * Nn + nb;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        if (nb + v < Nn) dst[v] = acc[r][t][v];
-                } else {
-                    uint16_t *dst = Y + int64_t(m) * ldy + nb;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        if (nb + v < Nn) dst[v] = E::round(acc[r][t][v]);
-                }
-            }
-        }
-    }
-}
-
-#undef NTS_LOAD_W
-
 // Y[m][n] = sum over splits, in split order, rounded once
 template <class E>
 __global__ __launch_bounds__(256) void nts_linear_reduce_kernel(const float *__restrict__ part, int splits,
@@ -184,6 +65,206 @@ __global__ __launch_bounds__(256) void nts_linear_reduce_kernel(const float *__r
     Y[(idx / Nn) * ldy + idx % Nn] = E::round(s);
 }
 
+
+// ---------------------------------------------------------------------------
+// Weight-streaming kernel (decode batches and short prefill chunks): bound by the
+// weight bytes, read exactly once; for wider batches there is also enough matrix-core
+// and LDS work that neither may be wasted.  A workgroup takes 32*MT batch rows and 128*RT weight rows.  Four
+// "consumer" wavefronts each own 32*RT weight rows for all of the batch rows, as
+// MT x RT tiles of v_mfma_f32_32x32x16.  A weight
+// row is used by one wavefront only, so weights go from global memory straight
+// into registers: lane (row = lane%32, g = lane/32) holds k = 32g .. 32g+31 of
+// its row for a 64-wide slab (64 contiguous bytes) and feeds the slab's four
+// MFMA steps s = 0..3 with k = 32g + 8s + e; the batch fragments are read from
+// LDS with the same k, so both operands agree.  The batch slab (32*MT rows x
+// 64 k) is shared by the consumers and is brought into LDS by a fifth,
+// "producer" wavefront.  Splitting the roles matters because a wavefront's
+// loads return in order: a consumer that also fetched batch rows would, each
+// time it waits for them, wait for every weight load issued before them, which
+// caps the weight bytes in flight at two slabs; with ~3 us of loaded HBM latency
+// that is a third of the bandwidth.  Consumers keep NSETS-1 slabs of weights in
+// flight (NSETS register sets used in rotation; the slab loop is unrolled by
+// NSETS so the sets are fixed registers).  K can be split over blockIdx.y (fp32
+// partial sums, reduced in split order by nts_linear_reduce_kernel).
+// Workgroup order: the batch tiles of one weight block run back to back on one
+// XCD, so that block is fetched from HBM once and then served by that XCD's L2.
+
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits for every
+// outstanding global load (its fences cover global memory), which would drain the weight
+// prefetch at every slab.
+__device__ __forceinline__ void nts_lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+constexpr int kStrK = 64;
+constexpr int kStrPitch = kStrK * 2 + 16;          // bytes per batch row in LDS
+constexpr int kStrThreads = 320;                   // four consumers and one producer
+
+template <class E, int MT, int RT, int NSETS>
+__global__ __launch_bounds__(kStrThreads) void nts_linear_stream_kernel(
+    const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
+    uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ part, int M, int Nn, int K,
+    int slabs_per_split, int tiles_m, int blocks_n)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    typedef typename E::vec8 vec8;
+    constexpr int kBuf = 32 * MT * kStrPitch;           // one of three batch-slab buffers
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int by = seq % tiles_m, bx = (seq / tiles_m) * 8 + xcd;
+    if (bx >= blocks_n) return;                         // whole workgroup leaves before any barrier
+    const int m0 = by * 32 * MT;
+    const int split = blockIdx.y;
+    const int n_slabs = K / kStrK;
+    const int s_lo = split * slabs_per_split, s_hi = min(n_slabs, s_lo + slabs_per_split);
+    // Workgroups walk their k range from different starting slabs (and wrap around): rows are
+    // a power-of-two number of bytes apart, so workgroups that all read the same k at the same
+    // time would keep hitting the same few memory channels.
+    const int s_cnt = s_hi - s_lo, s_rot = (bx * 5 + by) % s_cnt;
+#define NTS_STR_PHYS(ss) (s_lo + ((min((ss), s_hi - 1) - s_lo + s_rot) % s_cnt))
+
+    // Slab s lives in LDS buffer s % 3.  During slab period s the producer writes slab s+1
+    // and the consumers read slab s; the one barrier per period (in its middle for the
+    // consumers) publishes slab s+1 and retires slab s-1, so the consumers can read the first
+    // fragments of slab s+1 during the last MFMA step of slab s.
+    if (wv == 4) {
+        // producer: lane moves 16-byte vector (lane & 7) of rows (lane >> 3) + 8 q
+        const int sv = lane & 7, sr = lane >> 3;
+        const u32x4 *xrow[4 * MT];
+#pragma unroll
+        for (int q = 0; q < 4 * MT; ++q)
+            xrow[q] = reinterpret_cast<const u32x4 *>(X + int64_t(min(m0 + sr + 8 * q, M - 1)) * ldx + sv * 8);
+        const int st_off = sr * kStrPitch + sv * 16;
+        // XD register sets: the rows of slab s+1+XD are requested while slab s+1 is written,
+        // so XD round trips overlap (one per slab would cap the slab rate at the loaded L2 latency)
+        constexpr int XD = MT <= 2 ? 4 : (MT <= 4 ? 2 : 1);   // bounded by registers
+        u32x4 xr[XD][4 * MT];
+#define NTS_STR_LOAD_X(SET, slab)                                                              \
+    _Pragma("unroll") for (int q = 0; q < 4 * MT; ++q)                                         \
+        xr[SET][q] = xrow[q][NTS_STR_PHYS(slab) * (kStrK * 2 / 16)];
+#define NTS_STR_STORE_X(SET, buf)                                                              \
+    _Pragma("unroll") for (int q = 0; q < 4 * MT; ++q)                                         \
+        *reinterpret_cast<u32x4 *>((buf) + st_off + 8 * q * kStrPitch) = xr[SET][q];
+        NTS_STR_LOAD_X(0, s_lo)
+        NTS_STR_STORE_X(0, lds)
+#pragma unroll
+        for (int d = 0; d < XD; ++d) NTS_STR_LOAD_X(d, s_lo + 1 + d)
+        nts_lds_barrier();
+        int nb = 1;                                     // buffer of slab s+1
+#define NTS_STR_PERIOD(U, ss)                                                                  \
+    {                                                                                          \
+        NTS_STR_STORE_X(U, lds + nb * kBuf)  /* past the end: a copy of the last slab, never read */ \
+        NTS_STR_LOAD_X(U, (ss) + 1 + XD)                                                       \
+        nts_lds_barrier();                                                                     \
+        nb = nb == 2 ? 0 : nb + 1;                                                             \
+    }
+        int s = s_lo;
+        for (; s + XD <= s_hi; s += XD) {
+#pragma unroll
+            for (int u = 0; u < XD; ++u) NTS_STR_PERIOD(u, s + u)
+        }
+#pragma unroll
+        for (int u = 0; u < XD - 1; ++u)
+            if (s + u < s_hi) NTS_STR_PERIOD(u, s + u)
+#undef NTS_STR_PERIOD
+#undef NTS_STR_LOAD_X
+#undef NTS_STR_STORE_X
+        return;
+    }
+
+    const int fr = lane & 31, fg = lane >> 5;
+    const int n0 = bx * 128 * RT + wv * 32 * RT;
+    // weight rows of this lane (rows past the end are computed from the last row, not stored)
+    const u32x4 *arow[RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+        arow[r] = reinterpret_cast<const u32x4 *>(A + int64_t(min(n0 + r * 32 + fr, Nn - 1)) * lda + fg * 8);
+
+    f32x16 acc[MT][RT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][r][v] = 0.f;
+
+    u32x4 w[NSETS][RT][4];
+    // plain loads, not non-temporal ones: the instructions that share a 64-byte half line
+    // then meet in the L1 instead of each sending its own request to the L2
+#define NTS_STR_WLOAD(p) (*(p))
+#define NTS_STR_LOAD_W(DST, slab)                                                              \
+    _Pragma("unroll") for (int r = 0; r < RT; ++r)                                             \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                          \
+            DST[r][q] = NTS_STR_WLOAD(arow[r] + NTS_STR_PHYS(slab) * (kStrK * 2 / 16) + 2 * q);
+    // One MFMA step = one batch tile t at one k step k4 (step i = k4*MT + t).  Its batch
+    // fragment is read from LDS three steps ahead into a window of four registers; the last
+    // three reads of a slab already fetch the first fragments of the next slab.
+#define NTS_STR_FRAG(DST, buf, i)                                                              \
+    DST = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(                           \
+        (buf) + (((i) % MT) * 32 + fr) * kStrPitch + (((i) / MT) * 16 + fg * 8) * 2));
+    // Nothing in a slab is conditional (the compiler's wait-count bookkeeping would otherwise
+    // assume the shortest path and wait for the newest loads): past the end of this split's
+    // k range the weight loads repeat its last slab, which is in cache.
+#define NTS_STR_SLAB(U, ss)                                                                    \
+    {                                                                                          \
+        const unsigned char *xs = lds + cur * kBuf;                                            \
+        cur = cur == 2 ? 0 : cur + 1;                                                          \
+        const unsigned char *nx = lds + cur * kBuf;                                            \
+        NTS_STR_LOAD_W(w[((U) + NSETS - 1) % NSETS], (ss) + NSETS - 1)                         \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        _Pragma("unroll") for (int i = 0; i < kSteps; ++i) {                                   \
+            if (i == kBarrierStep) nts_lds_barrier();                                          \
+            if (i + 3 < kSteps) { NTS_STR_FRAG(xf[(i + 3) % 4], xs, i + 3) }                   \
+            else { NTS_STR_FRAG(xf[(i + 3) % 4], nx, i + 3 - kSteps) }                         \
+            _Pragma("unroll") for (int r = 0; r < RT; ++r)                                     \
+                acc[i % MT][r] = E::mfma32(xf[i % 4], __builtin_bit_cast(vec8, w[(U) % NSETS][r][i / MT]), \
+                                           acc[i % MT][r]);                                    \
+            __builtin_amdgcn_sched_barrier(0);                                                 \
+        }                                                                                      \
+    }
+
+    constexpr int kSteps = 4 * MT;
+    // the barrier of a slab comes before the first read from the next slab's buffer
+    constexpr int kBarrierStep = 2 * MT < kSteps - 3 ? 2 * MT : kSteps - 3;
+#pragma unroll
+    for (int d = 0; d < NSETS - 1; ++d) NTS_STR_LOAD_W(w[d], s_lo + d)
+    nts_lds_barrier();
+    vec8 xf[4];
+    NTS_STR_FRAG(xf[0], lds, 0)
+    NTS_STR_FRAG(xf[1], lds, 1)
+    NTS_STR_FRAG(xf[2], lds, 2)
+    int cur = 0;                                        // LDS buffer of the current slab
+    int s = s_lo;
+    for (; s + NSETS <= s_hi; s += NSETS) {
+#pragma unroll
+        for (int u = 0; u < NSETS; ++u) NTS_STR_SLAB(u, s + u)
+    }
+#pragma unroll
+    for (int u = 0; u < NSETS - 1; ++u)
+        if (s + u < s_hi) NTS_STR_SLAB(u, s + u)
+#undef NTS_STR_SLAB
+#undef NTS_STR_PHYS
+#undef NTS_STR_LOAD_W
+#undef NTS_STR_FRAG
+    // D[i = (v/4)*8 + (lane/32)*4 + v%4][j = lane%32]: batch row i, weight row j
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+            const int n = n0 + r * 32 + fr;
+            if (n < Nn) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + t * 32 + (v / 4) * 8 + fg * 4 + (v % 4);
+                    if (m < M) {
+                        if (part) part[(int64_t(split) * M + m) * Nn + n] = acc[t][r][v];
+                        else Y[int64_t(m) * ldy + n] = E::round(acc[t][r][v]);
+                    }
+                }
+            }
+        }
+}
 
 // ---------------------------------------------------------------------------
 // Large batches (M > 64, prefill): bound by the matrix cores.  A 256-thread
@@ -335,51 +416,90 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 
 }  // namespace
 
-static int skinny_row_tiles(int M) { return M > 32 ? 2 : 1; }
-static int skinny_waves(int) { return 4; }   // 8 wavefronts per workgroup measured slower for wide batches
-
-int nts_linear_skinny_splits(int M, int Nn, int K)
+template <class E, int MT, int RT, int NSETS>
+static hipError_t launch_stream_one(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda, uint16_t *Y,
+                                 int64_t ldy, float *part, int splits, int M, int Nn, int K, hipStream_t st)
 {
-    const int waves = (Nn + 16 * skinny_row_tiles(M) - 1) / (16 * skinny_row_tiles(M));
-    const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
-    int splits = (2048 + waves - 1) / waves;          // aim at >= 8 wavefronts per compute unit (swept: 512..8192)
-    // the fp32 partial sums are written and read back by the reduction: keep that traffic
-    // (splits * M * Nn * 8 bytes) under a fifth of the weight bytes, or 16 MiB if that is more
-    const int64_t budget = std::max<int64_t>(int64_t(Nn) * K * 2 / 5, int64_t(16) << 20);
-    const int64_t cap = budget / (int64_t(M) * Nn * 8);
-    if (splits > cap) splits = int(cap);
-    if (splits > n_chunks) splits = n_chunks;
-    if (splits < 1) splits = 1;
-    const int cps = (n_chunks + splits - 1) / splits;
-    return (n_chunks + cps - 1) / cps;                // no empty split
+    const int lds_bytes = 3 * 32 * MT * kStrPitch;
+    static bool configured = false;
+    if (!configured) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_stream_kernel<E, MT, RT, NSETS>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int tiles_m = (M + 32 * MT - 1) / (32 * MT), blocks_n = (Nn + 128 * RT - 1) / (128 * RT);
+    const int n_slabs = K / kStrK;
+    const int sps = (n_slabs + splits - 1) / splits;
+    const dim3 grid(unsigned((blocks_n + 7) / 8) * 8u * unsigned(tiles_m), unsigned((n_slabs + sps - 1) / sps));
+    hipLaunchKernelGGL((nts_linear_stream_kernel<E, MT, RT, NSETS>), grid, dim3(kStrThreads), lds_bytes, st, X, ldx, A,
+                       lda, Y, ldy, splits > 1 ? part : nullptr, M, Nn, K, sps, tiles_m, blocks_n);
+    return hipGetLastError();
 }
 
-hipError_t nts_launch_linear_skinny(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
-                                    uint16_t *Y, int64_t ldy, float *part, int splits, int M, int Nn,
-                                    int K, bool f16, hipStream_t st)
+// Configuration of the streaming kernel for a problem: the smallest batch tile that holds the
+// batch (at most 256 rows per tile; longer batches take several tiles, whose workgroups share
+// the weight block through one XCD's L2) and the K split with the smallest estimated time.
+// The estimate (microseconds, fitted to measurements on MI355X): a workgroup needs t_slab per
+// 64-wide slab, 0.75 for tiles up to 128 rows (the rate at which one compute unit can pull
+// weight bytes) and more for taller tiles (matrix-core and LDS work); workgroups run in waves
+// of 256, one per compute unit, and every wave pays about 3 for filling and draining its
+// pipelines; a split costs a second launch (about 5) plus writing and reading
+// splits * M * Nn fp32 partial sums at about 4 TB/s.  More splits must win by 5 %.  At least four slabs per split;
+// the workspace stays under 512 MiB.
+NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
 {
-    const int n_chunks = (K + kSkinnyChunk - 1) / kSkinnyChunk;
-    const int cps = (n_chunks + splits - 1) / splits;
-    const int rows_per_wg = 16 * skinny_row_tiles(M) * skinny_waves(M);
-    const dim3 grid((Nn + rows_per_wg - 1) / rows_per_wg, splits), block(skinny_waves(M) * 64);
-    float *p = splits > 1 ? part : nullptr;
-    const int mt = (M + 15) / 16;
-#define NTS_SK(MT, RT, WV)                                                                                            \
-    {                                                                                                               \
-        if (f16) hipLaunchKernelGGL((nts_linear_skinny_kernel<F16, MT, RT, WV>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps); \
-        else hipLaunchKernelGGL((nts_linear_skinny_kernel<Bf16, MT, RT, WV>), grid, block, 0, st, X, ldx, A, lda, Y, ldy, p, M, Nn, K, cps);    \
+    NtsStreamCfg c;
+    const int rows = M < 256 ? M : 256;
+    c.mt = rows <= 32 ? 1 : rows <= 64 ? 2 : rows <= 96 ? 3 : rows <= 128 ? 4 : rows <= 192 ? 6 : 8;
+    c.nsets = c.mt <= 4 ? 4 : 3;
+    const int tiles_m = (M + 32 * c.mt - 1) / (32 * c.mt), blocks_n = (Nn + 127) / 128;
+    const int64_t wgs = int64_t(tiles_m) * blocks_n;
+    const int n_slabs = K / kStrK;
+    const double t_slab = c.mt <= 4 ? 0.75 : c.mt == 6 ? 1.1 : 1.45;
+    const double out_elems = double(M) * Nn;
+    int best = 1;
+    double best_t = 0.;
+    for (int splits = 1; splits <= 32 && splits <= (n_slabs >= 4 ? n_slabs / 4 : 1); ++splits) {
+        const int sps = (n_slabs + splits - 1) / splits;
+        if ((n_slabs + sps - 1) / sps != splits) continue;                  // would leave an empty split
+        if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) break;
+        const double waves = double((wgs * splits + 255) / 256);
+        double t = waves * (sps * t_slab + 3.);
+        if (splits > 1) t += 5. + out_elems * splits * 8. / 4.0e6;
+        if (splits == 1 || t < 0.95 * best_t) {
+            best = splits;
+            best_t = t;
+        }
     }
-    if (mt == 1) NTS_SK(1, 1, 4)
-    else if (mt == 2) NTS_SK(2, 1, 4)
-    else if (mt == 3) NTS_SK(3, 2, 4)
-    else NTS_SK(4, 2, 4)
-#undef NTS_SK
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || splits <= 1) return e;
+    c.splits = best;
+    return c;
+}
+
+hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda, uint16_t *Y,
+                                    int64_t ldy, float *part, const NtsStreamCfg &c, int M, int Nn, int K,
+                                    bool f16, hipStream_t st)
+{
+    hipError_t e = hipErrorInvalidValue;
+#define NTS_STR(MT, NS)                                                                                        \
+    if (c.mt == MT && c.nsets == NS)                                                                           \
+        e = f16 ? launch_stream_one<F16, MT, 1, NS>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st)      \
+                : launch_stream_one<Bf16, MT, 1, NS>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st);
+    NTS_STR(1, 4) NTS_STR(2, 4) NTS_STR(3, 4) NTS_STR(4, 4) NTS_STR(6, 3) NTS_STR(8, 3)
+#undef NTS_STR
+    if (e != hipSuccess || c.splits <= 1) return e;
     const int64_t n = int64_t(M) * Nn;
-    if (f16) hipLaunchKernelGGL(nts_linear_reduce_kernel<F16>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, splits, M, Nn, Y, ldy);
-    else hipLaunchKernelGGL(nts_linear_reduce_kernel<Bf16>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, splits, M, Nn, Y, ldy);
+    if (f16) hipLaunchKernelGGL(nts_linear_reduce_kernel<F16>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, c.splits, M, Nn, Y, ldy);
+    else hipLaunchKernelGGL(nts_linear_reduce_kernel<Bf16>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, c.splits, M, Nn, Y, ldy);
     return hipGetLastError();
+}
+
+// The tiled kernel pays off once its 256 x 256 tiles fill the chip; below that the streaming
+// kernel (several batch tiles per weight block) is faster.
+bool nts_linear_use_tiled(int M, int Nn)
+{
+    const int64_t tiles = int64_t((M + kTileM - 1) / kTileM) * ((Nn + kTileN - 1) / kTileN);
+    return M > 256 && tiles >= 224;
 }
 
 hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
