@@ -223,7 +223,7 @@ def strategies(args, torch, b, wdev, make_case):
 
 def linear_bench(args, torch, b):
     """Shard-selecting linear layer: rank tp-1 of each TP level computes with its 1/tp of the
-    full weight.  Decode batches (M <= 64) are HBM-bound: bytes = the shard read once (+X, +Y).
+    full weight.  Batches up to 256 rows are HBM-bound: bytes = the shard read once (+X, +Y).
     Prefill batches are matrix-core-bound: 2*M*Nn*K flops against 2.5 PFLOP/s (bf16, dense).
     Launches are captured into a HIP graph that walks through more than 3 GiB of distinct
     weight copies, so no shard is served from a cache and launch gaps do not hide the kernels."""
@@ -235,7 +235,7 @@ def linear_bench(args, torch, b):
         copies = max(2, (3 << 30) // wbytes + 1)
         W = (torch.rand(copies, n_out, n_in, device="cuda") * 0.08 - 0.04).to(torch.bfloat16)
         for tp in (1, 2, 4, 8):
-            for M in (1, 16, 64, 4096):
+            for M in (1, 16, 64, 256, 1024, 4096):
                 k = n_in if split == "out" else n_in // tp
                 nn = n_out // tp if split == "out" else n_out
                 X = (torch.rand(M, k, device="cuda") * 4 - 2).to(torch.bfloat16)
@@ -250,7 +250,7 @@ def linear_bench(args, torch, b):
                                        workspace=ws.data_ptr(), workspace_bytes=wsb,
                                        hip_stream=torch.cuda.current_stream().cuda_stream, **kw)
 
-                n_launch = copies * 2 if M <= 64 else max(4, copies)
+                n_launch = copies * 2 if M <= 256 else max(4, copies)
                 launch(0)
                 torch.cuda.synchronize()
                 graph = torch.cuda.CUDAGraph()
@@ -269,7 +269,8 @@ def linear_bench(args, torch, b):
                     ts.append(e0.elapsed_time(e1) * 1e3 / n_launch)
                 us = sorted(ts)[2]
                 shard_bytes = nn * k * 2
-                if M <= 64:
+                # below ~312 flop per weight byte (2.5 PFLOP/s / 8 TB/s) the layer is bound by reading the shard
+                if M <= 256:
                     ach = (shard_bytes + M * k * 2 + M * nn * 2) / us / 1e3
                     roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS}
                 else:

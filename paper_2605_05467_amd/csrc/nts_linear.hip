@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void nts_linear_reduce_kernel(const float *__r
 // its row for a 64-wide slab (64 contiguous bytes) and feeds the slab's four
 // MFMA steps s = 0..3 with k = 32g + 8s + e; the batch fragments are read from
 // LDS with the same k, so both operands agree.  The batch slab (32*MT rows x
-// 64 k) is shared by the consumers and is brought into LDS by a fifth,
+// 64 k) is shared by the consumers and is brought into LDS by one more,
 // "producer" wavefront.  Splitting the roles matters because a wavefront's
 // loads return in order: a consumer that also fetched batch rows would, each
 // time it waits for them, wait for every weight load issued before them, which
@@ -99,10 +99,9 @@ __device__ __forceinline__ void nts_lds_barrier()
 
 constexpr int kStrK = 64;
 constexpr int kStrPitch = kStrK * 2 + 16;          // bytes per batch row in LDS
-constexpr int kStrThreads = 320;                   // four consumers and one producer
 
-template <class E, int MT, int RT, int NSETS>
-__global__ __launch_bounds__(kStrThreads) void nts_linear_stream_kernel(
+template <class E, int MT, int CW, int NSETS>
+__global__ __launch_bounds__(64 * (CW + 1)) void nts_linear_stream_kernel(
     const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
     uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ part, int M, int Nn, int K,
     int slabs_per_split, int tiles_m, int blocks_n)
@@ -128,7 +127,8 @@ __global__ __launch_bounds__(kStrThreads) void nts_linear_stream_kernel(
     // and the consumers read slab s; the one barrier per period (in its middle for the
     // consumers) publishes slab s+1 and retires slab s-1, so the consumers can read the first
     // fragments of slab s+1 during the last MFMA step of slab s.
-    if (wv == 4) {
+    constexpr int RT = 1;                               // 32-row weight tiles per consumer
+    if (wv == CW) {
         // producer: lane moves 16-byte vector (lane & 7) of rows (lane >> 3) + 8 q
         const int sv = lane & 7, sr = lane >> 3;
         const u32x4 *xrow[4 * MT];
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kStrThreads) void nts_linear_stream_kernel(
     }
 
     const int fr = lane & 31, fg = lane >> 5;
-    const int n0 = bx * 128 * RT + wv * 32 * RT;
+    const int n0 = (bx * CW + wv) * 32 * RT;
     // weight rows of this lane (rows past the end are computed from the last row, not stored)
     const u32x4 *arow[RT];
 #pragma unroll
@@ -416,63 +416,75 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 
 }  // namespace
 
-template <class E, int MT, int RT, int NSETS>
+template <class E, int MT, int CW, int NSETS>
 static hipError_t launch_stream_one(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda, uint16_t *Y,
                                  int64_t ldy, float *part, int splits, int M, int Nn, int K, hipStream_t st)
 {
     const int lds_bytes = 3 * 32 * MT * kStrPitch;
     static bool configured = false;
     if (!configured) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_stream_kernel<E, MT, RT, NSETS>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_stream_kernel<E, MT, CW, NSETS>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    const int tiles_m = (M + 32 * MT - 1) / (32 * MT), blocks_n = (Nn + 128 * RT - 1) / (128 * RT);
+    const int tiles_m = (M + 32 * MT - 1) / (32 * MT), blocks_n = (Nn + 32 * CW - 1) / (32 * CW);
     const int n_slabs = K / kStrK;
     const int sps = (n_slabs + splits - 1) / splits;
     const dim3 grid(unsigned((blocks_n + 7) / 8) * 8u * unsigned(tiles_m), unsigned((n_slabs + sps - 1) / sps));
-    hipLaunchKernelGGL((nts_linear_stream_kernel<E, MT, RT, NSETS>), grid, dim3(kStrThreads), lds_bytes, st, X, ldx, A,
+    hipLaunchKernelGGL((nts_linear_stream_kernel<E, MT, CW, NSETS>), grid, dim3(64 * (CW + 1)), lds_bytes, st, X, ldx, A,
                        lda, Y, ldy, splits > 1 ? part : nullptr, M, Nn, K, sps, tiles_m, blocks_n);
     return hipGetLastError();
 }
 
 // Configuration of the streaming kernel for a problem: the smallest batch tile that holds the
 // batch (at most 256 rows per tile; longer batches take several tiles, whose workgroups share
-// the weight block through one XCD's L2) and the K split with the smallest estimated time.
-// The estimate (microseconds, fitted to measurements on MI355X): a workgroup needs t_slab per
-// 64-wide slab, 0.75 for tiles up to 128 rows (the rate at which one compute unit can pull
-// weight bytes) and more for taller tiles (matrix-core and LDS work); workgroups run in waves
-// of 256, one per compute unit, and every wave pays about 3 for filling and draining its
-// pipelines; a split costs a second launch (about 5) plus writing and reading
-// splits * M * Nn fp32 partial sums at about 4 TB/s.  More splits must win by 5 %.  At least four slabs per split;
-// the workspace stays under 512 MiB.
+// the weight block through one XCD's L2), then the workgroup width and K split with the
+// smallest estimated time.  The estimate (microseconds, fitted to measurements on MI355X):
+// a compute unit with four consumer wavefronts needs t_slab per 64-wide slab, 0.75 for tiles
+// up to 128 rows (the rate at which one compute unit can pull weight bytes) and more for
+// taller tiles (matrix-core and LDS work); a lone narrow workgroup is latency-bound at about
+// 0.35 per slab; workgroups run in waves that fill the 256 compute units, and every wave pays
+// about 3 for filling and draining its pipelines; a split costs a second launch (about 5)
+// plus writing and reading splits * M * Nn fp32 partial sums at about 4 TB/s.  A split keeps
+// at least four slabs and the workspace stays under 512 MiB.  Narrow workgroups (one consumer)
+// are considered only for batches up to 256 rows and shards up to 16 MiB (measured: no gain
+// above that); every departure from the plain configuration must win by 5 %.
 NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
 {
     NtsStreamCfg c;
     const int rows = M < 256 ? M : 256;
     c.mt = rows <= 32 ? 1 : rows <= 64 ? 2 : rows <= 96 ? 3 : rows <= 128 ? 4 : rows <= 192 ? 6 : 8;
     c.nsets = c.mt <= 4 ? 4 : 3;
-    const int tiles_m = (M + 32 * c.mt - 1) / (32 * c.mt), blocks_n = (Nn + 127) / 128;
-    const int64_t wgs = int64_t(tiles_m) * blocks_n;
+    const int tiles_m = (M + 32 * c.mt - 1) / (32 * c.mt);
     const int n_slabs = K / kStrK;
     const double t_slab = c.mt <= 4 ? 0.75 : c.mt == 6 ? 1.1 : 1.45;
     const double out_elems = double(M) * Nn;
-    int best = 1;
+    const bool narrow_ok = M <= 256 && c.mt != 3 && c.mt != 6 && int64_t(Nn) * K * 2 <= (int64_t(16) << 20);
     double best_t = 0.;
-    for (int splits = 1; splits <= 32 && splits <= (n_slabs >= 4 ? n_slabs / 4 : 1); ++splits) {
-        const int sps = (n_slabs + splits - 1) / splits;
-        if ((n_slabs + sps - 1) / sps != splits) continue;                  // would leave an empty split
-        if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) break;
-        const double waves = double((wgs * splits + 255) / 256);
-        double t = waves * (sps * t_slab + 3.);
-        if (splits > 1) t += 5. + out_elems * splits * 8. / 4.0e6;
-        if (splits == 1 || t < 0.95 * best_t) {
-            best = splits;
-            best_t = t;
+    c.cw = 4;
+    c.splits = 1;
+    for (int cw = 4; cw >= 1; cw -= 3) {
+        if (cw == 1 && !narrow_ok) break;
+        const int64_t wgs = int64_t(tiles_m) * ((Nn + 32 * cw - 1) / (32 * cw));
+        const int per_cu_max = 4 / cw;                  // workgroups that share a compute unit
+        for (int splits = 1; splits <= 32 && splits <= (n_slabs >= 4 ? n_slabs / 4 : 1); ++splits) {
+            const int sps = (n_slabs + splits - 1) / splits;
+            if ((n_slabs + sps - 1) / sps != splits) continue;              // would leave an empty split
+            if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) break;
+            const int64_t total = wgs * splits;
+            const double waves = double((total + 256 * per_cu_max - 1) / (256 * per_cu_max));
+            const int64_t per_cu = std::min<int64_t>(per_cu_max, (total + 255) / 256);
+            const double t_wg = std::max(0.35, t_slab * double(per_cu) * cw / 4.);
+            double t = waves * (sps * t_wg + 3.);
+            if (splits > 1) t += 5. + out_elems * splits * 8. / 4.0e6;
+            if ((cw == 4 && splits == 1) || t < 0.95 * best_t) {
+                c.cw = cw;
+                c.splits = splits;
+                best_t = t;
+            }
         }
     }
-    c.splits = best;
     return c;
 }
 
@@ -481,11 +493,13 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
                                     bool f16, hipStream_t st)
 {
     hipError_t e = hipErrorInvalidValue;
-#define NTS_STR(MT, NS)                                                                                        \
-    if (c.mt == MT && c.nsets == NS)                                                                           \
-        e = f16 ? launch_stream_one<F16, MT, 1, NS>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st)      \
-                : launch_stream_one<Bf16, MT, 1, NS>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st);
-    NTS_STR(1, 4) NTS_STR(2, 4) NTS_STR(3, 4) NTS_STR(4, 4) NTS_STR(6, 3) NTS_STR(8, 3)
+#define NTS_STR(MT, CW, NS)                                                                                    \
+    if (c.mt == MT && c.cw == CW && c.nsets == NS)                                                             \
+        e = f16 ? launch_stream_one<F16, MT, CW, NS>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st)     \
+                : launch_stream_one<Bf16, MT, CW, NS>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st);
+    NTS_STR(1, 4, 4) NTS_STR(2, 4, 4) NTS_STR(3, 4, 4) NTS_STR(4, 4, 4) NTS_STR(6, 4, 3) NTS_STR(8, 4, 3)
+    NTS_STR(1, 1, 4) NTS_STR(2, 1, 4) NTS_STR(4, 1, 4) NTS_STR(8, 1, 3)
+    NTS_STR(1, 2, 4) NTS_STR(2, 2, 4) NTS_STR(4, 2, 4) NTS_STR(8, 2, 3)
 #undef NTS_STR
     if (e != hipSuccess || c.splits <= 1) return e;
     const int64_t n = int64_t(M) * Nn;

@@ -86,14 +86,26 @@ def test_argument_errors(env):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("M", [65, 200, 256, 300, 777])
+@pytest.mark.parametrize("M", [65, 96, 130, 192, 200, 256, 300, 777])
 @pytest.mark.parametrize("split", ["out", "in"])
 def test_large_batches_tile_edges(env, M, split):
-    """Prefill-size batches: the 256 x 256 tiled matrix-core kernel with ragged
+    """Wide batches on the weight-streaming kernel: every batch-tile height (96,
+    128, 192, 256 rows), several batch tiles per weight block, K splits, ragged
     edges in both output dimensions."""
     run_case(env, M, 96, 512, 2, 1, split, seed=M)
     run_case(env, M, 528, 1024 + 64, 1, 0, split, seed=M + 100, pad=8)
     run_case(env, M, 1024, 2048, 4, 3, split, seed=M + 200)
+
+
+@pytest.mark.parametrize("M", [520, 777])
+@pytest.mark.parametrize("split", ["out", "in"])
+def test_tiled_kernel_ragged_edges(env, M, split):
+    """Outputs with at least 224 tiles of 256 x 256 go to the tiled matrix-core
+    kernel: ragged edges in both output dimensions, both element formats."""
+    tp = 2
+    n_out, n_in = (2 * 19000, 256) if split == "out" else (19000, 2 * 256)
+    run_case(env, M, n_out, n_in, tp, 1, split, seed=M + 7)
+    run_case(env, M, n_out, n_in, tp, 0, split, seed=M + 8, dtype="f16")
 
 
 @pytest.mark.parametrize("layer", ["8b_qkv", "8b_down", "14b_o"])
