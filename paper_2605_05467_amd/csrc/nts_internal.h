@@ -105,7 +105,8 @@ hipError_t nts_launch_flatten(const int32_t *d_tok_off, const int32_t *d_pg_off,
 // nts_linear.hip: Y[M][Nn] = X[M][K] . A[Nn][K]^T, bf16 or f16 in, fp32 accumulate, same format out
 struct NtsStreamCfg {
     int mt = 1;       // batch rows per workgroup / 32
-    int cw = 4;       // consumer wavefronts per workgroup (32 weight rows each)
+    int cw = 4;       // consumer wavefronts per workgroup
+    int rt = 1;       // 32-row weight tiles per consumer
     int nsets = 4;    // weight register sets in rotation (nsets - 1 slabs in flight per wavefront)
     int splits = 1;   // K splits (> 1: fp32 partial sums in the workspace, reduced in split order)
 };

@@ -100,7 +100,7 @@ __device__ __forceinline__ void nts_lds_barrier()
 constexpr int kStrK = 64;
 constexpr int kStrPitch = kStrK * 2 + 16;          // bytes per batch row in LDS
 
-template <class E, int MT, int CW, int NSETS>
+template <class E, int MT, int CW, int NSETS, int RT>
 __global__ __launch_bounds__(64 * (CW + 1)) void nts_linear_stream_kernel(
     const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
     uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ part, int M, int Nn, int K,
@@ -127,7 +127,6 @@ __global__ __launch_bounds__(64 * (CW + 1)) void nts_linear_stream_kernel(
     // and the consumers read slab s; the one barrier per period (in its middle for the
     // consumers) publishes slab s+1 and retires slab s-1, so the consumers can read the first
     // fragments of slab s+1 during the last MFMA step of slab s.
-    constexpr int RT = 1;                               // 32-row weight tiles per consumer
     if (wv == CW) {
         // producer: lane moves 16-byte vector (lane & 7) of rows (lane >> 3) + 8 q
         const int sv = lane & 7, sr = lane >> 3;
@@ -345,7 +344,7 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
             ar[q] = ab[ao[q] + kTileK * 2 / 16];
         }
     }
-    __syncthreads();
+    nts_lds_barrier();
 
     // fragments of k step kk+1 are read from LDS while the MFMAs of step kk run
 #define NTS_LOAD_FRAGS(kk, XF, AF)                                                                     \
@@ -394,7 +393,7 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
         NTS_LOAD_FRAGS(3, xf1, af1)
         NTS_MFMAS(xf0, af0)
         NTS_MFMAS(xf1, af1)
-        __syncthreads();                                // buffer s&1 is free, buffer (s+1)&1 is complete
+        nts_lds_barrier();                              // LDS-only wait: the loads of slab s+2 stay in flight; buffer s&1 is free, buffer (s+1)&1 is complete
     }
 #undef NTS_LOAD_FRAGS
 #undef NTS_MFMAS
@@ -416,23 +415,23 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 
 }  // namespace
 
-template <class E, int MT, int CW, int NSETS>
+template <class E, int MT, int CW, int NSETS, int RT>
 static hipError_t launch_stream_one(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda, uint16_t *Y,
                                  int64_t ldy, float *part, int splits, int M, int Nn, int K, hipStream_t st)
 {
     const int lds_bytes = 3 * 32 * MT * kStrPitch;
     static bool configured = false;
     if (!configured) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_stream_kernel<E, MT, CW, NSETS>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_stream_kernel<E, MT, CW, NSETS, RT>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    const int tiles_m = (M + 32 * MT - 1) / (32 * MT), blocks_n = (Nn + 32 * CW - 1) / (32 * CW);
+    const int tiles_m = (M + 32 * MT - 1) / (32 * MT), blocks_n = (Nn + 32 * CW * RT - 1) / (32 * CW * RT);
     const int n_slabs = K / kStrK;
     const int sps = (n_slabs + splits - 1) / splits;
     const dim3 grid(unsigned((blocks_n + 7) / 8) * 8u * unsigned(tiles_m), unsigned((n_slabs + sps - 1) / sps));
-    hipLaunchKernelGGL((nts_linear_stream_kernel<E, MT, CW, NSETS>), grid, dim3(64 * (CW + 1)), lds_bytes, st, X, ldx, A,
+    hipLaunchKernelGGL((nts_linear_stream_kernel<E, MT, CW, NSETS, RT>), grid, dim3(64 * (CW + 1)), lds_bytes, st, X, ldx, A,
                        lda, Y, ldy, splits > 1 ? part : nullptr, M, Nn, K, sps, tiles_m, blocks_n);
     return hipGetLastError();
 }
@@ -493,13 +492,15 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
                                     bool f16, hipStream_t st)
 {
     hipError_t e = hipErrorInvalidValue;
-#define NTS_STR(MT, CW, NS)                                                                                    \
-    if (c.mt == MT && c.cw == CW && c.nsets == NS)                                                             \
-        e = f16 ? launch_stream_one<F16, MT, CW, NS>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st)     \
-                : launch_stream_one<Bf16, MT, CW, NS>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st);
-    NTS_STR(1, 4, 4) NTS_STR(2, 4, 4) NTS_STR(3, 4, 4) NTS_STR(4, 4, 4) NTS_STR(6, 4, 3) NTS_STR(8, 4, 3)
-    NTS_STR(1, 1, 4) NTS_STR(2, 1, 4) NTS_STR(4, 1, 4) NTS_STR(8, 1, 3)
-    NTS_STR(1, 2, 4) NTS_STR(2, 2, 4) NTS_STR(4, 2, 4) NTS_STR(8, 2, 3)
+#define NTS_STR(MT, CW, NS, RT)                                                                                \
+    if (c.mt == MT && c.cw == CW && c.nsets == NS && c.rt == RT)                                               \
+        e = f16 ? launch_stream_one<F16, MT, CW, NS, RT>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st) \
+                : launch_stream_one<Bf16, MT, CW, NS, RT>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st);
+    NTS_STR(1, 4, 4, 1) NTS_STR(2, 4, 4, 1) NTS_STR(3, 4, 4, 1) NTS_STR(4, 4, 4, 1) NTS_STR(6, 4, 3, 1) NTS_STR(8, 4, 3, 1)
+    NTS_STR(1, 1, 4, 1) NTS_STR(2, 1, 4, 1) NTS_STR(4, 1, 4, 1) NTS_STR(8, 1, 3, 1)
+#ifdef NTS_STREAM_EXPERIMENTS
+    NTS_STR(4, 3, 3, 4) NTS_STR(4, 3, 2, 4) NTS_STR(4, 4, 3, 2) NTS_STR(8, 3, 3, 2) NTS_STR(4, 3, 3, 2) NTS_STR(2, 3, 3, 4)
+#endif
 #undef NTS_STR
     if (e != hipSuccess || c.splits <= 1) return e;
     const int64_t n = int64_t(M) * Nn;
