@@ -66,3 +66,30 @@ def test_struct_sizes_match_the_header(b):
     # nts_desc: 10 int32, 2 int64, 3 pointers, 3 int64, 2 uint32; nts_info: 7 int64 + 2 int32
     assert ctypes.sizeof(b.nts_desc) == 40 + 16 + 24 + 24 + 8
     assert ctypes.sizeof(b.nts_info) == 64
+
+
+def test_linear_workspace_is_whole_partial_sum_planes_and_bounded(b):
+    """nts_shard_linear_workspace is host arithmetic: it must be a whole number of
+    fp32 [M][Nn] planes (one per K split), zero where no split is used, and stay
+    under the documented 512 MiB for every layer shape, TP level and batch."""
+    from workload.linear import LAYERS
+    seen_split = seen_none = False
+    for name, (n_out, n_in, split) in LAYERS.items():
+        for tp in (1, 2, 4, 8):
+            for M in (1, 7, 16, 64, 100, 256, 777, 4096):
+                sp = b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN
+                nn = n_out // tp if split == "out" else n_out
+                k = n_in if split == "out" else n_in // tp
+                ws = b.nts_shard_linear_workspace(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=tp - 1, split=sp)
+                plane = 4 * M * nn
+                assert ws % plane == 0 and ws <= 512 << 20, (name, tp, M, ws)
+                splits = ws // plane
+                assert splits != 1                                # one split needs no workspace
+                if splits:
+                    assert k // 64 // splits >= 1                 # never more splits than 64-wide slabs
+                    seen_split = True
+                else:
+                    seen_none = True
+    assert seen_split and seen_none
+    with pytest.raises(b.NtsError):
+        b.nts_shard_linear_workspace(M=4, n_out=64, n_in=72, tp=1, rank=0, split=b.NTS_SPLIT_OUT)
