@@ -68,26 +68,29 @@ __global__ __launch_bounds__(256) void nts_linear_reduce_kernel(const float *__r
 
 // ---------------------------------------------------------------------------
 // Weight-streaming kernel (decode batches and short prefill chunks): bound by the
-// weight bytes, read exactly once; for wider batches there is also enough matrix-core
-// and LDS work that neither may be wasted.  A workgroup takes 32*MT batch rows and 128*RT weight rows.  Four
-// "consumer" wavefronts each own 32*RT weight rows for all of the batch rows, as
-// MT x RT tiles of v_mfma_f32_32x32x16.  A weight
-// row is used by one wavefront only, so weights go from global memory straight
-// into registers: lane (row = lane%32, g = lane/32) holds k = 32g .. 32g+31 of
-// its row for a 64-wide slab (64 contiguous bytes) and feeds the slab's four
-// MFMA steps s = 0..3 with k = 32g + 8s + e; the batch fragments are read from
-// LDS with the same k, so both operands agree.  The batch slab (32*MT rows x
+// weight bytes, read exactly once; for wider batches there is also enough
+// matrix-core and LDS work that neither may be wasted.  A workgroup takes 32*MT
+// batch rows and 32*RT*CW weight rows.  CW "consumer" wavefronts each own 32*RT
+// weight rows for all of the batch rows, as MT x RT tiles of
+// v_mfma_f32_32x32x16 (RT = 1 in every configuration in use: two tiles per
+// consumer halve the LDS reads per MFMA but measured slower).  A weight row is
+// used by one wavefront only, so weights go from global memory straight into
+// registers: lane (row = lane%32, g = lane/32) holds, for a 64-wide slab, the
+// four 16-byte pieces k = 16s + 8g .. +7 (s = 0..3) of its row, one per MFMA
+// step; the batch fragments are read from LDS with the same k.  The loads are
+// plain, not non-temporal: the two lanes and two instructions that share a
+// 64-byte half line then meet in the L1 instead of each going to the L2, which
+// alone was worth 88 -> 54 us on a 224 MiB shard.  The batch slab (32*MT rows x
 // 64 k) is shared by the consumers and is brought into LDS by one more,
 // "producer" wavefront.  Splitting the roles matters because a wavefront's
 // loads return in order: a consumer that also fetched batch rows would, each
-// time it waits for them, wait for every weight load issued before them, which
-// caps the weight bytes in flight at two slabs; with ~3 us of loaded HBM latency
-// that is a third of the bandwidth.  Consumers keep NSETS-1 slabs of weights in
-// flight (NSETS register sets used in rotation; the slab loop is unrolled by
-// NSETS so the sets are fixed registers).  K can be split over blockIdx.y (fp32
-// partial sums, reduced in split order by nts_linear_reduce_kernel).
-// Workgroup order: the batch tiles of one weight block run back to back on one
-// XCD, so that block is fetched from HBM once and then served by that XCD's L2.
+// time it waits for them, wait for every weight load issued before them.
+// Consumers keep NSETS-1 slabs of weights in flight (NSETS register sets used in
+// rotation; the slab loop is unrolled by NSETS so the sets are fixed registers).
+// K can be split over blockIdx.y (fp32 partial sums, reduced in split order by
+// nts_linear_reduce_kernel).  Workgroup order: the batch tiles of one weight
+// block run back to back on one XCD, so that block is fetched from HBM once and
+// then served by that XCD's L2.
 
 // Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits for every
 // outstanding global load (its fences cover global memory), which would drain the weight
@@ -189,8 +192,6 @@ __global__ __launch_bounds__(64 * (CW + 1)) void nts_linear_stream_kernel(
             for (int v = 0; v < 16; ++v) acc[t][r][v] = 0.f;
 
     u32x4 w[NSETS][RT][4];
-    // plain loads, not non-temporal ones: the instructions that share a 64-byte half line
-    // then meet in the L1 instead of each sending its own request to the L2
 #define NTS_STR_WLOAD(p) (*(p))
 #define NTS_STR_LOAD_W(DST, slab)                                                              \
     _Pragma("unroll") for (int r = 0; r < RT; ++r)                                             \
@@ -498,9 +499,6 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
                 : launch_stream_one<Bf16, MT, CW, NS, RT>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st);
     NTS_STR(1, 4, 4, 1) NTS_STR(2, 4, 4, 1) NTS_STR(3, 4, 4, 1) NTS_STR(4, 4, 4, 1) NTS_STR(6, 4, 3, 1) NTS_STR(8, 4, 3, 1)
     NTS_STR(1, 1, 4, 1) NTS_STR(2, 1, 4, 1) NTS_STR(4, 1, 4, 1) NTS_STR(8, 1, 3, 1)
-#ifdef NTS_STREAM_EXPERIMENTS
-    NTS_STR(4, 3, 3, 4) NTS_STR(4, 3, 2, 4) NTS_STR(4, 4, 3, 2) NTS_STR(8, 3, 3, 2) NTS_STR(4, 3, 3, 2) NTS_STR(2, 3, 3, 4)
-#endif
 #undef NTS_STR
     if (e != hipSuccess || c.splits <= 1) return e;
     const int64_t n = int64_t(M) * Nn;
