@@ -338,66 +338,86 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
         *reinterpret_cast<u32x4 *>(lds + st_off + 32 * q * kPitch) = xr[q];
         *reinterpret_cast<u32x4 *>(lds + kTileM * kPitch + st_off + 32 * q * kPitch) = ar[q];
     }
-    if (n_slabs > 1) {
+    {
+        const uint32_t off = uint32_t(min(1, n_slabs - 1)) * (kTileK * 2 / 16);
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            xr[q] = xb[xo[q] + kTileK * 2 / 16];
-            ar[q] = ab[ao[q] + kTileK * 2 / 16];
+            xr[q] = xb[xo[q] + off];
+            ar[q] = ab[ao[q] + off];
         }
     }
     nts_lds_barrier();
 
-    // fragments of k step kk+1 are read from LDS while the MFMAs of step kk run
-#define NTS_LOAD_FRAGS(kk, XF, AF)                                                                     \
+    // Two fragment sets: while the 16 MFMAs of k step kk run on one set, the eight fragments of
+    // step kk+1 are read from LDS into the other, one read every STRIDE MFMAs and in the order
+    // the next step consumes them (A0 B0 B1 B2 B3 A1 A2 A3).  A wavefront issues in order and
+    // can have only 15 LDS operations outstanding (4-bit counter), so everything that goes
+    // through LDS is spread between the MFMAs instead of issued in bursts: the 16 stores of
+    // slab s+1 (in registers since the previous slab) and, right behind each store, the global
+    // load of slab s+2 into the same register, one pair per three MFMAs over the first three k
+    // steps.  sched_barrier pins this order; left alone the compiler serialises read - wait -
+    // MFMA.  Over a slab the LDS is about three quarters busy, evenly.
+#define NTS_READ_FRAG(base, kk, r, XF, AF)                                                             \
     {                                                                                                  \
-        _Pragma("unroll") for (int a = 0; a < 4; ++a)                                                  \
-            XF[a] = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(                       \
-                xs + (wm * 128 + a * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));                   \
-        _Pragma("unroll") for (int b = 0; b < 4; ++b)                                                  \
-            AF[b] = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(                       \
-                as + (wn * 128 + b * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));                   \
+        if ((r) == 0 || (r) >= 5) {                                                                    \
+            const int a_ = (r) == 0 ? 0 : (r) - 4;                                                     \
+            XF[a_] = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(                      \
+                (base) + (wm * 128 + a_ * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));              \
+        } else {                                                                                       \
+            const int b_ = (r) - 1;                                                                    \
+            AF[b_] = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(                      \
+                (base) + (kTileM + wn * 128 + b_ * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));     \
+        }                                                                                              \
     }
-#define NTS_MFMAS(XF, AF)                                                                              \
+#define NTS_STORE_ONE(i)                                                                               \
+    {                                                                                                  \
+        if ((i) & 1) *reinterpret_cast<u32x4 *>(nx + kTileM * kPitch + st_off + 32 * ((i) >> 1) * kPitch) = ar[(i) >> 1]; \
+        else *reinterpret_cast<u32x4 *>(nx + st_off + 32 * ((i) >> 1) * kPitch) = xr[(i) >> 1];         \
+    }
+#define NTS_LOAD_ONE(i)                                                                                \
+    {                                                                                                  \
+        if ((i) & 1) ar[(i) >> 1] = ab[ao[(i) >> 1] + off];                                            \
+        else xr[(i) >> 1] = xb[xo[(i) >> 1] + off];                                                    \
+    }
+    // the 16 MFMAs of one k step on (XF, AF); G0 = slot number of the first one within the slab;
+    // fragment r of step NKK at NBASE goes into (NXF, NAF) after MFMA r * STRIDE
+#define NTS_KSTEP(XF, AF, G0, NBASE, NKK, NXF, NAF, STRIDE)                                            \
     {                                                                                                  \
         _Pragma("unroll") for (int a = 0; a < 4; ++a)                                                  \
-            _Pragma("unroll") for (int b = 0; b < 4; ++b)                                              \
+            _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                            \
+                const int i = a * 4 + b, g = (G0) + i;       /* constants after unrolling */           \
                 acc[a][b] = E::mfma32(XF[a], AF[b], acc[a][b]);                                       \
+                if (i % (STRIDE) == 0 && i / (STRIDE) < 8) NTS_READ_FRAG(NBASE, NKK, i / (STRIDE), NXF, NAF) \
+                if (g % 3 == 0 && g / 3 < 16) NTS_STORE_ONE(g / 3)                                     \
+                if (g % 3 == 1 && g / 3 < 16) NTS_LOAD_ONE(g / 3)                                      \
+                __builtin_amdgcn_sched_barrier(0);                                                     \
+            }                                                                                          \
     }
 
+    // One barrier per slab, before the last k step: by then every wavefront has read all of
+    // slab s (so slab s+2 may overwrite its buffer from the next iteration on) and has written
+    // its part of slab s+1 (so the first fragments of slab s+1 can be read during the last k
+    // step).  The reads of the last k step are issued in the first half of the step before it,
+    // so the barrier's wait for LDS is short.  Nothing in the loop is conditional: past the end
+    // the loads repeat the last slab and the spare buffer takes the copy.
+    typedef typename E::vec8 vec8;
+    vec8 xf0[4], af0[4], xf1[4], af1[4];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) NTS_READ_FRAG(lds, 0, r, xf0, af0)
     for (int s = 0; s < n_slabs; ++s) {
-        const unsigned char *xs = lds + (s & 1) * kTileLds, *as = xs + kTileM * kPitch;
+        const unsigned char *xs = lds + (s & 1) * kTileLds;
         unsigned char *nx = lds + ((s + 1) & 1) * kTileLds;
-        typedef typename E::vec8 vec8;
-        vec8 xf0[4], af0[4], xf1[4], af1[4];
-        NTS_LOAD_FRAGS(0, xf0, af0)
-        NTS_LOAD_FRAGS(1, xf1, af1)
-        NTS_MFMAS(xf0, af0)
-        // slab s+1 (in registers) goes to the other LDS buffer and the loads of slab s+2 start
-        // while the matrix cores work on the first k step
-        if (s + 1 < n_slabs) {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                *reinterpret_cast<u32x4 *>(nx + st_off + 32 * q * kPitch) = xr[q];
-                *reinterpret_cast<u32x4 *>(nx + kTileM * kPitch + st_off + 32 * q * kPitch) = ar[q];
-            }
-            if (s + 2 < n_slabs) {
-                const uint32_t off = uint32_t(s + 2) * (kTileK * 2 / 16);
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    xr[q] = xb[xo[q] + off];
-                    ar[q] = ab[ao[q] + off];
-                }
-            }
-        }
-        NTS_LOAD_FRAGS(2, xf0, af0)
-        NTS_MFMAS(xf1, af1)
-        NTS_LOAD_FRAGS(3, xf1, af1)
-        NTS_MFMAS(xf0, af0)
-        NTS_MFMAS(xf1, af1)
-        nts_lds_barrier();                              // LDS-only wait: the loads of slab s+2 stay in flight; buffer s&1 is free, buffer (s+1)&1 is complete
+        const uint32_t off = uint32_t(min(s + 2, n_slabs - 1)) * (kTileK * 2 / 16);
+        NTS_KSTEP(xf0, af0, 0, xs, 1, xf1, af1, 2)
+        NTS_KSTEP(xf1, af1, 16, xs, 2, xf0, af0, 2)
+        NTS_KSTEP(xf0, af0, 32, xs, 3, xf1, af1, 1)
+        nts_lds_barrier();
+        NTS_KSTEP(xf1, af1, 48, nx, 0, xf0, af0, 2)
     }
-#undef NTS_LOAD_FRAGS
-#undef NTS_MFMAS
+#undef NTS_READ_FRAG
+#undef NTS_STORE_ONE
+#undef NTS_LOAD_ONE
+#undef NTS_KSTEP
     // D[i = (v/4)*8 + (lane/32)*4 + v%4][j = lane%32]: batch row i, weight row j
 #pragma unroll
     for (int a = 0; a < 4; ++a)
