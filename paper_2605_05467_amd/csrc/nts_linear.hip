@@ -418,20 +418,44 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 #undef NTS_STORE_ONE
 #undef NTS_LOAD_ONE
 #undef NTS_KSTEP
-    // D[i = (v/4)*8 + (lane/32)*4 + v%4][j = lane%32]: batch row i, weight row j
+    // Epilogue.  D[i = (v/4)*8 + (lane/32)*4 + v%4][j = lane%32]: batch row i, weight row j, so a
+    // lane holds a column of the output and storing from the accumulators means 2-byte stores,
+    // 64 bytes per row and instruction: 26 us per wave of tiles against 1.5 us per slab.  Instead
+    // each wavefront rounds a 32 x 128 strip to 16 bits, turns it through its own piece of LDS
+    // and writes whole 256-byte row segments, 16 bytes per lane.
+    nts_lds_barrier();                                  // every wavefront is done with the tile buffers
+    {
+        constexpr int kOutPitch = 128 * 2 + 16;         // bytes per strip row in LDS
+        unsigned char *strip = lds + wv * 32 * kOutPitch;
+        const int orow = lane >> 4, ocol = (lane & 15) * 8;
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < 4; ++a) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int n = n0 + wn * 128 + b * 32 + fr;
-            if (n < Nn) {
+            for (int b = 0; b < 4; ++b)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + wm * 128 + a * 32 + (v / 4) * 8 + fg * 4 + (v % 4);
-                    if (m < M) Y[int64_t(m) * ldy + n] = E::round(acc[a][b][v]);
+                for (int v = 0; v < 16; ++v)
+                    *reinterpret_cast<uint16_t *>(strip + ((v / 4) * 8 + fg * 4 + (v % 4)) * kOutPitch + (b * 32 + fr) * 2) =
+                        E::round(acc[a][b][v]);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the strip is complete (LDS works in order)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int r = j * 4 + orow;
+                const u32x4 val = *reinterpret_cast<const u32x4 *>(strip + r * kOutPitch + ocol * 2);
+                const int m = m0 + wm * 128 + a * 32 + r, n = n0 + wn * 128 + ocol;
+                if (m < M) {
+                    uint16_t *dst = Y + int64_t(m) * ldy + n;
+                    if (n + 8 <= Nn) {
+                        *reinterpret_cast<u32x4 *>(dst) = val;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (n + e < Nn) dst[e] = uint16_t(val[e >> 1] >> ((e & 1) * 16));
+                    }
                 }
             }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // strip read before it is overwritten
         }
+    }
 }
 
 }  // namespace
@@ -527,12 +551,13 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
     return hipGetLastError();
 }
 
-// The tiled kernel pays off once its 256 x 256 tiles fill the chip; below that the streaming
-// kernel (several batch tiles per weight block) is faster.
+// The tiled kernel pays off once its 256 x 256 tiles occupy most of the chip (measured
+// break-even near 150 tiles); below that the streaming kernel (several batch tiles per weight
+// block, K splits) is faster.
 bool nts_linear_use_tiled(int M, int Nn)
 {
     const int64_t tiles = int64_t((M + kTileM - 1) / kTileM) * ((Nn + kTileN - 1) / kTileN);
-    return M > 256 && tiles >= 224;
+    return M > 256 && tiles >= 160;
 }
 
 hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,

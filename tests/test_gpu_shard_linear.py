@@ -100,7 +100,7 @@ def test_large_batches_tile_edges(env, M, split):
 @pytest.mark.parametrize("M", [520, 777])
 @pytest.mark.parametrize("split", ["out", "in"])
 def test_tiled_kernel_ragged_edges(env, M, split):
-    """Outputs with at least 224 tiles of 256 x 256 go to the tiled matrix-core
+    """Outputs with at least 160 tiles of 256 x 256 go to the tiled matrix-core
     kernel: ragged edges in both output dimensions, both element formats."""
     tp = 2
     n_out, n_in = (2 * 19000, 256) if split == "out" else (19000, 2 * 256)
