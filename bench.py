@@ -282,6 +282,25 @@ def linear_bench(args, torch, b):
                 del graph
         del W
     b.nts_free(ctx)
+    if not args.no_cpu_baseline:
+        # the oracle (slice, then fp64 matmul of the exact 16-bit values) timed beside it on the host
+        import numpy as np
+        import threadpoolctl
+        from oracle import shard_linear as osl
+        from workload.linear import linear_inputs
+        n_out, n_in, split = LAYERS["8b_gate_up"]
+        M, tp = 2048, 1
+        Xh, Wh = linear_inputs(11, M, n_out, n_in, x_cols=n_in)
+        X64, W64 = osl.bf16_to_f64(Xh), osl.bf16_to_f64(Wh)
+        t0 = time.perf_counter()
+        osl.shard_linear(X64, W64, tp, tp - 1, split)
+        dt = time.perf_counter() - t0
+        threads = max((p_["num_threads"] for p_ in threadpoolctl.threadpool_info()), default=1)
+        flops = 2.0 * 2 * M * (n_out // tp) * n_in             # the product and the error-bound product
+        print(json.dumps({"linear_cpu_baseline": {"value": flops / dt / 1e12, "unit": "TFLOP/s (fp64)", "cores": threads,
+                                                  "kind": "oracle", "seconds": dt,
+                                                  "sample": f"8b_gate_up TP{tp} rank {tp - 1}, M = {M}: slice + two "
+                                                            f"{M} x {n_out // tp} x {n_in} fp64 products"}}), flush=True)
 
 
 def planner_bench():
