@@ -115,6 +115,30 @@ class Pair:
         return info
 
 
+def copy_ceiling(torch, b, ctx, stream):
+    """What a plain linear copy reaches on this GPU, through the same mover: nts_run_pack with
+    the identity slot list and whole rows is a straight 1 GiB copy (read once, write once)."""
+    import numpy as np
+    L, H, D, T = 4, 8, 128, 65536
+    pool = torch.empty(L * 2 * T * H * D * 2, dtype=torch.uint8, device="cuda").fill_(7)
+    out = torch.empty_like(pool)
+    plan = b.nts_plan_create(ctx, L=L, D=D, elem_bytes=2, page_size=1, Hs=H, Hd=H, src_head_off=0, dst_head_off=0,
+                             w=H, S_src=T, S_dst=T, ctx_len=[T], src_pages=np.arange(T, dtype=np.int32),
+                             dst_pages=np.arange(T, dtype=np.int32), staging_bytes=0, flags=0)
+    sp = b.layer_ptrs(pool.data_ptr(), L, T * H * D * 2)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):
+        b.nts_run_pack(plan, sp, out.data_ptr(), stream)
+    n = 20
+    e0.record()
+    for _ in range(n):
+        b.nts_run_pack(plan, sp, out.data_ptr(), stream)
+    e1.record()
+    torch.cuda.synchronize()
+    b.nts_plan_free(plan)
+    return 2.0 * pool.numel() * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def measured_traffic(workload: str):
     """HBM bytes per stage-kernel launch from the committed rocprofv3 --pmc summary, if any."""
     path = os.path.join(ROOT, "profiles", f"nts_stage_kernel_{workload}_pmc.txt")
@@ -414,6 +438,10 @@ def main():
     avg_launch_ms = kernel_ms / launches
     achieved = alg_bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
     traffic = measured_traffic(args.workload)
+    n_pairs = len(pairs)
+    del pairs, staging
+    torch.cuda.empty_cache()
+    ceiling = copy_ceiling(torch, b, ctx, stream)
 
     out = {
         "metric": "hot-path items/sec on 1 MI355X (fragments/s through route+plan+pack+staging+unpack)",
@@ -425,19 +453,21 @@ def main():
         "config": {"workload": f"{args.workload}: {WORKLOAD_DESC[args.workload]}",
                    "tokens": T, "fragments": F, "fragment_bytes": infos[0].frag_bytes,
                    "payload_bytes": X, "staging_bytes_each": infos[0].chunk_bytes,
-                   "stage_launches_per_step": launches, "pairs": len(pairs),
+                   "stage_launches_per_step": launches, "pairs": n_pairs,
                    "pairs_run_as": "one batch (nts_run_migrate_batch)" if batch else "one call per pair"},
         "tokens_per_s": T / (ms_per_step * 1e-3),
         "payload_GBps": X / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "kernel": "nts_stage_kernel<16> (pack chunk k || unpack chunk k-1)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "copy_ceiling": ceiling, "frac_of_copy_ceiling": achieved / ceiling,
+                     "copy_ceiling_how": "plain 1 GiB linear copy through the same mover (identity slot list), "
+                                         "measured in this run",
                      "algorithmic_bytes_per_launch": alg_bytes_per_launch,
                      "avg_launch_ms": avg_launch_ms, "launches_per_step": launches,
                      "timing": "HIP events on the launch stream around each step's stage launches "
                                "(includes the gaps between back-to-back launches)"},
     }
-    del pairs, staging
     b.nts_free(ctx)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)
