@@ -484,16 +484,18 @@ static hipError_t launch_stream_one(const uint16_t *X, int64_t ldx, const uint16
 // Configuration of the streaming kernel for a problem: the smallest batch tile that holds the
 // batch (at most 256 rows per tile; longer batches take several tiles, whose workgroups share
 // the weight block through one XCD's L2), then the workgroup width and K split with the
-// smallest estimated time.  The estimate (microseconds, fitted to measurements on MI355X):
-// a compute unit with four consumer wavefronts needs t_slab per 64-wide slab, 0.75 for tiles
-// up to 128 rows (the rate at which one compute unit can pull weight bytes) and more for
-// taller tiles (matrix-core and LDS work); a lone narrow workgroup is latency-bound at about
-// 0.35 per slab; workgroups run in waves that fill the 256 compute units, and every wave pays
-// about 3 for filling and draining its pipelines; a split costs a second launch (about 5)
-// plus writing and reading splits * M * Nn fp32 partial sums at about 4 TB/s.  A split keeps
-// at least four slabs and the workspace stays under 512 MiB.  Narrow workgroups (one consumer)
-// are considered only for batches up to 256 rows and shards up to 16 MiB (measured: no gain
-// above that); every departure from the plain configuration must win by 5 %.
+// smallest estimated time.  The estimate is in microseconds and its constants are fitted to
+// measurements on MI355X.  One compute unit pulls weight bytes at about 24 GB/s however many
+// wavefronts ask, so a four-consumer workgroup needs t_slab per 64-wide slab (0.66 for
+// batches up to 32 rows, 0.75 up to 128, more for taller tiles: matrix-core and LDS work), a
+// one-consumer workgroup a quarter of that but not less than 0.21 (latency), and workgroups
+// that share a compute unit share its rate.  Every wave of workgroups pays a fixed cost for
+// filling and draining its pipelines (4 wide, 1 narrow for batches up to 32 rows; 3
+// otherwise).  A split costs a second launch (3 to 5) plus writing and reading
+// splits * M * Nn fp32 partial sums at about 4 TB/s; it keeps at least four slabs, and the
+// workspace stays under 512 MiB.  One-consumer workgroups are considered for batches up to
+// 32 rows, and up to 256 rows on shards up to 16 MiB (measured: no gain otherwise).  More
+// splits must win by 5 %, narrow workgroups by 10 %.
 NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
 {
     NtsStreamCfg c;
@@ -502,33 +504,42 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
     c.nsets = c.mt <= 4 ? 4 : 3;
     const int tiles_m = (M + 32 * c.mt - 1) / (32 * c.mt);
     const int n_slabs = K / kStrK;
-    const double t_slab = c.mt <= 4 ? 0.75 : c.mt == 6 ? 1.1 : 1.45;
+    const bool small = c.mt == 1;
+    const double t_slab = small ? 0.66 : c.mt <= 4 ? 0.75 : c.mt == 6 ? 1.1 : 1.45;
+    const double split_cost = small ? 3. : 5.;
     const double out_elems = double(M) * Nn;
-    const bool narrow_ok = M <= 256 && c.mt != 3 && c.mt != 6 && int64_t(Nn) * K * 2 <= (int64_t(16) << 20);
+    const bool narrow_ok = small || (M <= 256 && c.mt != 3 && c.mt != 6 && int64_t(Nn) * K * 2 <= (int64_t(16) << 20));
     double best_t = 0.;
     c.cw = 4;
     c.splits = 1;
     for (int cw = 4; cw >= 1; cw -= 3) {
         if (cw == 1 && !narrow_ok) break;
         const int64_t wgs = int64_t(tiles_m) * ((Nn + 32 * cw - 1) / (32 * cw));
-        const int per_cu_max = 4 / cw;                  // workgroups that share a compute unit
+        const double t_wg = cw == 4 ? t_slab : std::max(0.21, t_slab / 4.);
+        const double fixed = !small ? 3. : cw == 4 ? 4. : 1.;
+        const int per_cu = 4 / cw;                      // workgroups a compute unit holds at a time
+        const double win = cw == 4 ? 0.95 : 0.90;
+        double best_cw = 0.;
+        int best_splits = 0;
         for (int splits = 1; splits <= 32 && splits <= (n_slabs >= 4 ? n_slabs / 4 : 1); ++splits) {
             const int sps = (n_slabs + splits - 1) / splits;
             if ((n_slabs + sps - 1) / sps != splits) continue;              // would leave an empty split
             if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) break;
             const int64_t total = wgs * splits;
-            const double waves = double((total + 256 * per_cu_max - 1) / (256 * per_cu_max));
-            const int64_t per_cu = std::min<int64_t>(per_cu_max, (total + 255) / 256);
-            const double t_wg = std::max(0.35, t_slab * double(per_cu) * cw / 4.);
-            double t = waves * (sps * t_wg + 3.);
-            if (splits > 1) t += 5. + out_elems * splits * 8. / 4.0e6;
-            if ((cw == 4 && splits == 1) || t < 0.95 * best_t) {
-                c.cw = cw;
-                c.splits = splits;
-                best_t = t;
+            double t = double((total + 255) / 256) * sps * t_wg + fixed * double((total + 256 * per_cu - 1) / (256 * per_cu));
+            if (splits > 1) t += split_cost + out_elems * splits * 8. / 4.0e6;
+            if (best_splits == 0 || t < 0.95 * best_cw) {
+                best_splits = splits;
+                best_cw = t;
             }
         }
+        if (cw == 4 || best_cw < win * best_t) {
+            c.cw = cw;
+            c.splits = best_splits;
+            best_t = best_cw;
+        }
     }
+    if (c.cw == 1 && small) c.nsets = 8;                // a lone consumer needs more weight bytes in flight
     return c;
 }
 
@@ -543,6 +554,7 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
                 : launch_stream_one<Bf16, MT, CW, NS, RT>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st);
     NTS_STR(1, 4, 4, 1) NTS_STR(2, 4, 4, 1) NTS_STR(3, 4, 4, 1) NTS_STR(4, 4, 4, 1) NTS_STR(6, 4, 3, 1) NTS_STR(8, 4, 3, 1)
     NTS_STR(1, 1, 4, 1) NTS_STR(2, 1, 4, 1) NTS_STR(4, 1, 4, 1) NTS_STR(8, 1, 3, 1)
+    NTS_STR(1, 1, 8, 1)
 #undef NTS_STR
     if (e != hipSuccess || c.splits <= 1) return e;
     const int64_t n = int64_t(M) * Nn;
