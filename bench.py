@@ -316,15 +316,17 @@ def linear_bench(args, torch, b):
         M, tp = 2048, 1
         Xh, Wh = linear_inputs(11, M, n_out, n_in, x_cols=n_in)
         X64, W64 = osl.bf16_to_f64(Xh), osl.bf16_to_f64(Wh)
+        reps = 8
         t0 = time.perf_counter()
-        osl.shard_linear(X64, W64, tp, tp - 1, split)
-        dt = time.perf_counter() - t0
+        for _ in range(reps):
+            osl.shard_linear(X64, W64, tp, tp - 1, split)
+        dt = (time.perf_counter() - t0) / reps
         threads = max((p_["num_threads"] for p_ in threadpoolctl.threadpool_info()), default=1)
         flops = 2.0 * 2 * M * (n_out // tp) * n_in             # the product and the error-bound product
         print(json.dumps({"linear_cpu_baseline": {"value": flops / dt / 1e12, "unit": "TFLOP/s (fp64)", "cores": threads,
                                                   "kind": "oracle", "seconds": dt,
                                                   "sample": f"8b_gate_up TP{tp} rank {tp - 1}, M = {M}: slice + two "
-                                                            f"{M} x {n_out // tp} x {n_in} fp64 products"}}), flush=True)
+                                                            f"{M} x {n_out // tp} x {n_in} fp64 products, {reps} passes"}}), flush=True)
 
 
 def planner_bench():
