@@ -67,6 +67,8 @@ def parse_args():
     ap.add_argument("--linear", action="store_true",
                     help="TP-shard-selecting linear layer (Sec. 3.2.1): decode and prefill batches of the "
                          "8B model's four layers at TP 1/2/4/8, one JSON line each")
+    ap.add_argument("--library", action="store_true",
+                    help="with --linear: also time torch.matmul (hipBLASLt) on the same shards, graph-replayed alike")
     ap.add_argument("--planner", action="store_true",
                     help="goodput-efficiency planner (Sec. 3.3.1): planning time at 128 GPUs x 4 tiers (host only)")
     ap.add_argument("--strategies", action="store_true",
@@ -292,6 +294,27 @@ def linear_bench(args, torch, b):
                     torch.cuda.synchronize()
                     ts.append(e0.elapsed_time(e1) * 1e3 / n_launch)
                 us = sorted(ts)[2]
+                lib_us = None
+                if args.library:
+                    # the same shard through torch.matmul (hipBLASLt), replayed from a graph in the same way
+                    Wv = W[:, (tp - 1) * nn:tp * nn, :] if split == "out" else W[:, :, (tp - 1) * k:tp * k]
+                    torch.matmul(X, Wv[0].t(), out=Y)
+                    torch.cuda.synchronize()
+                    lgraph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(lgraph):
+                        for i in range(n_launch):
+                            torch.matmul(X, Wv[i % copies].t(), out=Y)
+                    lgraph.replay()
+                    torch.cuda.synchronize()
+                    ts = []
+                    for _ in range(5):
+                        e0.record()
+                        lgraph.replay()
+                        e1.record()
+                        torch.cuda.synchronize()
+                        ts.append(e0.elapsed_time(e1) * 1e3 / n_launch)
+                    lib_us = sorted(ts)[2]
+                    del lgraph
                 shard_bytes = nn * k * 2
                 # below ~312 flop per weight byte (2.5 PFLOP/s / 8 TB/s) the layer is bound by reading the shard
                 if M <= 256:
@@ -302,7 +325,9 @@ def linear_bench(args, torch, b):
                     roof = {"bound": "mfma", "achieved": ach, "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0}
                 print(json.dumps({"linear": layer, "split": split, "tp": tp, "rank": tp - 1, "M": M, "Nn": nn, "K": k,
                                   "shard_MiB": shard_bytes / 2**20, "us_per_call": us, "dtype": "bf16",
-                                  "k_splits": wsb // (4 * M * nn) if wsb else 1, "roofline": roof}), flush=True)
+                                  "k_splits": wsb // (4 * M * nn) if wsb else 1, "roofline": roof,
+                                  **({"library_us_per_call": lib_us, "vs_library": us / lib_us} if lib_us else {})}),
+                      flush=True)
                 del graph
         del W
     b.nts_free(ctx)

@@ -485,17 +485,17 @@ static hipError_t launch_stream_one(const uint16_t *X, int64_t ldx, const uint16
 // batch (at most 256 rows per tile; longer batches take several tiles, whose workgroups share
 // the weight block through one XCD's L2), then the workgroup width and K split with the
 // smallest estimated time.  The estimate is in microseconds and its constants are fitted to
-// measurements on MI355X.  One compute unit pulls weight bytes at about 24 GB/s however many
-// wavefronts ask, so a four-consumer workgroup needs t_slab per 64-wide slab (0.66 for
-// batches up to 32 rows, 0.75 up to 128, more for taller tiles: matrix-core and LDS work), a
-// one-consumer workgroup a quarter of that but not less than 0.21 (latency), and workgroups
-// that share a compute unit share its rate.  Every wave of workgroups pays a fixed cost for
-// filling and draining its pipelines (4 wide, 1 narrow for batches up to 32 rows; 3
-// otherwise).  A split costs a second launch (3 to 5) plus writing and reading
-// splits * M * Nn fp32 partial sums at about 4 TB/s; it keeps at least four slabs, and the
-// workspace stays under 512 MiB.  One-consumer workgroups are considered for batches up to
-// 32 rows, and up to 256 rows on shards up to 16 MiB (measured: no gain otherwise).  More
-// splits must win by 5 %, narrow workgroups by 10 %.
+// measurements on MI355X.  What bounds a workgroup is the rate at which its compute unit's L1
+// takes in bytes, about 31 GB/s however many wavefronts ask and whether the lines come from
+// HBM or from the L2: per 64-wide slab a workgroup brings in 128 bytes for each of its
+// 32*CW weight rows and 32*MT batch rows, so a slab costs a four-consumer workgroup
+// 0.132 * (4 + MT) and a one-consumer workgroup 0.21 + 0.136 * (MT - 1) (0.21 is latency),
+// and workgroups that share a compute unit share its rate.  Every wave of
+// workgroups pays a fixed cost for filling and draining its pipelines (4 wide, 1 narrow for
+// batches up to 32 rows; 3 otherwise).  A split costs a second launch (3 to 5) plus writing
+// and reading splits * M * Nn fp32 partial sums at about 4 TB/s; it keeps at least four
+// slabs, and the workspace stays under 512 MiB.  Every departure from the plain
+// configuration (more splits, one-consumer workgroups) must win by 5 %.
 NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
 {
     NtsStreamCfg c;
@@ -505,20 +505,17 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
     const int tiles_m = (M + 32 * c.mt - 1) / (32 * c.mt);
     const int n_slabs = K / kStrK;
     const bool small = c.mt == 1;
-    const double t_slab = small ? 0.66 : c.mt <= 4 ? 0.75 : c.mt == 6 ? 1.1 : 1.45;
     const double split_cost = small ? 3. : 5.;
     const double out_elems = double(M) * Nn;
-    const bool narrow_ok = small || (M <= 256 && c.mt != 3 && c.mt != 6 && int64_t(Nn) * K * 2 <= (int64_t(16) << 20));
     double best_t = 0.;
     c.cw = 4;
     c.splits = 1;
     for (int cw = 4; cw >= 1; cw -= 3) {
-        if (cw == 1 && !narrow_ok) break;
+        if (cw == 1 && (c.mt == 3 || c.mt == 6)) break;                     // not instantiated
         const int64_t wgs = int64_t(tiles_m) * ((Nn + 32 * cw - 1) / (32 * cw));
-        const double t_wg = cw == 4 ? t_slab : std::max(0.21, t_slab / 4.);
+        const double t_wg = cw == 4 ? 0.132 * (4 + c.mt) : 0.21 + 0.136 * (c.mt - 1);
         const double fixed = !small ? 3. : cw == 4 ? 4. : 1.;
         const int per_cu = 4 / cw;                      // workgroups a compute unit holds at a time
-        const double win = cw == 4 ? 0.95 : 0.90;
         double best_cw = 0.;
         int best_splits = 0;
         for (int splits = 1; splits <= 32 && splits <= (n_slabs >= 4 ? n_slabs / 4 : 1); ++splits) {
@@ -533,7 +530,7 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
                 best_cw = t;
             }
         }
-        if (cw == 4 || best_cw < win * best_t) {
+        if (cw == 4 || best_cw < 0.95 * best_t) {
             c.cw = cw;
             c.splits = best_splits;
             best_t = best_cw;
