@@ -500,42 +500,52 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
 {
     NtsStreamCfg c;
     const int rows = M < 256 ? M : 256;
-    c.mt = rows <= 32 ? 1 : rows <= 64 ? 2 : rows <= 96 ? 3 : rows <= 128 ? 4 : rows <= 192 ? 6 : 8;
-    c.nsets = c.mt <= 4 ? 4 : 3;
-    const int tiles_m = (M + 32 * c.mt - 1) / (32 * c.mt);
+    const int mt_min = rows <= 32 ? 1 : rows <= 64 ? 2 : rows <= 96 ? 3 : rows <= 128 ? 4 : rows <= 192 ? 6 : 8;
     const int n_slabs = K / kStrK;
-    const bool small = c.mt == 1;
+    const bool small = mt_min == 1;
     const double split_cost = small ? 3. : 5.;
     const double out_elems = double(M) * Nn;
     double best_t = 0.;
+    c.mt = mt_min;
     c.cw = 4;
     c.splits = 1;
-    for (int cw = 4; cw >= 1; cw -= 3) {
-        if (cw == 1 && (c.mt == 3 || c.mt == 6)) break;                     // not instantiated
-        const int64_t wgs = int64_t(tiles_m) * ((Nn + 32 * cw - 1) / (32 * cw));
-        const double t_wg = cw == 4 ? 0.132 * (4 + c.mt) : 0.21 + 0.136 * (c.mt - 1);
-        const double fixed = !small ? 3. : cw == 4 ? 4. : 1.;
-        const int per_cu = 4 / cw;                      // workgroups a compute unit holds at a time
-        double best_cw = 0.;
-        int best_splits = 0;
-        for (int splits = 1; splits <= 32 && splits <= (n_slabs >= 4 ? n_slabs / 4 : 1); ++splits) {
-            const int sps = (n_slabs + splits - 1) / splits;
-            if ((n_slabs + sps - 1) / sps != splits) continue;              // would leave an empty split
-            if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) break;
-            const int64_t total = wgs * splits;
-            double t = double((total + 255) / 256) * sps * t_wg + fixed * double((total + 256 * per_cu - 1) / (256 * per_cu));
-            if (splits > 1) t += split_cost + out_elems * splits * 8. / 4.0e6;
-            if (best_splits == 0 || t < 0.95 * best_cw) {
-                best_splits = splits;
-                best_cw = t;
+    static const int kTiles[] = {8, 6, 4, 3, 2, 1};
+    for (int mt : kTiles) {
+        if (mt > mt_min || (mt == 1 && !small)) continue;
+        const int tiles_m = (M + 32 * mt - 1) / (32 * mt);
+        const int lds_fit = (160 * 1024) / (3 * 32 * mt * kStrPitch);
+        for (int cw = 4; cw >= 1; cw >>= 1) {
+            if (cw == 2 && (mt & (mt - 1)) != 0) continue;                  // not instantiated
+            if (cw == 2 && mt == 1) continue;
+            if (cw == 1 && (mt == 3 || mt == 6)) continue;
+            const int64_t wgs = int64_t(tiles_m) * ((Nn + 32 * cw - 1) / (32 * cw));
+            const double t_wg = cw > 1 ? 0.132 * (cw + mt) : 0.21 + 0.136 * (mt - 1);
+            const double fixed = !small ? 3. : cw == 4 ? 4. : 1.;
+            const int per_cu = 4 / cw < lds_fit ? 4 / cw : lds_fit;     // workgroups a compute unit holds at a time
+            double best_here = 0.;
+            int best_splits = 0;
+            for (int splits = 1; splits <= 32 && splits <= (n_slabs >= 4 ? n_slabs / 4 : 1); ++splits) {
+                const int sps = (n_slabs + splits - 1) / splits;
+                if ((n_slabs + sps - 1) / sps != splits) continue;          // would leave an empty split
+                if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) break;
+                const int64_t total = wgs * splits;
+                double t = double((total + 255) / 256) * sps * t_wg +
+                           fixed * double((total + 256 * per_cu - 1) / (256 * per_cu));
+                if (splits > 1) t += split_cost + out_elems * splits * 8. / 4.0e6;
+                if (best_splits == 0 || t < 0.95 * best_here) {
+                    best_splits = splits;
+                    best_here = t;
+                }
+            }
+            if (best_t == 0. || best_here < 0.95 * best_t) {
+                c.mt = mt;
+                c.cw = cw;
+                c.splits = best_splits;
+                best_t = best_here;
             }
         }
-        if (cw == 4 || best_cw < 0.95 * best_t) {
-            c.cw = cw;
-            c.splits = best_splits;
-            best_t = best_cw;
-        }
     }
+    c.nsets = c.mt <= 4 ? 4 : 3;
     if (c.cw == 1 && small) c.nsets = 8;                // a lone consumer needs more weight bytes in flight
     return c;
 }
@@ -552,6 +562,7 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
     NTS_STR(1, 4, 4, 1) NTS_STR(2, 4, 4, 1) NTS_STR(3, 4, 4, 1) NTS_STR(4, 4, 4, 1) NTS_STR(6, 4, 3, 1) NTS_STR(8, 4, 3, 1)
     NTS_STR(1, 1, 4, 1) NTS_STR(2, 1, 4, 1) NTS_STR(4, 1, 4, 1) NTS_STR(8, 1, 3, 1)
     NTS_STR(1, 1, 8, 1)
+    NTS_STR(2, 2, 4, 1) NTS_STR(4, 2, 4, 1) NTS_STR(8, 2, 3, 1)
 #undef NTS_STR
     if (e != hipSuccess || c.splits <= 1) return e;
     const int64_t n = int64_t(M) * Nn;
