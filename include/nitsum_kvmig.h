@@ -273,6 +273,23 @@ typedef struct nts_linear_desc {
 } nts_linear_desc;
 
 int nts_shard_linear_workspace(const nts_linear_desc *d, size_t *bytes);
+
+/*
+ * Which kernel and launch shape nts_shard_linear uses for a descriptor (host
+ * arithmetic only, no GPU needed; the choice depends on M, the shard's size
+ * and nothing else).  For callers that log or tune around it and for tests
+ * that must reach every kernel variant.  Errors: NTS_EINVAL as above.
+ */
+typedef struct nts_linear_launch {
+    int32_t tiled;       /* 1: 256 x 256 matrix-core tiles; 0: weight-streaming kernel */
+    int32_t tile_rows;   /* batch rows per workgroup */
+    int32_t tile_cols;   /* output columns (weight rows) per workgroup */
+    int32_t k_splits;    /* parts the reduction is cut into; > 1 uses the workspace */
+    int32_t slabs_ahead; /* 64-wide weight slabs a wavefront keeps in flight */
+    int32_t reserved[3];
+} nts_linear_launch;
+
+int nts_shard_linear_launch(const nts_linear_desc *d, nts_linear_launch *out);
 int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, const void *W_full,
                      void *Y, void *workspace, size_t workspace_bytes, void *hip_stream);
 

@@ -42,7 +42,7 @@ EXPORTS = (
     "nts_plan_create", "nts_plan_free", "nts_plan_info", "nts_plan_slots",
     "nts_run_pack", "nts_run_pack_chunk", "nts_run_unpack", "nts_run_unpack_chunk",
     "nts_run_migrate", "nts_run_migrate_batch", "nts_run_migrate_direct", "nts_run_memcpy_baseline",
-    "nts_shard_linear", "nts_shard_linear_workspace",
+    "nts_shard_linear", "nts_shard_linear_workspace", "nts_shard_linear_launch",
     "nts_balanced_block", "nts_goodput_efficiency", "nts_plan_cluster",
 )
 NTS_TP_LEVELS = 4
@@ -67,6 +67,13 @@ class nts_linear_desc(ctypes.Structure):
         ("M", ctypes.c_int32), ("n_out", ctypes.c_int32), ("n_in", ctypes.c_int32), ("tp", ctypes.c_int32),
         ("rank", ctypes.c_int32), ("split", ctypes.c_int32), ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
         ("ldx", ctypes.c_int64), ("ldw", ctypes.c_int64), ("ldy", ctypes.c_int64),
+    ]
+
+
+class nts_linear_launch(ctypes.Structure):
+    _fields_ = [
+        ("tiled", ctypes.c_int32), ("tile_rows", ctypes.c_int32), ("tile_cols", ctypes.c_int32),
+        ("k_splits", ctypes.c_int32), ("slabs_ahead", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3),
     ]
 
 
@@ -110,6 +117,7 @@ _lib.nts_run_migrate_batch.argtypes = [_i, _vp, _vp, _vp, _vp, _vp]
 _lib.nts_run_migrate_direct.argtypes = [_vp, _vp, _vp, _vp]
 _lib.nts_run_memcpy_baseline.argtypes = [_vp, _vp, _vp, _i, _vp, ctypes.POINTER(_i64)]
 _lib.nts_shard_linear_workspace.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(ctypes.c_size_t)]
+_lib.nts_shard_linear_launch.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(nts_linear_launch)]
 _lib.nts_shard_linear.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _d = ctypes.c_double
 _lib.nts_balanced_block.argtypes = [_d, _d, _i, _pi, _pi]
@@ -274,6 +282,16 @@ def nts_shard_linear_workspace(*, M: int, n_out: int, n_in: int, tp: int, rank: 
     if st != NTS_OK:
         raise NtsError(st, "nts_shard_linear_workspace")
     return n.value
+
+
+def nts_shard_linear_launch(*, M: int, n_out: int, n_in: int, tp: int, rank: int, split: int,
+                            ldx: int = 0, ldw: int = 0, ldy: int = 0, dtype: int = 0) -> "nts_linear_launch":
+    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy, dtype)
+    out = nts_linear_launch()
+    st = _lib.nts_shard_linear_launch(ctypes.byref(d), ctypes.byref(out))
+    if st != NTS_OK:
+        raise NtsError(st, "nts_shard_linear_launch")
+    return out
 
 
 def nts_shard_linear(ctx: int, X: int, W_full: int, Y: int, *, M: int, n_out: int, n_in: int, tp: int,

@@ -764,6 +764,19 @@ int nts_shard_linear_workspace(const nts_linear_desc *d, size_t *bytes)
     return NTS_OK;
 }
 
+int nts_shard_linear_launch(const nts_linear_desc *d, nts_linear_launch *out)
+{
+    LinearGeom g;
+    if (!out || linear_geom(d, &g) != NTS_OK) return NTS_EINVAL;
+    *out = nts_linear_launch{};
+    out->tiled = g.tiled ? 1 : 0;
+    out->tile_rows = g.tiled ? 256 : 32 * g.cfg.mt;
+    out->tile_cols = g.tiled ? 256 : 32 * g.cfg.cw * g.cfg.rt;
+    out->k_splits = g.cfg.splits;
+    out->slabs_ahead = g.tiled ? 2 : g.cfg.nsets - 1;
+    return NTS_OK;
+}
+
 int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, const void *W_full, void *Y,
                      void *workspace, size_t workspace_bytes, void *hip_stream)
 {

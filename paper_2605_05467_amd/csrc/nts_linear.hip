@@ -481,21 +481,23 @@ static hipError_t launch_stream_one(const uint16_t *X, int64_t ldx, const uint16
     return hipGetLastError();
 }
 
-// Configuration of the streaming kernel for a problem: the smallest batch tile that holds the
-// batch (at most 256 rows per tile; longer batches take several tiles, whose workgroups share
-// the weight block through one XCD's L2), then the workgroup width and K split with the
-// smallest estimated time.  The estimate is in microseconds and its constants are fitted to
-// measurements on MI355X.  What bounds a workgroup is the rate at which its compute unit's L1
-// takes in bytes, about 31 GB/s however many wavefronts ask and whether the lines come from
-// HBM or from the L2: per 64-wide slab a workgroup brings in 128 bytes for each of its
-// 32*CW weight rows and 32*MT batch rows, so a slab costs a four-consumer workgroup
-// 0.132 * (4 + MT) and a one-consumer workgroup 0.21 + 0.136 * (MT - 1) (0.21 is latency),
-// and workgroups that share a compute unit share its rate.  Every wave of
-// workgroups pays a fixed cost for filling and draining its pipelines (4 wide, 1 narrow for
-// batches up to 32 rows; 3 otherwise).  A split costs a second launch (3 to 5) plus writing
-// and reading splits * M * Nn fp32 partial sums at about 4 TB/s; it keeps at least four
-// slabs, and the workspace stays under 512 MiB.  Every departure from the plain
-// configuration (more splits, one-consumer workgroups) must win by 5 %.
+// Configuration of the streaming kernel for a problem: batch-tile height (any instantiated
+// one up to the smallest that holds the batch, at most 256 rows; a batch longer than the tile
+// takes several, whose workgroups share the weight block through one XCD's L2), workgroup
+// width (4, 2 or 1 consumers) and K split with the smallest estimated time.  The estimate is
+// in microseconds and its constants are fitted to measurements on MI355X.  What bounds a
+// workgroup is the rate at which its compute unit's L1 takes in bytes, about 31 GB/s however
+// many wavefronts ask and whether the lines come from HBM or from the L2: per 64-wide slab a
+// workgroup brings in 128 bytes for each of its 32*CW weight rows and 32*MT batch rows, so a
+// slab costs a workgroup 0.132 * (CW + MT), a one-consumer workgroup 0.21 + 0.136 * (MT - 1)
+// (0.21 is latency), and workgroups that share a compute unit share its rate.  Square-ish
+// tiles take in the fewest bytes per product, small ones fill the chip when the output is
+// small: the estimate weighs the two.  Every wave of workgroups pays a fixed cost for filling
+// and draining its pipelines (4 wide, 1 narrow for batches up to 32 rows; 3 otherwise).  A
+// split costs a second launch (3 to 5) plus writing and reading splits * M * Nn fp32 partial
+// sums at about 4 TB/s; it keeps at least four slabs, and the workspace stays under 512 MiB.
+// Candidates are tried from the plain configuration (tallest tile, four consumers, no split)
+// outwards, and each must beat the best so far by 5 %.
 NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
 {
     NtsStreamCfg c;
@@ -517,7 +519,7 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
         for (int cw = 4; cw >= 1; cw >>= 1) {
             if (cw == 2 && (mt & (mt - 1)) != 0) continue;                  // not instantiated
             if (cw == 2 && mt == 1) continue;
-            if (cw == 1 && (mt == 3 || mt == 6)) continue;
+            if (cw == 1 && (mt == 3 || mt >= 6)) continue;
             const int64_t wgs = int64_t(tiles_m) * ((Nn + 32 * cw - 1) / (32 * cw));
             const double t_wg = cw > 1 ? 0.132 * (cw + mt) : 0.21 + 0.136 * (mt - 1);
             const double fixed = !small ? 3. : cw == 4 ? 4. : 1.;
@@ -560,8 +562,7 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
         e = f16 ? launch_stream_one<F16, MT, CW, NS, RT>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st) \
                 : launch_stream_one<Bf16, MT, CW, NS, RT>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st);
     NTS_STR(1, 4, 4, 1) NTS_STR(2, 4, 4, 1) NTS_STR(3, 4, 4, 1) NTS_STR(4, 4, 4, 1) NTS_STR(6, 4, 3, 1) NTS_STR(8, 4, 3, 1)
-    NTS_STR(1, 1, 4, 1) NTS_STR(2, 1, 4, 1) NTS_STR(4, 1, 4, 1) NTS_STR(8, 1, 3, 1)
-    NTS_STR(1, 1, 8, 1)
+    NTS_STR(1, 1, 8, 1) NTS_STR(2, 1, 4, 1) NTS_STR(4, 1, 4, 1)
     NTS_STR(2, 2, 4, 1) NTS_STR(4, 2, 4, 1) NTS_STR(8, 2, 3, 1)
 #undef NTS_STR
     if (e != hipSuccess || c.splits <= 1) return e;

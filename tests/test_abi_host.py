@@ -93,3 +93,24 @@ def test_linear_workspace_is_whole_partial_sum_planes_and_bounded(b):
     assert seen_split and seen_none
     with pytest.raises(b.NtsError):
         b.nts_shard_linear_workspace(M=4, n_out=64, n_in=72, tp=1, rank=0, split=b.NTS_SPLIT_OUT)
+
+
+def test_linear_launch_query_reaches_every_kernel_variant(b):
+    """The launch query is host arithmetic.  The shapes the GPU suite runs must land
+    on the variant the table names, together they must reach every instantiated
+    variant, and the query must agree with the workspace size."""
+    from linear_cases import CASES, VARIANTS
+    seen = set()
+    for M, Nn, K, rows, cols, is_split in CASES:
+        for sp, n_out, n_in in ((b.NTS_SPLIT_OUT, 2 * Nn, K), (b.NTS_SPLIT_IN, Nn, 2 * K)):
+            kw = dict(M=M, n_out=n_out, n_in=n_in, tp=2, rank=1, split=sp)
+            l = b.nts_shard_linear_launch(**kw)
+            assert (l.tile_rows, l.tile_cols, l.k_splits > 1) == (rows, cols, is_split), (M, Nn, K)
+            assert l.tiled == int((rows, cols) == (256, 256))
+            ws = b.nts_shard_linear_workspace(**kw)
+            assert ws == (l.k_splits * M * Nn * 4 if l.k_splits > 1 else 0)
+            assert 1 <= l.slabs_ahead <= 7
+            seen.add((l.tile_rows, l.tile_cols))
+    assert seen == VARIANTS
+    with pytest.raises(b.NtsError):
+        b.nts_shard_linear_launch(M=0, n_out=64, n_in=64, tp=1, rank=0, split=b.NTS_SPLIT_OUT)

@@ -4,6 +4,7 @@ products in any order plus one rounding to bfloat16."""
 import numpy as np
 import pytest
 
+from linear_cases import CASES
 from oracle import shard_linear as osl
 from workload.linear import LAYERS, linear_inputs
 
@@ -89,12 +90,30 @@ def test_argument_errors(env):
 @pytest.mark.parametrize("M", [65, 96, 130, 192, 200, 256, 300, 777])
 @pytest.mark.parametrize("split", ["out", "in"])
 def test_large_batches_tile_edges(env, M, split):
-    """Wide batches on the weight-streaming kernel: every batch-tile height (96,
-    128, 192, 256 rows), several batch tiles per weight block, K splits, ragged
-    edges in both output dimensions."""
+    """Wide batches on small shards: several batch tiles per weight block, K
+    splits, ragged edges in both output dimensions."""
     run_case(env, M, 96, 512, 2, 1, split, seed=M)
     run_case(env, M, 528, 1024 + 64, 1, 0, split, seed=M + 100, pad=8)
     run_case(env, M, 1024, 2048, 4, 3, split, seed=M + 200)
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "M%d_N%d_K%d_tile%dx%d%s" % (c[:5] + ("_split" if c[5] else "",)))
+@pytest.mark.parametrize("split", ["out", "in"])
+def test_every_kernel_variant(env, case, split):
+    """One shard shape per instantiated kernel variant (tile height x workgroup
+    width, with and without a K split, one and several batch tiles), selected at
+    TP level 2 from a full matrix twice the shard, as rank 1; the variant each
+    shape reaches is pinned by the CPU suite."""
+    torch, b, ctx = env
+    M, Nn, K, rows, cols, is_split = case
+    n_out, n_in = (2 * Nn, K) if split == "out" else (Nn, 2 * K)
+    sp = b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN
+    pad = 8 if M % 2 else 0
+    l = b.nts_shard_linear_launch(M=M, n_out=n_out, n_in=n_in, tp=2, rank=1, split=sp, ldx=K + pad,
+                                  ldw=n_in + pad, ldy=Nn + pad)
+    assert (l.tile_rows, l.tile_cols, l.k_splits > 1) == (rows, cols, is_split)
+    run_case(env, M, n_out, n_in, 2, 1, split, seed=M + Nn, pad=pad,
+             dtype="f16" if (M + Nn // 8) % 3 == 0 else "bf16")
 
 
 @pytest.mark.parametrize("M", [520, 777])
