@@ -269,6 +269,7 @@ def linear_bench(args, torch, b):
                 kw = dict(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=tp - 1,
                           split=b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN)
                 wsb = b.nts_shard_linear_workspace(**kw)
+                how = b.nts_shard_linear_launch(**kw)
                 ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
 
                 def launch(i):
@@ -325,7 +326,9 @@ def linear_bench(args, torch, b):
                     roof = {"bound": "mfma", "achieved": ach, "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0}
                 print(json.dumps({"linear": layer, "split": split, "tp": tp, "rank": tp - 1, "M": M, "Nn": nn, "K": k,
                                   "shard_MiB": shard_bytes / 2**20, "us_per_call": us, "dtype": "bf16",
-                                  "k_splits": wsb // (4 * M * nn) if wsb else 1, "roofline": roof,
+                                  "kernel": "tiled" if how.tiled else "stream",
+                                  "tile": "%dx%d" % (how.tile_rows, how.tile_cols), "k_splits": how.k_splits,
+                                  "roofline": roof,
                                   **({"library_us_per_call": lib_us, "vs_library": us / lib_us} if lib_us else {})}),
                       flush=True)
                 del graph
