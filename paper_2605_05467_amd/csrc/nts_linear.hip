@@ -37,6 +37,10 @@ __device__ __forceinline__ uint16_t f32_to_f16_rne(float f)
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // The two 16-bit element formats: matrix-core instructions and the final rounding.
 struct Bf16 {
@@ -44,12 +48,23 @@ struct Bf16 {
     static __device__ __forceinline__ f32x4 mfma16(vec8 a, vec8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
     static __device__ __forceinline__ f32x16 mfma32(vec8 a, vec8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
     static __device__ __forceinline__ uint16_t round(float f) { return f32_to_bf16_rne(f); }
+    // two values at once (lo in bits 0..15): one v_cvt_pk_bf16_f32, round to nearest even
+    static __device__ __forceinline__ uint32_t round2(float lo, float hi)
+    {
+        const f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    }
 };
 struct F16 {
     typedef f16x8 vec8;
     static __device__ __forceinline__ f32x4 mfma16(vec8 a, vec8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
     static __device__ __forceinline__ f32x16 mfma32(vec8 a, vec8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
     static __device__ __forceinline__ uint16_t round(float f) { return f32_to_f16_rne(f); }
+    static __device__ __forceinline__ uint32_t round2(float lo, float hi)
+    {
+        const f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    }
 };
 
 // Y[m][n] = sum over splits, in split order, rounded once
@@ -218,7 +233,7 @@ __global__ __launch_bounds__(64 * (CW + 1)) void nts_linear_stream_kernel(
             if (i + 3 < kSteps) { NTS_STR_FRAG(xf[(i + 3) % 4], xs, i + 3) }                   \
             else { NTS_STR_FRAG(xf[(i + 3) % 4], nx, i + 3 - kSteps) }                         \
             _Pragma("unroll") for (int r = 0; r < RT; ++r)                                     \
-                acc[i % MT][r] = E::mfma32(xf[i % 4], __builtin_bit_cast(vec8, w[(U) % NSETS][r][i / MT]), \
+                acc[i % MT][r] = E::mfma32(__builtin_bit_cast(vec8, w[(U) % NSETS][r][i / MT]), xf[i % 4], \
                                            acc[i % MT][r]);                                    \
             __builtin_amdgcn_sched_barrier(0);                                                 \
         }                                                                                      \
@@ -247,23 +262,47 @@ __global__ __launch_bounds__(64 * (CW + 1)) void nts_linear_stream_kernel(
 #undef NTS_STR_PHYS
 #undef NTS_STR_LOAD_W
 #undef NTS_STR_FRAG
-    // D[i = (v/4)*8 + (lane/32)*4 + v%4][j = lane%32]: batch row i, weight row j
+    // The weight rows are the first MFMA operand, so D[i][j] has i = weight row, j = batch row:
+    // lane (fr, fg) holds, of batch row fr of tile t, the output columns (v/4)*8 + fg*4 + v%4 of
+    // tile r, four neighbours per group of v: one 8-byte store of four rounded values (two per
+    // conversion instruction), or one 16-byte store of partial sums.
+    const bool vec_ok = (Nn & 3) == 0;
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
+    for (int t = 0; t < MT; ++t) {
+        const int m = m0 + t * 32 + fr;
+        if (m >= M) continue;
 #pragma unroll
-        for (int r = 0; r < RT; ++r) {
-            const int n = n0 + r * 32 + fr;
-            if (n < Nn) {
+        for (int r = 0; r < RT; ++r)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + t * 32 + (v / 4) * 8 + fg * 4 + (v % 4);
-                    if (m < M) {
-                        if (part) part[(int64_t(split) * M + m) * Nn + n] = acc[t][r][v];
-                        else Y[int64_t(m) * ldy + n] = E::round(acc[t][r][v]);
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + r * 32 + g * 8 + fg * 4;
+                if (n >= Nn) continue;
+                const float v0 = acc[t][r][4 * g], v1 = acc[t][r][4 * g + 1], v2 = acc[t][r][4 * g + 2],
+                            v3 = acc[t][r][4 * g + 3];
+                if (part) {
+                    float *dst = part + (int64_t(split) * M + m) * Nn + n;
+                    if (vec_ok) {                       // then n + 4 <= Nn and the address is 16-byte aligned
+                        const f32x4 q = {v0, v1, v2, v3};
+                        *reinterpret_cast<f32x4 *>(dst) = q;
+                    } else {
+                        dst[0] = v0;
+                        if (n + 1 < Nn) dst[1] = v1;
+                        if (n + 2 < Nn) dst[2] = v2;
+                        if (n + 3 < Nn) dst[3] = v3;
+                    }
+                } else {
+                    uint16_t *dst = Y + int64_t(m) * ldy + n;
+                    const u32x2 pk = {E::round2(v0, v1), E::round2(v2, v3)};
+                    if (n + 4 <= Nn) {
+                        *reinterpret_cast<u32x2 *>(dst) = pk;
+                    } else {
+                        dst[0] = uint16_t(pk[0]);
+                        if (n + 1 < Nn) dst[1] = uint16_t(pk[0] >> 16);
+                        if (n + 2 < Nn) dst[2] = uint16_t(pk[1]);
                     }
                 }
             }
-        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -326,24 +365,26 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     const int n_slabs = K / kTileK;
     const int st_off = sr * kPitch + sv * 16;           // where this thread's staged vectors go
 
-    // prologue: slab 0 into LDS buffer 0, slab 1 into registers
+    // prologue: slab 0 into LDS buffer 0, slab 1 into registers; both slabs' loads are issued
+    // before the first wait, so the tile starts after one memory latency, not two
     u32x4 xr[8], ar[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        xr[q] = xb[xo[q]];
-        ar[q] = ab[ao[q]];
-    }
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        *reinterpret_cast<u32x4 *>(lds + st_off + 32 * q * kPitch) = xr[q];
-        *reinterpret_cast<u32x4 *>(lds + kTileM * kPitch + st_off + 32 * q * kPitch) = ar[q];
-    }
     {
+        u32x4 x0[8], a0[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            x0[q] = xb[xo[q]];
+            a0[q] = ab[ao[q]];
+        }
         const uint32_t off = uint32_t(min(1, n_slabs - 1)) * (kTileK * 2 / 16);
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             xr[q] = xb[xo[q] + off];
             ar[q] = ab[ao[q] + off];
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            *reinterpret_cast<u32x4 *>(lds + st_off + 32 * q * kPitch) = x0[q];
+            *reinterpret_cast<u32x4 *>(lds + kTileM * kPitch + st_off + 32 * q * kPitch) = a0[q];
         }
     }
     nts_lds_barrier();
@@ -386,7 +427,7 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
         _Pragma("unroll") for (int a = 0; a < 4; ++a)                                                  \
             _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                            \
                 const int i = a * 4 + b, g = (G0) + i;       /* constants after unrolling */           \
-                acc[a][b] = E::mfma32(XF[a], AF[b], acc[a][b]);                                       \
+                acc[a][b] = E::mfma32(AF[b], XF[a], acc[a][b]);                                       \
                 if (i % (STRIDE) == 0 && i / (STRIDE) < 8) NTS_READ_FRAG(NBASE, NKK, i / (STRIDE), NXF, NAF) \
                 if (g % 3 == 0 && g / 3 < 16) NTS_STORE_ONE(g / 3)                                     \
                 if (g % 3 == 1 && g / 3 < 16) NTS_LOAD_ONE(g / 3)                                      \
@@ -418,14 +459,16 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 #undef NTS_STORE_ONE
 #undef NTS_LOAD_ONE
 #undef NTS_KSTEP
-    // Epilogue.  D[i = (v/4)*8 + (lane/32)*4 + v%4][j = lane%32]: batch row i, weight row j, so a
-    // lane holds a column of the output and storing from the accumulators means 2-byte stores,
-    // 64 bytes per row and instruction: 26 us per wave of tiles against 1.5 us per slab.  Instead
-    // each wavefront rounds a 32 x 128 strip to 16 bits, turns it through its own piece of LDS
-    // and writes whole 256-byte row segments, 16 bytes per lane.
+    // Epilogue.  The weight fragment is the first MFMA operand, so D[i][j] has i = weight row,
+    // j = batch row: lane (fr, fg) holds, of batch row fr of tile a, the output columns
+    // (v/4)*8 + fg*4 + v%4 of tile b, four neighbours per group of v.  Stored from there a row
+    // would get 16 bytes per instruction; instead each wavefront rounds a 32 x 128 strip to 16
+    // bits two values per instruction, puts it into its own piece of LDS 8 bytes per lane (row
+    // pitch 264 B: the 32 rows of a store fall into different banks) and writes whole 256-byte
+    // row segments, 16 bytes per lane.
     nts_lds_barrier();                                  // every wavefront is done with the tile buffers
     {
-        constexpr int kOutPitch = 128 * 2 + 16;         // bytes per strip row in LDS
+        constexpr int kOutPitch = 128 * 2 + 8;          // bytes per strip row in LDS
         unsigned char *strip = lds + wv * 32 * kOutPitch;
         const int orow = lane >> 4, ocol = (lane & 15) * 8;
 #pragma unroll
@@ -433,14 +476,18 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 #pragma unroll
             for (int b = 0; b < 4; ++b)
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    *reinterpret_cast<uint16_t *>(strip + ((v / 4) * 8 + fg * 4 + (v % 4)) * kOutPitch + (b * 32 + fr) * 2) =
-                        E::round(acc[a][b][v]);
+                for (int g = 0; g < 4; ++g) {
+                    const u32x2 pk = {E::round2(acc[a][b][4 * g], acc[a][b][4 * g + 1]),
+                                      E::round2(acc[a][b][4 * g + 2], acc[a][b][4 * g + 3])};
+                    *reinterpret_cast<u32x2 *>(strip + fr * kOutPitch + (b * 32 + g * 8 + fg * 4) * 2) = pk;
+                }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the strip is complete (LDS works in order)
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int r = j * 4 + orow;
-                const u32x4 val = *reinterpret_cast<const u32x4 *>(strip + r * kOutPitch + ocol * 2);
+                const u32x2 lo = *reinterpret_cast<const u32x2 *>(strip + r * kOutPitch + ocol * 2);
+                const u32x2 hi = *reinterpret_cast<const u32x2 *>(strip + r * kOutPitch + ocol * 2 + 8);
+                const u32x4 val = {lo[0], lo[1], hi[0], hi[1]};
                 const int m = m0 + wm * 128 + a * 32 + r, n = n0 + wn * 128 + ocol;
                 if (m < M) {
                     uint16_t *dst = Y + int64_t(m) * ldy + n;
