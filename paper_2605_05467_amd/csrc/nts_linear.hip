@@ -532,70 +532,74 @@ static hipError_t launch_stream_one(const uint16_t *X, int64_t ldx, const uint16
 // one up to the smallest that holds the batch, at most 256 rows; a batch longer than the tile
 // takes several, whose workgroups share the weight block through one XCD's L2), workgroup
 // width (4, 2 or 1 consumers) and K split with the smallest estimated time.  The estimate is
-// in microseconds and its constants are fitted to measurements on MI355X.  What bounds a
-// workgroup is the rate at which its compute unit's L1 takes in bytes, about 31 GB/s however
-// many wavefronts ask and whether the lines come from HBM or from the L2: per 64-wide slab a
-// workgroup brings in 128 bytes for each of its 32*CW weight rows and 32*MT batch rows, so a
-// slab costs a workgroup 0.132 * (CW + MT), a one-consumer workgroup 0.21 + 0.136 * (MT - 1)
-// (0.21 is latency), and workgroups that share a compute unit share its rate.  Square-ish
-// tiles take in the fewest bytes per product, small ones fill the chip when the output is
-// small: the estimate weighs the two.  Every wave of workgroups pays a fixed cost for filling
-// and draining its pipelines (4 wide, 1 narrow for batches up to 32 rows; 3 otherwise).  A
-// split costs a second launch (3 to 5) plus writing and reading splits * M * Nn fp32 partial
-// sums at about 4 TB/s; it keeps at least four slabs, and the workspace stays under 512 MiB.
-// Candidates are tried from the plain configuration (tallest tile, four consumers, no split)
-// outwards, and each must beat the best so far by 5 %.
+// in microseconds, from measurements on MI355X of every instantiation at one workgroup per
+// compute unit:
+//   * per 64-wide slab a workgroup needs kSlabUs[width][height], set by what its compute unit
+//     can take in and feed to the matrix cores; workgroups that share a compute unit share
+//     that rate (two take twice as long), so the slabs cost rounds * slabs * kSlabUs with
+//     rounds = workgroups / 256 rounded up;
+//   * all of them together cannot read the shard faster than about 6.1 TB/s;
+//   * every round pays kRoundUs[width][height] for filling and draining its pipelines and for
+//     the output (rounds that fit a compute unit together pay it once), every launch 2.5;
+//   * a split adds the second launch plus writing and reading splits * M * Nn fp32 partial
+//     sums at about 4 TB/s; it keeps at least four slabs and the workspace under 512 MiB.
+// Square-ish tiles take in the fewest bytes per product, small ones fill the chip when the
+// output is small: the estimate weighs the two.  Candidates are tried from the plain
+// configuration (tallest tile, four consumers, no split) outwards, and each must beat the
+// best so far by 5 %.
+struct StreamVariant {
+    int mt, cw;
+    double slab_us, round_us;
+};
+static const StreamVariant kStreamVariants[] = {
+    {8, 4, 1.237, 7.2}, {6, 4, 1.047, 6.2}, {4, 4, 0.822, 4.9}, {4, 2, 0.529, 2.9},
+    {4, 1, 0.402, 2.45}, {3, 4, 0.662, 4.2}, {2, 4, 0.556, 3.7}, {2, 2, 0.343, 2.0}, {2, 1, 0.243, 1.3},
+    {1, 4, 0.490, 3.0}, {1, 1, 0.178, 1.25},
+};
+
 NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
 {
     NtsStreamCfg c;
     const int rows = M < 256 ? M : 256;
     const int mt_min = rows <= 32 ? 1 : rows <= 64 ? 2 : rows <= 96 ? 3 : rows <= 128 ? 4 : rows <= 192 ? 6 : 8;
     const int n_slabs = K / kStrK;
-    const bool small = mt_min == 1;
-    const double split_cost = small ? 3. : 5.;
     const double out_elems = double(M) * Nn;
+    const double hbm_us = double(Nn) * K * 2. / 6.1e6;
     double best_t = 0.;
     c.mt = mt_min;
     c.cw = 4;
     c.splits = 1;
-    static const int kTiles[] = {8, 6, 4, 3, 2, 1};
-    for (int mt : kTiles) {
-        if (mt > mt_min || (mt == 1 && !small)) continue;
-        const int tiles_m = (M + 32 * mt - 1) / (32 * mt);
-        const int lds_fit = (160 * 1024) / (3 * 32 * mt * kStrPitch);
-        for (int cw = 4; cw >= 1; cw >>= 1) {
-            if (cw == 2 && (mt & (mt - 1)) != 0) continue;                  // not instantiated
-            if (cw == 2 && mt == 1) continue;
-            if (cw == 1 && (mt == 3 || mt >= 6)) continue;
-            const int64_t wgs = int64_t(tiles_m) * ((Nn + 32 * cw - 1) / (32 * cw));
-            const double t_wg = cw > 1 ? 0.132 * (cw + mt) : 0.21 + 0.136 * (mt - 1);
-            const double fixed = !small ? 3. : cw == 4 ? 4. : 1.;
-            const int per_cu = 4 / cw < lds_fit ? 4 / cw : lds_fit;     // workgroups a compute unit holds at a time
-            double best_here = 0.;
-            int best_splits = 0;
-            for (int splits = 1; splits <= 32 && splits <= (n_slabs >= 4 ? n_slabs / 4 : 1); ++splits) {
-                const int sps = (n_slabs + splits - 1) / splits;
-                if ((n_slabs + sps - 1) / sps != splits) continue;          // would leave an empty split
-                if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) break;
-                const int64_t total = wgs * splits;
-                double t = double((total + 255) / 256) * sps * t_wg +
-                           fixed * double((total + 256 * per_cu - 1) / (256 * per_cu));
-                if (splits > 1) t += split_cost + out_elems * splits * 8. / 4.0e6;
-                if (best_splits == 0 || t < 0.95 * best_here) {
-                    best_splits = splits;
-                    best_here = t;
-                }
+    for (const StreamVariant &v : kStreamVariants) {
+        if (v.mt > mt_min || (v.mt == 1 && mt_min > 1)) continue;
+        const int tiles_m = (M + 32 * v.mt - 1) / (32 * v.mt);
+        const int lds_fit = (160 * 1024) / (3 * 32 * v.mt * kStrPitch);
+        const int per_cu = 4 / v.cw < lds_fit ? 4 / v.cw : lds_fit;     // workgroups a compute unit holds at a time
+        const int64_t wgs = int64_t(tiles_m) * ((Nn + 32 * v.cw - 1) / (32 * v.cw));
+        double best_here = 0.;
+        int best_splits = 0;
+        for (int splits = 1; splits <= 32 && splits <= (n_slabs >= 4 ? n_slabs / 4 : 1); ++splits) {
+            const int sps = (n_slabs + splits - 1) / splits;
+            if ((n_slabs + sps - 1) / sps != splits) continue;              // would leave an empty split
+            if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) break;
+            const int64_t total = wgs * splits;
+            const double cu_us = double((total + 255) / 256) * sps * v.slab_us;
+            double t = 2.5 + (cu_us > hbm_us ? cu_us : hbm_us) +
+                       v.round_us * double((total + 256 * per_cu - 1) / (256 * per_cu));
+            if (splits > 1) t += 2.5 + out_elems * splits * 8. / 4.0e6;
+            if (best_splits == 0 || t < 0.95 * best_here) {
+                best_splits = splits;
+                best_here = t;
             }
-            if (best_t == 0. || best_here < 0.95 * best_t) {
-                c.mt = mt;
-                c.cw = cw;
-                c.splits = best_splits;
-                best_t = best_here;
-            }
+        }
+        if (best_t == 0. || best_here < 0.95 * best_t) {
+            c.mt = v.mt;
+            c.cw = v.cw;
+            c.splits = best_splits;
+            best_t = best_here;
         }
     }
     c.nsets = c.mt <= 4 ? 4 : 3;
-    if (c.cw == 1 && small) c.nsets = 8;                // a lone consumer needs more weight bytes in flight
+    if (c.cw == 1 && c.mt == 1) c.nsets = 8;            // a lone consumer needs more weight bytes in flight
     return c;
 }
 
@@ -610,7 +614,7 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
                 : launch_stream_one<Bf16, MT, CW, NS, RT>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st);
     NTS_STR(1, 4, 4, 1) NTS_STR(2, 4, 4, 1) NTS_STR(3, 4, 4, 1) NTS_STR(4, 4, 4, 1) NTS_STR(6, 4, 3, 1) NTS_STR(8, 4, 3, 1)
     NTS_STR(1, 1, 8, 1) NTS_STR(2, 1, 4, 1) NTS_STR(4, 1, 4, 1)
-    NTS_STR(2, 2, 4, 1) NTS_STR(4, 2, 4, 1) NTS_STR(8, 2, 3, 1)
+    NTS_STR(2, 2, 4, 1) NTS_STR(4, 2, 4, 1)
 #undef NTS_STR
     if (e != hipSuccess || c.splits <= 1) return e;
     const int64_t n = int64_t(M) * Nn;
