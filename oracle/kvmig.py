@@ -11,6 +11,10 @@ Migration"):
   rank, the heads both intervals have in common.
 * ``flatten``: the metadata exchanged before the transfer (request, context
   length, pages) turned into one slot per migrated token.
+* ``runs``: the migrated tokens cut into maximal runs that sit in neighbouring
+  slots on both sides (with small pages a request's KV is scattered over many
+  regions, with a contiguous per-request layout over few: the two layouts of
+  the paper's microbenchmark).
 * ``pack`` / ``unpack`` / ``migrate_direct``: plain loops in C
   (``kvmig_oracle.c``) that gather the moved head slice of every token into a
   contiguous stream, scatter such a stream into the destination pool, or do
@@ -96,6 +100,24 @@ def flatten(ctx_len: Sequence[int], pages: Sequence[int], p: int) -> np.ndarray:
             out.append(int(pages[at + t // p]) * p + t % p)
         at += n_pg
     return np.asarray(out, dtype=np.int32)
+
+
+def runs(sslot: Sequence[int], dslot: Sequence[int]) -> np.ndarray:
+    """Start index of every run, then T: ``[s_0 = 0, s_1, ..., s_{n-1}, T]`` (just
+    ``[0]`` for no tokens).  Token j continues the run of token j-1 exactly when
+    it sits in the next slot on the source side AND in the next slot on the
+    destination side; otherwise it starts a run.  When a fragment is a whole
+    token row on both sides, a run is one contiguous region per (layer, K|V):
+    the regions a per-region copy has to issue (Sec. 3.2.2, the fragmented
+    against the contiguous layout)."""
+    if len(sslot) != len(dslot):
+        raise ValueError("slot lists differ in length")
+    out: List[int] = []
+    for j in range(len(sslot)):
+        if j == 0 or int(sslot[j]) != int(sslot[j - 1]) + 1 or int(dslot[j]) != int(dslot[j - 1]) + 1:
+            out.append(j)
+    out.append(len(sslot))
+    return np.asarray(out if len(sslot) else [0], dtype=np.int32)
 
 
 # ----------------------------------------------------------------------------

@@ -23,6 +23,66 @@ def rand_pool(rng, L, S, Hl, D, dtype=np.uint16):
     return (bits & np.uint64(np.iinfo(dtype).max)).astype(dtype).reshape(L, 2, S, Hl, D)
 
 
+# ------------------------------------------------------------------- runs ---
+
+def test_runs_of_a_hand_written_example():
+    """Written out by hand: source slots break after index 2 and 5, destination
+    slots after index 4 (and 2): boundaries at 0, 3, 5, 6."""
+    s = [10, 11, 12, 40, 41, 42, 7, 8]
+    d = [20, 21, 22, 30, 31, 50, 51, 52]
+    #    run 0       | run 1 | r2 | run 3
+    assert orc.runs(s, d).tolist() == [0, 3, 5, 6, 8]
+    assert orc.runs([], []).tolist() == [0]
+    assert orc.runs([5], [9]).tolist() == [0, 1]
+    with pytest.raises(ValueError):
+        orc.runs([1, 2], [1])
+
+
+def test_runs_closed_forms_of_the_two_layouts():
+    """Contiguous per-request layout with a gap between requests on either
+    side: one run per non-empty request.  Token-granular pages placed so that
+    no two neighbours are adjacent: one run per token.  Pages of p tokens in
+    such a placement: one run per page (a last partial page included)."""
+    ctx_len = [40, 0, 1, 25]
+    src_pages, dst_pages, at_s, at_d = [], [], 3, 500
+    for n in ctx_len:
+        src_pages += list(range(at_s, at_s + n))
+        dst_pages += list(range(at_d, at_d + n))
+        at_s += n + 2                                   # a gap on the source side only
+        at_d += n
+    s, d = orc.flatten(ctx_len, src_pages, 1), orc.flatten(ctx_len, dst_pages, 1)
+    assert orc.runs(s, d).tolist() == [0, 40, 41, 66]
+    T = 50
+    odd = [2 * j for j in range(T)]                     # every other slot: never adjacent
+    assert orc.runs(odd, list(range(T))).tolist() == list(range(T + 1))
+    assert orc.runs(list(range(T)), odd).tolist() == list(range(T + 1))
+    p, n_tok = 4, 22                                    # 5 full pages and a page of 2
+    pages = [3 * i for i in range(6)]
+    s = orc.flatten([n_tok], pages, p)
+    assert orc.runs(s, s).tolist() == [0, 4, 8, 12, 16, 20, 22]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_runs_partition_is_valid_and_maximal(seed):
+    """Brute force on random slot lists with planted runs: inside a run both
+    sides advance by one; across every boundary at least one side does not;
+    the runs tile [0, T)."""
+    rng = SplitMix64(700 + seed)
+    s, d = [], []
+    while len(s) < 300:
+        n = int(rng.integers(1, 9, 1)[0])
+        a, b = int(rng.integers(0, 5000, 1)[0]), int(rng.integers(0, 5000, 1)[0])
+        s += list(range(a, a + n))
+        d += list(range(b, b + n)) if rng.integers(0, 4, 1)[0] else list(range(b + n, b, -1))
+    r = orc.runs(s, d).tolist()
+    T = len(s)
+    assert r[0] == 0 and r[-1] == T and all(x < y for x, y in zip(r, r[1:]))
+    for a, b in zip(r, r[1:]):
+        assert all(s[j] == s[j - 1] + 1 and d[j] == d[j - 1] + 1 for j in range(a + 1, b))
+        if b < T:
+            assert s[b] != s[b - 1] + 1 or d[b] != d[b - 1] + 1
+
+
 # ---------------------------------------------------------------- routing ---
 
 def test_route_reproduces_paper_worked_example():
