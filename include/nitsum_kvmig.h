@@ -63,6 +63,7 @@ typedef enum nts_status {
 enum {
     NTS_MAX_LAYERS = 96,          /* 2*L base pointers travel as kernel arguments */
     NTS_VALIDATE_UNIQUE_DST = 1u, /* plan flag: check destination slots are distinct */
+    NTS_DETECT_RUNS = 2u,         /* plan flag: also find the runs of neighbouring slots */
     NTS_DEFAULT_STAGING_BYTES = 64 << 20
 };
 
@@ -91,7 +92,7 @@ typedef struct nts_desc {
     int64_t dst_token_stride; /* bytes between destination slots; 0 = Hd*D*elem_bytes */
     int64_t staging_bytes;    /* B: size of ONE staging buffer; 0 = 64 MiB.  Rounded
                                  down to a whole number of fragments (at least one). */
-    uint32_t flags;           /* NTS_VALIDATE_UNIQUE_DST */
+    uint32_t flags;           /* NTS_VALIDATE_UNIQUE_DST | NTS_DETECT_RUNS */
     uint32_t reserved;
 } nts_desc;
 
@@ -104,7 +105,7 @@ typedef struct nts_info {
     int64_t chunk_bytes;  /* chunk_frags * frag_bytes <= staging_bytes */
     int64_t n_chunks;     /* ceil(F / chunk_frags); 0 for an empty plan */
     int32_t vec_bytes;    /* bytes each lane moves per access (16, 8 or 4) */
-    int32_t reserved;
+    int32_t n_runs;       /* runs found with NTS_DETECT_RUNS; 0 without the flag */
 } nts_info;
 
 /* Create a context on HIP device `device_id`.  *out is owned by the caller
@@ -148,6 +149,21 @@ int nts_route(int H, int Ns, int rs, int Nd, int rd,
 int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out);
 int nts_plan_free(nts_plan *plan);
 int nts_plan_info(const nts_plan *plan, nts_info *out);
+
+/*
+ * Runs (plan flag NTS_DETECT_RUNS).  With small pages a request's KV lies in
+ * many scattered regions, with a contiguous per-request layout in few (paper
+ * Sec. 3.2.2).  Token j continues the run of token j-1 when it sits in the next
+ * slot on the source side and in the next slot on the destination side; the
+ * plan then holds, on the device, the first token of every run in token order.
+ * When a fragment is a whole token row on both sides a run is one contiguous
+ * region per (layer, K|V); nts_run_memcpy_baseline's merge_runs uses the list.
+ * The kernels' results do not depend on the flag.
+ * nts_plan_runs copies the list to the host: run_start_host receives
+ * n_runs + 1 int32 (n_runs from nts_plan_info), the last one T.  Synchronises.
+ * Errors: NTS_EINVAL (null, or the plan was made without the flag).
+ */
+int nts_plan_runs(nts_plan *plan, int32_t *run_start_host);
 
 /* Copy the flattened slot lists back to the host (each int32 [T], either may
  * be NULL).  Synchronises; meant for tests and debugging. */

@@ -35,11 +35,12 @@ _lib = ctypes.CDLL(LIB_PATH)
 NTS_OK, NTS_EINVAL, NTS_ERANGE, NTS_EDUP, NTS_EALIAS, NTS_ENOMEM, NTS_EHIP = 0, -1, -2, -3, -4, -5, -6
 NTS_MAX_LAYERS = 96
 NTS_VALIDATE_UNIQUE_DST = 1
+NTS_DETECT_RUNS = 2
 NTS_DEFAULT_STAGING_BYTES = 64 << 20
 
 EXPORTS = (
     "nts_init", "nts_free", "nts_last_error", "nts_strerror", "nts_route",
-    "nts_plan_create", "nts_plan_free", "nts_plan_info", "nts_plan_slots",
+    "nts_plan_create", "nts_plan_free", "nts_plan_info", "nts_plan_slots", "nts_plan_runs",
     "nts_run_pack", "nts_run_pack_chunk", "nts_run_unpack", "nts_run_unpack_chunk",
     "nts_run_migrate", "nts_run_migrate_batch", "nts_run_migrate_direct", "nts_run_memcpy_baseline",
     "nts_shard_linear", "nts_shard_linear_workspace", "nts_shard_linear_launch",
@@ -91,7 +92,7 @@ class nts_info(ctypes.Structure):
     _fields_ = [
         ("T", ctypes.c_int64), ("F", ctypes.c_int64), ("frag_bytes", ctypes.c_int64),
         ("X", ctypes.c_int64), ("chunk_frags", ctypes.c_int64), ("chunk_bytes", ctypes.c_int64),
-        ("n_chunks", ctypes.c_int64), ("vec_bytes", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("n_chunks", ctypes.c_int64), ("vec_bytes", ctypes.c_int32), ("n_runs", ctypes.c_int32),
     ]
 
 
@@ -108,6 +109,7 @@ _lib.nts_plan_create.argtypes = [_vp, ctypes.POINTER(nts_desc), ctypes.POINTER(_
 _lib.nts_plan_free.argtypes = [_vp]
 _lib.nts_plan_info.argtypes = [_vp, ctypes.POINTER(nts_info)]
 _lib.nts_plan_slots.argtypes = [_vp, _vp, _vp]
+_lib.nts_plan_runs.argtypes = [_vp, _vp]
 _lib.nts_run_pack.argtypes = [_vp, _vp, _vp, _vp]
 _lib.nts_run_pack_chunk.argtypes = [_vp, _vp, _i64, _vp, _vp]
 _lib.nts_run_unpack.argtypes = [_vp, _vp, _vp, _vp]
@@ -206,6 +208,15 @@ def nts_plan_slots(plan: int) -> Tuple[np.ndarray, np.ndarray]:
     if st != NTS_OK:
         raise NtsError(st, "nts_plan_slots")
     return s, d
+
+
+def nts_plan_runs(plan: int) -> np.ndarray:
+    """First token of every run, then T (n_runs + 1 entries); the plan needs NTS_DETECT_RUNS."""
+    r = np.empty(nts_plan_info(plan).n_runs + 1, np.int32)
+    st = _lib.nts_plan_runs(plan, r.ctypes.data)
+    if st != NTS_OK:
+        raise NtsError(st, "nts_plan_runs")
+    return r
 
 
 def layer_ptrs(base_ptr: int, L: int, slab_bytes: int):

@@ -229,6 +229,7 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     pl->S_src = d->S_src; pl->S_dst = d->S_dst;
     pl->src_stride = src_stride; pl->dst_stride = dst_stride;
     pl->T = T;
+    pl->has_runs = (d->flags & NTS_DETECT_RUNS) != 0;
     pl->F = T * 2 * d->L;
     pl->frag_bytes = frag;
     if (pl->F > INT64_MAX / frag) {
@@ -253,7 +254,8 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     }
 
     DeviceGuard guard(ctx->device);
-    // device block: sslot | dslot | meta (tok_off | pg_off | src pages | dst pages) | bitmap | err
+    // device block: sslot | dslot | meta (tok_off | pg_off | src pages | dst pages) | bitmap | err |
+    // run starts | per-block run counts (the last two only with NTS_DETECT_RUNS)
     // pinned host block: err readback (256 B) | meta
     const bool uniq = (d->flags & NTS_VALIDATE_UNIQUE_DST) != 0;
     const int64_t n_off = int64_t(d->n_req) + 1;
@@ -263,7 +265,9 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     const int64_t b_meta = 2 * b_off + 2 * b_pages;
     const int64_t bitmap_words = uniq ? (d->S_dst + 31) / 32 : 0;
     const int64_t b_bitmap = align_up(bitmap_words * 4, 256);
-    const int64_t total = 2 * b_slots + b_meta + b_bitmap + 256;
+    const bool want_runs = (d->flags & NTS_DETECT_RUNS) != 0;
+    const int64_t b_runs = want_runs ? align_up((T + 1) * 4, 256) + align_up(((T + 255) / 256) * 4, 256) : 0;
+    const int64_t total = 2 * b_slots + b_meta + b_bitmap + 256 + b_runs;
 
     hipError_t e = hipSuccess;
     if (ctx->h_pinned_bytes < size_t(b_meta + 256)) {
@@ -332,7 +336,7 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     memcpy(h_meta + b_off, pg_off.data(), size_t(n_off) * 4);
     memcpy(h_meta + 2 * b_off, d->src_pages, size_t(NP) * 4);
     memcpy(h_meta + 2 * b_off + b_pages, d->dst_pages, size_t(NP) * 4);
-    h_err[0] = h_err[1] = 0;
+    h_err[0] = h_err[1] = h_err[2] = 0;
     char *d_bm = d_meta + b_meta;
     int32_t *d_err = reinterpret_cast<int32_t *>(d_bm + b_bitmap);
     NtsFlattenSide fs, fd;
@@ -352,7 +356,13 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
         if ((e = nts_launch_flatten(reinterpret_cast<const int32_t *>(d_meta),
                                     reinterpret_cast<const int32_t *>(d_meta + b_off), d->n_req,
                                     uint32_t(T), p, fs, fd, d_err, st)) != hipSuccess) break;
-        if ((e = hipMemcpyAsync(const_cast<int32_t *>(h_err), d_err, 8, hipMemcpyDeviceToHost, st)) != hipSuccess) break;
+        if (want_runs) {
+            pl->d_run_start = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(d_err) + 256);
+            int32_t *d_counts = pl->d_run_start + align_up((T + 1) * 4, 256) / 4;
+            if ((e = nts_launch_detect_runs(pl->d_sslot, pl->d_dslot, uint32_t(T), d_counts, pl->d_run_start,
+                                            d_err + 2, st)) != hipSuccess) break;
+        }
+        if ((e = hipMemcpyAsync(const_cast<int32_t *>(h_err), d_err, 12, hipMemcpyDeviceToHost, st)) != hipSuccess) break;
         e = hipStreamSynchronize(st);
     } while (0);
     const int err_range = h_err[0], err_dup = h_err[1];
@@ -363,6 +373,7 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
         if (err_range) return fail(ctx, NTS_ERANGE, "a page id lies outside its pool");
         return fail(ctx, NTS_EDUP, "two migrated tokens share a destination slot");
     }
+    pl->n_runs = want_runs ? h_err[2] : 0;
     ++ctx->n_plans;
     *out = pl;
     return NTS_OK;
@@ -431,7 +442,7 @@ int nts_plan_info(const nts_plan *pl, nts_info *out)
     out->chunk_bytes = pl->chunk_bytes;
     out->n_chunks = pl->n_chunks;
     out->vec_bytes = pl->vec;
-    out->reserved = 0;
+    out->n_runs = int32_t(pl->n_runs);
     return NTS_OK;
 }
 
@@ -442,6 +453,19 @@ int nts_plan_slots(const nts_plan *pl, int32_t *sslot_host, int32_t *dslot_host)
     DeviceGuard guard(pl->ctx->device);
     if (sslot_host) NTS_HIP(pl->ctx, hipMemcpy(sslot_host, pl->d_sslot, size_t(pl->T) * 4, hipMemcpyDeviceToHost));
     if (dslot_host) NTS_HIP(pl->ctx, hipMemcpy(dslot_host, pl->d_dslot, size_t(pl->T) * 4, hipMemcpyDeviceToHost));
+    return NTS_OK;
+}
+
+int nts_plan_runs(nts_plan *pl, int32_t *run_start_host)
+{
+    if (!pl || !run_start_host) return NTS_EINVAL;
+    if (!pl->has_runs) return fail(pl->ctx, NTS_EINVAL, "the plan was made without NTS_DETECT_RUNS");
+    if (pl->T == 0) {
+        run_start_host[0] = 0;
+        return NTS_OK;
+    }
+    DeviceGuard guard(pl->ctx->device);
+    NTS_HIP(pl->ctx, hipMemcpy(run_start_host, pl->d_run_start, size_t(pl->n_runs + 1) * 4, hipMemcpyDeviceToHost));
     return NTS_OK;
 }
 
@@ -694,15 +718,28 @@ int nts_run_memcpy_baseline(nts_plan *pl, const void *const *src_layer_ptrs, voi
     const int64_t so = int64_t(pl->src_head_off) * pl->D * pl->e, dof = int64_t(pl->dst_head_off) * pl->D * pl->e;
     // a run of tokens in neighbouring slots on both sides is one region when a fragment is a whole row
     const bool can_merge = merge_runs && pl->frag_bytes == pl->src_stride && pl->frag_bytes == pl->dst_stride;
+    // the plan's own run list when it has one, else the same rule applied to the host copies
+    if (can_merge && pl->has_runs && pl->h_run_start.empty()) {
+        try {
+            pl->h_run_start.resize(size_t(pl->n_runs) + 1);
+        } catch (...) {
+            return fail(ctx, NTS_ENOMEM, "host allocation failed");
+        }
+        NTS_HIP(ctx, hipMemcpy(pl->h_run_start.data(), pl->d_run_start, size_t(pl->n_runs + 1) * 4, hipMemcpyDeviceToHost));
+    }
     int64_t copies = 0;
     for (int lc = 0; lc < 2 * pl->L; ++lc) {
-        int64_t j = 0;
+        int64_t j = 0, r = 0;
         while (j < pl->T) {
             int64_t len = 1;
-            if (can_merge)
+            if (can_merge && pl->has_runs) {
+                len = int64_t(pl->h_run_start[size_t(r) + 1]) - j;
+                ++r;
+            } else if (can_merge) {
                 while (j + len < pl->T && pl->h_sslot[j + len] == pl->h_sslot[j] + len &&
                        pl->h_dslot[j + len] == pl->h_dslot[j] + len)
                     ++len;
+            }
             const char *s = stab.p[lc] + int64_t(pl->h_sslot[j]) * pl->src_stride + so;
             char *d = dtab.p[lc] + int64_t(pl->h_dslot[j]) * pl->dst_stride + dof;
             NTS_HIP(ctx, hipMemcpyAsync(d, s, size_t(len * pl->frag_bytes), hipMemcpyDeviceToDevice, st));

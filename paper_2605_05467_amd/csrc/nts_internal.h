@@ -45,8 +45,12 @@ struct nts_plan {
     size_t d_block_bytes = 0;
     int32_t *d_sslot = nullptr;
     int32_t *d_dslot = nullptr;
+    // run list (plan flag NTS_DETECT_RUNS): n_runs + 1 token indices, the last one T
+    bool has_runs = false;
+    int32_t *d_run_start = nullptr;
+    int64_t n_runs = 0;
     // host copies of the slot lists, fetched on first use by the per-fragment memcpy baseline
-    std::vector<int32_t> h_sslot, h_dslot;
+    std::vector<int32_t> h_sslot, h_dslot, h_run_start;
     // streams this plan's run calls have launched on; their pending work reads d_block
     std::vector<hipStream_t> used_streams;
 };
@@ -101,6 +105,11 @@ struct NtsFlattenSide {
 hipError_t nts_launch_flatten(const int32_t *d_tok_off, const int32_t *d_pg_off, int n_req, uint32_t T,
                               int p, const NtsFlattenSide &src, const NtsFlattenSide &dst,
                               int32_t *d_err, hipStream_t st);
+// run_start[0 .. n) = first token of every run in token order, run_start[n] = T, *d_n_runs = n;
+// d_block_count: scratch of ceil(T / 256) entries
+hipError_t nts_launch_detect_runs(const int32_t *d_sslot, const int32_t *d_dslot, uint32_t T,
+                                  int32_t *d_block_count, int32_t *d_run_start, int32_t *d_n_runs,
+                                  hipStream_t st);
 
 // nts_linear.hip: Y[M][Nn] = X[M][K] . A[Nn][K]^T, bf16 or f16 in, fp32 accumulate, same format out
 struct NtsStreamCfg {

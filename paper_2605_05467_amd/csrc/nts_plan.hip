@@ -40,7 +40,93 @@ __global__ __launch_bounds__(256) void nts_flatten_kernel(
     }
 }
 
+// Run detection (plan flag NTS_DETECT_RUNS): token j starts a run unless it sits in the slot
+// after token j-1's on the source side and on the destination side.  With small pages a
+// request's KV is scattered over many regions, with a contiguous per-request layout over few
+// (paper Sec. 3.2.2); a run is one contiguous region per (layer, K|V) when a fragment is a
+// whole token row.  Three launches, no atomics, so the list comes out in token order:
+// heads per 256-token block, exclusive scan of the block counts by one workgroup, then every
+// head writes its token index at (block offset + rank inside the block by ballot).
+__device__ __forceinline__ bool nts_run_head(const int32_t *__restrict__ ss, const int32_t *__restrict__ ds,
+                                             uint32_t j)
+{
+    return j == 0 || ss[j] != ss[j - 1] + 1 || ds[j] != ds[j - 1] + 1;
+}
+
+__global__ __launch_bounds__(256) void nts_run_count_kernel(const int32_t *__restrict__ ss,
+                                                            const int32_t *__restrict__ ds, uint32_t T,
+                                                            int32_t *__restrict__ block_count)
+{
+    const uint32_t j = blockIdx.x * 256u + threadIdx.x;
+    const int n = __syncthreads_count(j < T && nts_run_head(ss, ds, j));
+    if (threadIdx.x == 0) block_count[blockIdx.x] = n;
+}
+
+// one workgroup: block_count[0..nb) -> exclusive offsets in place; the total goes to *n_runs and
+// the closing entry run_start[total] = T is written here
+__global__ __launch_bounds__(256) void nts_run_scan_kernel(int32_t *__restrict__ block_count, uint32_t nb,
+                                                           uint32_t T, int32_t *__restrict__ run_start,
+                                                           int32_t *__restrict__ n_runs)
+{
+    __shared__ int32_t part[256];
+    __shared__ int32_t carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (uint32_t base = 0; base < nb; base += 256u) {
+        const uint32_t i = base + threadIdx.x;
+        const int32_t v = i < nb ? block_count[i] : 0;
+        part[threadIdx.x] = v;
+        __syncthreads();
+        for (int d = 1; d < 256; d <<= 1) {                 // inclusive scan of the 256 entries
+            const int32_t add = int(threadIdx.x) >= d ? part[threadIdx.x - d] : 0;
+            __syncthreads();
+            part[threadIdx.x] += add;
+            __syncthreads();
+        }
+        const int32_t before = carry;
+        if (i < nb) block_count[i] = before + part[threadIdx.x] - v;
+        __syncthreads();
+        if (threadIdx.x == 255) carry = before + part[255];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        run_start[carry] = int32_t(T);
+        *n_runs = carry;
+    }
+}
+
+__global__ __launch_bounds__(256) void nts_run_scatter_kernel(const int32_t *__restrict__ ss,
+                                                              const int32_t *__restrict__ ds, uint32_t T,
+                                                              const int32_t *__restrict__ block_off,
+                                                              int32_t *__restrict__ run_start)
+{
+    __shared__ int32_t wave_heads[4];
+    const uint32_t j = blockIdx.x * 256u + threadIdx.x;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const bool head = j < T && nts_run_head(ss, ds, j);
+    const unsigned long long m = __ballot(head);
+    if (lane == 0) wave_heads[wv] = __popcll(m);
+    __syncthreads();
+    if (!head) return;
+    int32_t at = block_off[blockIdx.x] + __popcll(m & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wv; ++w) at += wave_heads[w];
+    run_start[at] = int32_t(j);
+}
+
 }  // namespace
+
+hipError_t nts_launch_detect_runs(const int32_t *d_sslot, const int32_t *d_dslot, uint32_t T,
+                                  int32_t *d_block_count, int32_t *d_run_start, int32_t *d_n_runs,
+                                  hipStream_t st)
+{
+    if (T == 0) return hipSuccess;
+    const uint32_t nb = (T + 255u) / 256u;
+    hipLaunchKernelGGL(nts_run_count_kernel, dim3(nb), dim3(256), 0, st, d_sslot, d_dslot, T, d_block_count);
+    hipLaunchKernelGGL(nts_run_scan_kernel, dim3(1), dim3(256), 0, st, d_block_count, nb, T, d_run_start, d_n_runs);
+    hipLaunchKernelGGL(nts_run_scatter_kernel, dim3(nb), dim3(256), 0, st, d_sslot, d_dslot, T, d_block_count,
+                       d_run_start);
+    return hipGetLastError();
+}
 
 hipError_t nts_launch_flatten(const int32_t *d_tok_off, const int32_t *d_pg_off, int n_req, uint32_t T,
                               int p, const NtsFlattenSide &src, const NtsFlattenSide &dst,

@@ -1,11 +1,13 @@
 """Seeded random geometries: every case draws a model shape, page size, TP pair,
-request mix, pool sizes, row padding and staging size, runs pack, the pipelined
+request mix, pool sizes, row padding and staging size (every other case also asks
+for run detection), runs pack, the pipelined
 migration and the pool-to-pool kernel through the C ABI and compares whole
 outputs with the oracle, bit for bit."""
 import numpy as np
 import pytest
 
 from gpu_util import draw_case, random_case_host, random_case_plan_args
+from oracle import kvmig as orc
 
 pytestmark = pytest.mark.gpu
 N_CASES = 64
@@ -30,11 +32,15 @@ def test_random_geometry(env, seed):
                                                                       "stream", "want"))
     src_d = [torch.from_numpy(a).cuda() for a in src_arr]
     kw = random_case_plan_args(b, c, h)
+    if seed % 2:
+        kw["flags"] |= b.NTS_DETECT_RUNS
     plan = b.nts_plan_create(ctx, **kw)
     try:
         info = b.nts_plan_info(plan)
         s, d = b.nts_plan_slots(plan)
         assert np.array_equal(s, sslot) and np.array_equal(d, dslot)
+        if seed % 2:
+            assert np.array_equal(b.nts_plan_runs(plan), orc.runs(sslot, dslot))
         assert info.X == stream_h.nbytes
         st = torch.cuda.current_stream().cuda_stream
         sp = [t.data_ptr() for t in src_d]

@@ -351,6 +351,88 @@ def test_memcpy_baseline_merges_contiguous_runs(b, ctx, torch):
     assert n == runs * sh.L * 2 and runs <= 5
 
 
+@pytest.mark.parametrize("layout,p,n_req,mean_len", [("contiguous", 1, 40, 3000), ("fragmented", 1, 40, 3000),
+                                                     ("fragmented", 16, 300, 400), ("zipf_runs", 1, 64, 1500),
+                                                     ("contiguous", 4, 3, 50)])
+def test_run_detection_equals_oracle(b, ctx, torch, layout, p, n_req, mean_len):
+    """NTS_DETECT_RUNS: the device-built run list is the oracle's, entry for entry, on layouts
+    with few long runs, with one run per token, with one run per page and with a skewed mix;
+    sizes span several hundred 256-token blocks (more than one pass of the block scan) down
+    to a single partial block."""
+    rng = SplitMix64(1234 + p + n_req)
+    ctx_len = lengths_uniform(rng, n_req, max(1, mean_len // 2), mean_len * 3 // 2, n_req * mean_len)
+    n_pages = int(((ctx_len.astype(np.int64) + p - 1) // p).sum())
+    S = (n_pages + 64) * p * 2
+    src_pages = random_pages(rng, ctx_len, p, S // p, layout)
+    dst_pages = random_pages(rng, ctx_len, p, S // p, "fragmented" if layout == "fragmented" else "contiguous")
+    kw = dict(L=1, D=32, elem_bytes=2, page_size=p, Hs=2, Hd=2, src_head_off=0, dst_head_off=0, w=2, S_src=S,
+              S_dst=S, ctx_len=ctx_len, src_pages=src_pages, dst_pages=dst_pages)
+    plan = b.nts_plan_create(ctx, flags=b.NTS_VALIDATE_UNIQUE_DST | b.NTS_DETECT_RUNS, **kw)
+    plain = b.nts_plan_create(ctx, flags=b.NTS_VALIDATE_UNIQUE_DST, **kw)
+    try:
+        sslot, dslot = orc.flatten(ctx_len, src_pages, p), orc.flatten(ctx_len, dst_pages, p)
+        want = orc.runs(sslot, dslot)
+        info = b.nts_plan_info(plan)
+        assert info.T == len(sslot) and info.n_runs == len(want) - 1
+        assert np.array_equal(b.nts_plan_runs(plan), want)
+        assert b.nts_plan_info(plain).n_runs == 0
+        with pytest.raises(b.NtsError) as ei:
+            b.nts_plan_runs(plain)
+        assert ei.value.status == b.NTS_EINVAL
+    finally:
+        b.nts_plan_free(plan)
+        b.nts_plan_free(plain)
+
+
+def test_run_flag_changes_no_result_and_feeds_the_memcpy_baseline(b, ctx, torch):
+    """Same migration with and without NTS_DETECT_RUNS: identical bytes from the pipelined path,
+    the pool-to-pool kernel and the merged per-region baseline, and the baseline issues one copy
+    per run and (layer, K|V) either way.  A zero-token plan has zero runs."""
+    from gpu_util import device_pool, host_layers, make_plan, oracle_slots, slab_bytes, to_host
+    rng = SplitMix64(77)
+    ctx_len = np.array([300, 0, 17, 1, 260], np.int32)
+    S = 1024
+    case = PairCase(name="runs", shape=ModelShape(L=3, H=4, D=64, e=2), p=1, Ns=1, rs=0, Nd=1, rd=0,
+                    S_src=S, S_dst=S, ctx_len=ctx_len,
+                    src_pages=random_pages(rng, ctx_len, 1, S, "zipf_runs"),
+                    dst_pages=random_pages(rng, ctx_len, 1, S, "contiguous"), seed_src=17, seed_dst=18)
+    sh = case.shape
+    src_h = host_layers(case, "src", range(sh.L))
+    want = host_layers(case, "dst", range(sh.L)).copy()
+    sslot, dslot = oracle_slots(case)
+    orc.migrate_direct(src_h, want, sslot, dslot, 0, 0, 4)
+    n_runs = len(orc.runs(sslot, dslot)) - 1
+    src_d = device_pool(case, "src")
+    sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+    st = torch.cuda.current_stream().cuda_stream
+    for flags in (b.NTS_VALIDATE_UNIQUE_DST, b.NTS_VALIDATE_UNIQUE_DST | b.NTS_DETECT_RUNS):
+        plan = make_plan(b, ctx, case, staging_bytes=1 << 16, flags=flags)
+        try:
+            info = b.nts_plan_info(plan)
+            assert info.n_runs == (n_runs if flags & b.NTS_DETECT_RUNS else 0)
+            staging = torch.empty(2 * info.chunk_bytes, dtype=torch.uint8, device="cuda")
+            for which in ("migrate", "direct", "memcpy"):
+                dst_d = device_pool(case, "dst")
+                dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
+                if which == "migrate":
+                    b.nts_run_migrate(plan, sp, dp, staging.data_ptr(), st)
+                elif which == "direct":
+                    b.nts_run_migrate_direct(plan, sp, dp, st)
+                else:
+                    assert b.nts_run_memcpy_baseline(plan, sp, dp, True, st) == n_runs * sh.L * 2
+                torch.cuda.synchronize()
+                assert to_host(dst_d).tobytes() == want.tobytes(), (flags, which)
+        finally:
+            b.nts_plan_free(plan)
+    empty = b.nts_plan_create(ctx, L=1, D=32, elem_bytes=2, page_size=1, Hs=2, Hd=2, src_head_off=0, dst_head_off=0,
+                              w=2, S_src=8, S_dst=8, ctx_len=np.zeros(2, np.int32), src_pages=np.zeros(0, np.int32),
+                              dst_pages=np.zeros(0, np.int32), flags=b.NTS_DETECT_RUNS)
+    try:
+        assert b.nts_plan_info(empty).n_runs == 0 and b.nts_plan_runs(empty).tolist() == [0]
+    finally:
+        b.nts_plan_free(empty)
+
+
 def test_migrate_can_be_captured_in_a_hip_graph(b, ctx, torch):
     """run calls allocate nothing and never synchronise, so a caller may record
     them into a HIP graph: several replays, with eager work in between, all
