@@ -127,6 +127,17 @@ def test_tiled_kernel_ragged_edges(env, M, split):
     run_case(env, M, n_out, n_in, tp, 0, split, seed=M + 8, dtype="f16")
 
 
+@pytest.mark.parametrize("M,n_out,n_in", [(1, 8, 64), (300, 8, 64), (20000, 264, 128), (20000, 520, 128),
+                                          (3, 40, 16384), (257, 24, 64)])
+@pytest.mark.parametrize("split", ["out", "in"])
+def test_extreme_aspect_ratios(env, M, n_out, n_in, split):
+    """Outputs narrower than one weight tile, batches of tens of thousands of rows on
+    a few columns (streaming kernel with many batch tiles, and the tiled kernel
+    with a single ragged tile column), one slab of reduction and hundreds."""
+    run_case(env, M, n_out * 2 if split == "out" else n_out, n_in if split == "out" else n_in * 2, 2, 1, split,
+             seed=M + n_out)
+
+
 @pytest.mark.parametrize("layer", ["8b_qkv", "8b_down", "14b_o"])
 def test_decoder_layer_shapes_prefill_batch(env, layer):
     n_out, n_in, split = LAYERS[layer]
