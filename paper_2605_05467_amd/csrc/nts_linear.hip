@@ -342,16 +342,20 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 
     // staging map: 256 rows x 8 vectors of 16 B per operand and slab; thread t takes
     // vector (t & 7) of rows (t >> 3) + 32 * q, q = 0..7: eight lanes read one 128 B line.
-    // Row offsets are kept as 32-bit counts of 16-byte units from the operand's base.
+    // A load's address is a uniform 64-bit base (the tile's first row plus the slab) plus a
+    // 32-bit byte offset per lane that never changes (row inside the tile times the row
+    // stride), so the slab loop spends no vector instructions on addresses.
     const int sv = tid & 7, sr = tid >> 3;
     uint32_t xo[8], ao[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
         const int r = sr + 32 * q;
-        xo[q] = uint32_t((int64_t(min(m0 + r, M - 1)) * ldx) >> 3) + sv;
-        ao[q] = uint32_t((int64_t(min(n0 + r, Nn - 1)) * lda) >> 3) + sv;
+        xo[q] = uint32_t(min(m0 + r, M - 1) - m0) * uint32_t(ldx * 2) + uint32_t(sv * 16);
+        ao[q] = uint32_t(min(n0 + r, Nn - 1) - n0) * uint32_t(lda * 2) + uint32_t(sv * 16);
     }
-    const u32x4 *xb = reinterpret_cast<const u32x4 *>(X), *ab = reinterpret_cast<const u32x4 *>(A);
+    const char *xt = reinterpret_cast<const char *>(X) + int64_t(m0) * ldx * 2;
+    const char *at = reinterpret_cast<const char *>(A) + int64_t(n0) * lda * 2;
+#define NTS_GLOAD(base, o) (*reinterpret_cast<const u32x4 *>((base) + (o)))
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -372,14 +376,15 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
         u32x4 x0[8], a0[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            x0[q] = xb[xo[q]];
-            a0[q] = ab[ao[q]];
+            x0[q] = NTS_GLOAD(xt, xo[q]);
+            a0[q] = NTS_GLOAD(at, ao[q]);
         }
-        const uint32_t off = uint32_t(min(1, n_slabs - 1)) * (kTileK * 2 / 16);
+        const int64_t off = int64_t(min(1, n_slabs - 1)) * (kTileK * 2);
+        const char *xg = xt + off, *ag = at + off;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            xr[q] = xb[xo[q] + off];
-            ar[q] = ab[ao[q] + off];
+            xr[q] = NTS_GLOAD(xg, xo[q]);
+            ar[q] = NTS_GLOAD(ag, ao[q]);
         }
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
@@ -417,8 +422,8 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     }
 #define NTS_LOAD_ONE(i)                                                                                \
     {                                                                                                  \
-        if ((i) & 1) ar[(i) >> 1] = ab[ao[(i) >> 1] + off];                                            \
-        else xr[(i) >> 1] = xb[xo[(i) >> 1] + off];                                                    \
+        if ((i) & 1) ar[(i) >> 1] = NTS_GLOAD(ag, ao[(i) >> 1]);                                       \
+        else xr[(i) >> 1] = NTS_GLOAD(xg, xo[(i) >> 1]);                                               \
     }
     // the 16 MFMAs of one k step on (XF, AF); G0 = slot number of the first one within the slab;
     // fragment r of step NKK at NBASE goes into (NXF, NAF) after MFMA r * STRIDE
@@ -445,16 +450,28 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     vec8 xf0[4], af0[4], xf1[4], af1[4];
 #pragma unroll
     for (int r = 0; r < 8; ++r) NTS_READ_FRAG(lds, 0, r, xf0, af0)
-    for (int s = 0; s < n_slabs; ++s) {
-        const unsigned char *xs = lds + (s & 1) * kTileLds;
-        unsigned char *nx = lds + ((s + 1) & 1) * kTileLds;
-        const uint32_t off = uint32_t(min(s + 2, n_slabs - 1)) * (kTileK * 2 / 16);
-        NTS_KSTEP(xf0, af0, 0, xs, 1, xf1, af1, 2)
-        NTS_KSTEP(xf1, af1, 16, xs, 2, xf0, af0, 2)
-        NTS_KSTEP(xf0, af0, 32, xs, 3, xf1, af1, 1)
-        nts_lds_barrier();
-        NTS_KSTEP(xf1, af1, 48, nx, 0, xf0, af0, 2)
+    // Two slabs per trip, so each slab's LDS buffer is a constant: fragment reads and stores then
+    // carry their whole address in the instruction's offset field from a few per-lane bases.
+#define NTS_SLAB(XS, NX, S)                                                                            \
+    {                                                                                                  \
+        const unsigned char *xs = (XS);                                                                \
+        unsigned char *nx = (NX);                                                                      \
+        const int64_t off = int64_t(min((S) + 2, n_slabs - 1)) * (kTileK * 2);                         \
+        const char *xg = xt + off, *ag = at + off;                                                     \
+        NTS_KSTEP(xf0, af0, 0, xs, 1, xf1, af1, 2)                                                     \
+        NTS_KSTEP(xf1, af1, 16, xs, 2, xf0, af0, 2)                                                    \
+        NTS_KSTEP(xf0, af0, 32, xs, 3, xf1, af1, 1)                                                    \
+        nts_lds_barrier();                                                                             \
+        NTS_KSTEP(xf1, af1, 48, nx, 0, xf0, af0, 2)                                                    \
     }
+    int s = 0;
+    for (; s + 2 <= n_slabs; s += 2) {
+        NTS_SLAB(lds, lds + kTileLds, s)
+        NTS_SLAB(lds + kTileLds, lds, s + 1)
+    }
+    if (s < n_slabs) NTS_SLAB(lds, lds + kTileLds, s)
+#undef NTS_SLAB
+#undef NTS_GLOAD
 #undef NTS_READ_FRAG
 #undef NTS_STORE_ONE
 #undef NTS_LOAD_ONE
