@@ -15,6 +15,8 @@
 
 #include "nts_internal.h"
 
+#include <atomic>
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -524,18 +526,30 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 
 }  // namespace
 
+// A kernel that wants more dynamic LDS than the default limit has to be told so once per
+// device.  The devices done are kept as a bit set per kernel; two first calls at the same time
+// only repeat the (idempotent) attribute call.
+static hipError_t allow_dynamic_lds(std::atomic<uint64_t> &done, const void *kernel, int bytes)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (unsigned(dev) & 63u);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
+
 template <class E, int MT, int CW, int NSETS, int RT>
 static hipError_t launch_stream_one(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda, uint16_t *Y,
                                  int64_t ldy, float *part, int splits, int M, int Nn, int K, hipStream_t st)
 {
     const int lds_bytes = 3 * 32 * MT * kStrPitch;
-    static bool configured = false;
-    if (!configured) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_stream_kernel<E, MT, CW, NSETS, RT>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static std::atomic<uint64_t> configured{0};
+    const hipError_t ea = allow_dynamic_lds(
+        configured, reinterpret_cast<const void *>(nts_linear_stream_kernel<E, MT, CW, NSETS, RT>), lds_bytes);
+    if (ea != hipSuccess) return ea;
     const int tiles_m = (M + 32 * MT - 1) / (32 * MT), blocks_n = (Nn + 32 * CW * RT - 1) / (32 * CW * RT);
     const int n_slabs = K / kStrK;
     const int sps = (n_slabs + splits - 1) / splits;
@@ -652,16 +666,13 @@ bool nts_linear_use_tiled(int M, int Nn)
 hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
                                    uint16_t *Y, int64_t ldy, int M, int Nn, int K, bool f16, hipStream_t st)
 {
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_tiled_kernel<Bf16>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kTileLds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(nts_linear_tiled_kernel<F16>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kTileLds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static std::atomic<uint64_t> configured[2] = {{0}, {0}};
+    const hipError_t ea = allow_dynamic_lds(
+        configured[f16 ? 1 : 0],
+        f16 ? reinterpret_cast<const void *>(nts_linear_tiled_kernel<F16>)
+            : reinterpret_cast<const void *>(nts_linear_tiled_kernel<Bf16>),
+        2 * kTileLds);
+    if (ea != hipSuccess) return ea;
     const int tiles_m = (M + kTileM - 1) / kTileM, tiles_n = (Nn + kTileN - 1) / kTileN;
     const int sups = ((tiles_m + kSupM - 1) / kSupM) * ((tiles_n + kSupN - 1) / kSupN);
     const dim3 grid(unsigned((sups + 7) / 8) * 8u * kSupM * kSupN), block(256);
