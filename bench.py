@@ -67,6 +67,8 @@ def parse_args():
     ap.add_argument("--linear", action="store_true",
                     help="TP-shard-selecting linear layer (Sec. 3.2.1): decode and prefill batches of the "
                          "8B model's four layers at TP 1/2/4/8, one JSON line each")
+    ap.add_argument("--model", default="8b", choices=("8b", "14b"),
+                    help="with --linear: whose layer shapes (the paper serves an 8B and a 14B model)")
     ap.add_argument("--library", action="store_true",
                     help="with --linear: also time torch.matmul (hipBLASLt) on the same shards, graph-replayed alike")
     ap.add_argument("--planner", action="store_true",
@@ -255,7 +257,7 @@ def linear_bench(args, torch, b):
     weight copies, so no shard is served from a cache and launch gaps do not hide the kernels."""
     from workload.linear import LAYERS
     ctx = b.nts_init(0)
-    for layer in ("8b_qkv", "8b_o", "8b_gate_up", "8b_down"):
+    for layer in (f"{args.model}_qkv", f"{args.model}_o", f"{args.model}_gate_up", f"{args.model}_down"):
         n_out, n_in, split = LAYERS[layer]
         wbytes = n_out * n_in * 2
         copies = max(2, (3 << 30) // wbytes + 1)

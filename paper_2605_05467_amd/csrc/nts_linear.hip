@@ -565,13 +565,14 @@ static hipError_t launch_stream_one(const uint16_t *X, int64_t ldx, const uint16
 // width (4, 2 or 1 consumers) and K split with the smallest estimated time.  The estimate is
 // in microseconds, from measurements on MI355X of every instantiation at one workgroup per
 // compute unit:
-//   * per 64-wide slab a workgroup needs kSlabUs[width][height], set by what its compute unit
+//   * per 64-wide slab a workgroup needs its variant's slab_us, set by what its compute unit
 //     can take in and feed to the matrix cores; workgroups that share a compute unit share
-//     that rate (two take twice as long), so the slabs cost rounds * slabs * kSlabUs with
+//     that rate (two take twice as long), so the slabs cost rounds * slabs * slab_us with
 //     rounds = workgroups / 256 rounded up;
 //   * all of them together cannot read the shard faster than about 6.1 TB/s;
-//   * every round pays kRoundUs[width][height] for filling and draining its pipelines and for
-//     the output (rounds that fit a compute unit together pay it once), every launch 2.5;
+//   * every round pays the variant's round_us for filling and draining its pipelines and for
+//     the output (rounds that fit a compute unit together pay it once, plus 0.7 for each
+//     further one), every launch 2.5;
 //   * a split adds the second launch plus writing and reading splits * M * Nn fp32 partial
 //     sums at about 4 TB/s; it keeps at least four slabs and the workspace under 512 MiB.
 // Square-ish tiles take in the fewest bytes per product, small ones fill the chip when the
@@ -613,9 +614,10 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
             if ((n_slabs + sps - 1) / sps != splits) continue;              // would leave an empty split
             if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) break;
             const int64_t total = wgs * splits;
-            const double cu_us = double((total + 255) / 256) * sps * v.slab_us;
-            double t = 2.5 + (cu_us > hbm_us ? cu_us : hbm_us) +
-                       v.round_us * double((total + 256 * per_cu - 1) / (256 * per_cu));
+            const int64_t rounds = (total + 255) / 256, seq_rounds = (total + 256 * per_cu - 1) / (256 * per_cu);
+            const double cu_us = double(rounds) * sps * v.slab_us;
+            double t = 2.5 + (cu_us > hbm_us ? cu_us : hbm_us) + v.round_us * double(seq_rounds) +
+                       0.7 * double(rounds - seq_rounds);
             if (splits > 1) t += 2.5 + out_elems * splits * 8. / 4.0e6;
             if (best_splits == 0 || t < 0.95 * best_here) {
                 best_splits = splits;
