@@ -149,3 +149,37 @@ def test_decoder_layer_shapes_prefill_batch(env, layer):
 def test_float16_elements(env, M, split):
     run_case(env, M, 208, 1024 + 128, 2, 1, split, seed=M + 300, pad=8, dtype="f16")
     run_case(env, M, 1024, 2048, 4, 3, split, seed=M + 400, dtype="f16")
+
+
+@pytest.mark.parametrize("layer", ["8b_qkv", "8b_o", "8b_gate_up", "8b_down"])
+def test_bench_shapes_sampled_rows(env, layer):
+    """The shapes bench.py --linear times (full 8B layer, rank tp-1 at TP 1 and 8,
+    decode, short-prefill and prefill batches), each checked on eight whole output
+    rows that the oracle computes from the full weight matrix."""
+    torch, b, ctx = env
+    n_out, n_in, split = LAYERS[layer]
+    Xh, Wh = linear_inputs(77, 4096, n_out, n_in)
+    Wf = osl.bf16_to_f64(Wh)
+    Wd = torch.from_numpy(Wh.view(np.int16)).cuda()
+    sp = b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN
+    rng = np.random.default_rng(5)
+    for tp in (1, 8):
+        k = n_in if split == "out" else n_in // tp
+        nn = n_out // tp if split == "out" else n_out
+        for M in (16, 256, 4096):
+            Xm = np.ascontiguousarray(Xh[:M, :k])
+            Xd = torch.from_numpy(Xm.view(np.int16)).cuda()
+            Yd = torch.empty((M, nn), dtype=torch.int16, device="cuda")
+            kw = dict(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=tp - 1, split=sp)
+            ws_bytes = b.nts_shard_linear_workspace(**kw)
+            ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+            b.nts_shard_linear(ctx, Xd.data_ptr(), Wd.data_ptr(), Yd.data_ptr(), workspace=ws.data_ptr(),
+                               workspace_bytes=ws_bytes, hip_stream=torch.cuda.current_stream().cuda_stream, **kw)
+            torch.cuda.synchronize()
+            rows = np.unique(np.concatenate([[0, 1, M // 2, M - 1], rng.integers(0, M, 4)]))
+            want, bound = osl.shard_linear(osl.bf16_to_f64(Xm[rows]), Wf, tp, tp - 1, split)
+            got = osl.bf16_to_f64(Yd[torch.from_numpy(rows).cuda()].cpu().numpy().view(np.uint16))
+            tol = osl.tolerance(want, bound, k, out_bits=8)
+            err = np.abs(got - want)
+            assert got.shape == want.shape == (len(rows), nn)
+            assert np.all(err <= tol), (layer, tp, M, float((err / tol).max()))
