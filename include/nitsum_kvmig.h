@@ -297,12 +297,14 @@ int nts_shard_linear_workspace(const nts_linear_desc *d, size_t *bytes);
  * that must reach every kernel variant.  Errors: NTS_EINVAL as above.
  */
 typedef struct nts_linear_launch {
-    int32_t tiled;       /* 1: 256 x 256 matrix-core tiles; 0: weight-streaming kernel */
+    int32_t tiled;       /* 1: 256 x 256 matrix-core tiles; 0: weight-streaming kernel, or, with
+                            tile_rows == 16, the decode kernel */
     int32_t tile_rows;   /* batch rows per workgroup */
     int32_t tile_cols;   /* output columns (weight rows) per workgroup */
     int32_t k_splits;    /* parts the reduction is cut into; > 1 uses the workspace */
     int32_t slabs_ahead; /* 64-wide weight slabs a wavefront keeps in flight */
-    int32_t reserved[3];
+    int32_t k_waves;     /* wavefronts of a workgroup that share its reduction range (decode kernel), else 1 */
+    int32_t reserved[2];
 } nts_linear_launch;
 
 int nts_shard_linear_launch(const nts_linear_desc *d, nts_linear_launch *out);

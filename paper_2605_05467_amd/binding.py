@@ -74,7 +74,8 @@ class nts_linear_desc(ctypes.Structure):
 class nts_linear_launch(ctypes.Structure):
     _fields_ = [
         ("tiled", ctypes.c_int32), ("tile_rows", ctypes.c_int32), ("tile_cols", ctypes.c_int32),
-        ("k_splits", ctypes.c_int32), ("slabs_ahead", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3),
+        ("k_splits", ctypes.c_int32), ("slabs_ahead", ctypes.c_int32), ("k_waves", ctypes.c_int32),
+        ("reserved", ctypes.c_int32 * 2),
     ]
 
 

@@ -807,10 +807,12 @@ int nts_shard_linear_launch(const nts_linear_desc *d, nts_linear_launch *out)
     if (!out || linear_geom(d, &g) != NTS_OK) return NTS_EINVAL;
     *out = nts_linear_launch{};
     out->tiled = g.tiled ? 1 : 0;
-    out->tile_rows = g.tiled ? 256 : 32 * g.cfg.mt;
-    out->tile_cols = g.tiled ? 256 : 32 * g.cfg.cw * g.cfg.rt;
+    const bool decode = !g.tiled && g.cfg.ks > 0;
+    out->tile_rows = g.tiled ? 256 : decode ? 16 : 32 * g.cfg.mt;
+    out->tile_cols = g.tiled ? 256 : decode ? 16 * g.cfg.rt : 32 * g.cfg.cw * g.cfg.rt;
     out->k_splits = g.cfg.splits;
     out->slabs_ahead = g.tiled ? 2 : g.cfg.nsets - 1;
+    out->k_waves = decode ? g.cfg.ks : 1;
     return NTS_OK;
 }
 

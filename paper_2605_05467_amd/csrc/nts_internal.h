@@ -115,9 +115,10 @@ hipError_t nts_launch_detect_runs(const int32_t *d_sslot, const int32_t *d_dslot
 struct NtsStreamCfg {
     int mt = 1;       // batch rows per workgroup / 32
     int cw = 4;       // consumer wavefronts per workgroup
-    int rt = 1;       // 32-row weight tiles per consumer
+    int rt = 1;       // 32-row weight tiles per consumer (decode kernel: 16-row blocks per wavefront)
     int nsets = 4;    // weight register sets in rotation (nsets - 1 slabs in flight per wavefront)
     int splits = 1;   // K splits (> 1: fp32 partial sums in the workspace, reduced in split order)
+    int ks = 0;       // > 0: the decode kernel (16 weight rows per workgroup, ks wavefronts sharing K) instead
 };
 NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K);
 bool nts_linear_use_tiled(int M, int Nn);

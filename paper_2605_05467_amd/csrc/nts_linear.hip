@@ -308,6 +308,117 @@ __global__ __launch_bounds__(64 * (CW + 1)) void nts_linear_stream_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Decode kernel (batches of at most 16 rows on shards too small to fill the chip with 32-row
+// blocks): what a compute unit can stream depends on how many wavefronts ask, about 13 GB/s
+// for one and HBM speed for four, so a mid-size shard needs a thousand wavefronts with their
+// own weights.  A workgroup takes 16 weight rows (v_mfma_f32_16x16x32: weight rows first, so
+// a lane ends with four neighbouring output columns of one batch row) and its KS wavefronts
+// split the K range among themselves; a wavefront streams its weights and the matching
+// batch elements (a few KiB, always in the L2) straight into NSETS register sets, with no
+// LDS, no barrier and no producer in the loop, so the wavefronts' trip counts may differ.  At
+// the end the partial tiles meet in LDS and wavefront 0 adds them in wavefront order: one
+// launch, reproducible.  blockIdx.y can split K further (partial planes + reduce kernel, as
+// in the streaming kernel).
+template <class E, int KS, int RB, int NSETS>
+__global__ __launch_bounds__(64 * KS) void nts_linear_decode_kernel(
+    const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
+    uint16_t *__restrict__ Y, int64_t ldy, float *__restrict__ part, int M, int Nn, int K, int slabs_per_split)
+{
+    typedef typename E::vec8 vec8;
+    __shared__ f32x4 red[KS > 1 ? KS - 1 : 1][RB][64];
+    const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int n0 = blockIdx.x * 16 * RB, split = blockIdx.y;
+    const int n_slabs = K / kStrK;
+    const int wg_lo = split * slabs_per_split, wg_hi = min(n_slabs, wg_lo + slabs_per_split);
+    // this wavefront's share of the workgroup's slabs: contiguous, sizes differ by at most one
+    const int cnt = wg_hi - wg_lo, per = cnt / KS, rem = cnt % KS;
+    const int lo = wg_lo + g * per + min(g, rem), hi = lo + per + (g < rem ? 1 : 0);
+    const int last = max(min(hi, n_slabs) - 1, 0);      // requests past the end repeat a slab inside the matrix
+    const int fr = lane & 15, kg = lane >> 4;           // row and k group of this lane in both operands
+    const u32x4 *wrow[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r)
+        wrow[r] = reinterpret_cast<const u32x4 *>(A + int64_t(min(n0 + r * 16 + fr, Nn - 1)) * lda + kg * 8);
+    const u32x4 *xrow = reinterpret_cast<const u32x4 *>(X + int64_t(min(fr, M - 1)) * ldx + kg * 8);
+
+    f32x4 acc[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+    u32x4 w[NSETS][RB][2], x[NSETS][2];
+#define NTS_DEC_LOAD(SET, slab)                                                                \
+    {                                                                                          \
+        const int off_ = min((slab), last) * (kStrK * 2 / 16);                                 \
+        _Pragma("unroll") for (int r = 0; r < RB; ++r) {                                       \
+            w[SET][r][0] = wrow[r][off_];                                                      \
+            w[SET][r][1] = wrow[r][off_ + 4];                                                  \
+        }                                                                                      \
+        x[SET][0] = xrow[off_];                                                                \
+        x[SET][1] = xrow[off_ + 4];                                                            \
+    }
+#define NTS_DEC_SLAB(U, ss)                                                                    \
+    {                                                                                          \
+        NTS_DEC_LOAD(((U) + NSETS - 1) % NSETS, (ss) + NSETS - 1)                              \
+        _Pragma("unroll") for (int q = 0; q < 2; ++q)                                          \
+            _Pragma("unroll") for (int r = 0; r < RB; ++r)                                     \
+                acc[r] = E::mfma16(__builtin_bit_cast(vec8, w[(U) % NSETS][r][q]),             \
+                                   __builtin_bit_cast(vec8, x[(U) % NSETS][q]), acc[r]);       \
+    }
+#pragma unroll
+    for (int d = 0; d < NSETS - 1; ++d) NTS_DEC_LOAD(d, lo + d)
+    int s = lo;
+    for (; s + NSETS <= hi; s += NSETS) {
+#pragma unroll
+        for (int u = 0; u < NSETS; ++u) NTS_DEC_SLAB(u, s + u)
+    }
+#pragma unroll
+    for (int u = 0; u < NSETS - 1; ++u)
+        if (s + u < hi) NTS_DEC_SLAB(u, s + u)
+#undef NTS_DEC_SLAB
+#undef NTS_DEC_LOAD
+    if (KS > 1) {
+        if (g > 0) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r) red[g - 1][r][lane] = acc[r];
+        }
+        __syncthreads();
+        if (g > 0) return;
+#pragma unroll
+        for (int k = 1; k < KS; ++k)
+#pragma unroll
+            for (int r = 0; r < RB; ++r) acc[r] += red[k - 1][r][lane];
+    }
+    // D[i][j]: i = weight row = (lane / 16) * 4 + v, j = batch row = lane % 16
+    const int m = fr;
+    if (m >= M) return;
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+        const int n = n0 + r * 16 + kg * 4;
+        if (n >= Nn) continue;
+        if (part) {
+            float *dst = part + (int64_t(split) * M + m) * Nn + n;
+            if ((Nn & 3) == 0) {
+                *reinterpret_cast<f32x4 *>(dst) = acc[r];
+            } else {
+                dst[0] = acc[r][0];
+                if (n + 1 < Nn) dst[1] = acc[r][1];
+                if (n + 2 < Nn) dst[2] = acc[r][2];
+                if (n + 3 < Nn) dst[3] = acc[r][3];
+            }
+        } else {
+            uint16_t *dst = Y + int64_t(m) * ldy + n;
+            const u32x2 pk = {E::round2(acc[r][0], acc[r][1]), E::round2(acc[r][2], acc[r][3])};
+            if (n + 4 <= Nn) {
+                *reinterpret_cast<u32x2 *>(dst) = pk;
+            } else {
+                dst[0] = uint16_t(pk[0]);
+                if (n + 1 < Nn) dst[1] = uint16_t(pk[0] >> 16);
+                if (n + 2 < Nn) dst[2] = uint16_t(pk[1]);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Large batches (M > 64, prefill): bound by the matrix cores.  A 256-thread
 // workgroup computes a 256 x 256 tile of Y; each of its four wavefronts owns a
 // 128 x 128 quadrant as 4 x 4 tiles of v_mfma_f32_32x32x16_bf16 (256 fp32
@@ -633,7 +744,63 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
     }
     c.nsets = c.mt <= 4 ? 4 : 3;
     if (c.cw == 1 && c.mt == 1) c.nsets = 8;            // a lone consumer needs more weight bytes in flight
+    if (M > 16) return c;
+
+    // The decode kernel against the best of the above.  Its estimate: a wavefront alone streams
+    // about 10 GB/s of weights, a compute unit at most 26, less when the batch rows (fetched
+    // by every wavefront for its own K range) take a share of the 40 GB/s a compute unit
+    // can take in; the chip at most 6.1 TB/s; a launch 2.5, every round of workgroups 1, short
+    // K ranges pay for their pipeline fill, and wide batches 0.08 per row.
+    const double bytes = double(Nn) * K * 2.;
+    double best_dec = 0.;
+    int dec_ks = 0, dec_rb = 0, dec_splits = 0;
+    for (int rb = 1; rb <= 2; ++rb)
+        for (int ks = 2; ks <= 4; ks *= 2)      // eight never came out ahead in this estimate
+            for (int splits = 1; splits <= 4; splits *= 2) {
+                const int sps = (n_slabs + splits - 1) / splits;
+                if ((n_slabs + sps - 1) / sps != splits) continue;
+                const int spw = sps / ks;                                   // slabs per wavefront
+                if (spw < 4) continue;
+                if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) continue;
+                const int64_t wgs = int64_t((Nn + 16 * rb - 1) / (16 * rb)) * splits;
+                if (wgs > 384) continue;        // measured: with more than 1.5 workgroups per compute unit the
+                                                // streaming kernel's larger blocks do better than this estimate
+                const int per_cu = 12 / ks;                                 // workgroups a compute unit holds
+                const int64_t rounds = (wgs + 256 * per_cu - 1) / (256 * per_cu);
+                const int64_t wg_cu = (wgs + 255) / 256;                    // workgroups of the busiest compute unit
+                double rate = 10. * double(ks * (wg_cu < per_cu ? wg_cu : per_cu));
+                const double shared = 40. / (1. + double(M) / (16. * rb));
+                if (rate > shared) rate = shared;
+                if (rate > 26.) rate = 26.;
+                double stream_us = bytes / double(wgs) * double(wg_cu) / (rate * 1e3);
+                if (stream_us < hbm_us) stream_us = hbm_us;
+                double t = 2.5 + 1.0 * double(rounds) + stream_us + 0.08 * M + (spw < 16 ? 0.25 * (16 - spw) : 0.);
+                if (splits > 1) t += 2.5 + out_elems * splits * 8. / 4.0e6;
+                if (dec_ks == 0 || t < best_dec) {
+                    best_dec = t;
+                    dec_ks = ks;
+                    dec_rb = rb;
+                    dec_splits = splits;
+                }
+            }
+    if (dec_ks > 0 && best_dec < 0.95 * best_t) {
+        c.ks = dec_ks;
+        c.rt = dec_rb;                                  // row blocks of 16 per wavefront
+        c.splits = dec_splits;
+        c.nsets = dec_rb == 1 ? 8 : 6;
+    }
     return c;
+}
+
+template <class E, int KS, int RB>
+static hipError_t launch_decode_one(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda, uint16_t *Y,
+                                    int64_t ldy, float *part, int splits, int M, int Nn, int K, hipStream_t st)
+{
+    const int n_slabs = K / kStrK, sps = (n_slabs + splits - 1) / splits;
+    const dim3 grid(unsigned((Nn + 16 * RB - 1) / (16 * RB)), unsigned((n_slabs + sps - 1) / sps));
+    hipLaunchKernelGGL((nts_linear_decode_kernel<E, KS, RB, (RB == 1 ? 8 : 6)>), grid, dim3(64 * KS), 0, st, X, ldx, A,
+                       lda, Y, ldy, splits > 1 ? part : nullptr, M, Nn, K, sps);
+    return hipGetLastError();
 }
 
 hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda, uint16_t *Y,
@@ -641,6 +808,15 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
                                     bool f16, hipStream_t st)
 {
     hipError_t e = hipErrorInvalidValue;
+    if (c.ks > 0) {
+        if (M > 16) return hipErrorInvalidValue;
+#define NTS_DEC(KS, RB)                                                                                        \
+    if (c.ks == KS && c.rt == RB)                                                                              \
+        e = f16 ? launch_decode_one<F16, KS, RB>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st)         \
+                : launch_decode_one<Bf16, KS, RB>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st);
+        NTS_DEC(2, 1) NTS_DEC(4, 1) NTS_DEC(2, 2) NTS_DEC(4, 2)
+#undef NTS_DEC
+    } else {
 #define NTS_STR(MT, CW, NS, RT)                                                                                \
     if (c.mt == MT && c.cw == CW && c.nsets == NS && c.rt == RT)                                               \
         e = f16 ? launch_stream_one<F16, MT, CW, NS, RT>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st) \
@@ -649,6 +825,7 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
     NTS_STR(1, 1, 8, 1) NTS_STR(2, 1, 4, 1) NTS_STR(4, 1, 4, 1)
     NTS_STR(2, 2, 4, 1) NTS_STR(4, 2, 4, 1)
 #undef NTS_STR
+    }
     if (e != hipSuccess || c.splits <= 1) return e;
     const int64_t n = int64_t(M) * Nn;
     if (f16) hipLaunchKernelGGL(nts_linear_reduce_kernel<F16>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, c.splits, M, Nn, Y, ldy);

@@ -1,37 +1,48 @@
 """Shard shapes (M, Nn, K) that reach every variant of the linear layer's kernels:
 each instantiated (batch-tile rows, workgroup columns) of the weight-streaming
-kernel, with and without a K split, with one and with several batch tiles, and
-the tiled kernel; all with ragged edges.  The CPU suite checks, through the
+kernel, with and without a K split, with one and with several batch tiles, the
+decode kernel's (row blocks, wavefronts per K range) pairs and the tiled kernel;
+all with ragged edges.  The CPU suite checks, through the
 library's launch query, that every shape still lands on the variant named here
 and that no instantiated variant is left out; the GPU suite runs them against the
 oracle."""
 
-# (M, Nn, K, tile_rows, tile_cols, split?)      tiled kernel: rows = cols = 256
+# (M, Nn, K, tile_rows, tile_cols, split?, k_waves)
+# tiled kernel: rows = cols = 256; decode kernel: rows = 16, k_waves = wavefronts sharing K
 CASES = [
-    (1, 208, 256, 32, 32, False),
-    (7, 208, 2048, 32, 32, True),
-    (1, 28680, 1088, 32, 128, False),
-    (16, 9000, 3072, 32, 128, True),
-    (65, 208, 256, 64, 32, False),
-    (65, 208, 2048, 64, 32, True),
-    (65, 4104, 256, 64, 64, False),
-    (65, 528, 4096, 64, 64, True),
-    (65, 9000, 1088, 64, 128, False),
-    (130, 2056, 4096, 64, 128, True),
-    (200, 9000, 512, 96, 128, False),
-    (130, 3080, 3072, 96, 128, True),
-    (777, 208, 4096, 128, 32, True),
-    (200, 7000, 256, 128, 64, False),
-    (200, 2056, 2048, 128, 64, True),
-    (300, 9000, 512, 128, 128, False),
-    (200, 4104, 3072, 128, 128, True),
-    (1000, 4104, 256, 192, 128, False),
-    (130, 4104, 6144, 192, 128, True),
-    (777, 7000, 256, 256, 128, False),
-    (200, 4104, 8320, 256, 128, True),
-    (520, 19000, 256, 256, 256, False),
+    (1, 208, 256, 32, 32, False, 1),
+    (7, 208, 2048, 32, 32, True, 1),
+    (1, 28680, 1088, 32, 128, False, 1),
+    (16, 9000, 3072, 32, 128, True, 1),
+    (65, 208, 256, 64, 32, False, 1),
+    (65, 208, 2048, 64, 32, True, 1),
+    (65, 4104, 256, 64, 64, False, 1),
+    (65, 528, 4096, 64, 64, True, 1),
+    (65, 9000, 1088, 64, 128, False, 1),
+    (130, 2056, 4096, 64, 128, True, 1),
+    (200, 9000, 512, 96, 128, False, 1),
+    (130, 3080, 3072, 96, 128, True, 1),
+    (777, 208, 4096, 128, 32, True, 1),
+    (200, 7000, 256, 128, 64, False, 1),
+    (200, 2056, 2048, 128, 64, True, 1),
+    (300, 9000, 512, 128, 128, False, 1),
+    (200, 4104, 3072, 128, 128, True, 1),
+    (1000, 4104, 256, 192, 128, False, 1),
+    (130, 4104, 6144, 192, 128, True, 1),
+    (777, 7000, 256, 256, 128, False, 1),
+    (200, 4104, 8320, 256, 128, True, 1),
+    (520, 19000, 256, 256, 256, False, 1),
+    (1, 184, 1600, 16, 16, False, 2),
+    (3, 904, 11904, 16, 16, True, 2),
+    (7, 2104, 3392, 16, 16, False, 4),
+    (1, 904, 12352, 16, 16, True, 4),
+    (1, 9424, 2048, 16, 32, False, 2),
+    (1, 4624, 4288, 16, 32, False, 4),
+    (12, 3664, 15488, 16, 32, True, 4),
+    (9, 1744, 16384, 16, 32, True, 4),
 ]
 
-# every (rows, cols) the library instantiates; (256, 256) is the tiled kernel
-VARIANTS = {(32, 32), (32, 128), (64, 32), (64, 64), (64, 128), (96, 128), (128, 32), (128, 64), (128, 128),
-            (192, 128), (256, 128), (256, 256)}
+# every (rows, cols, k_waves) the library instantiates
+VARIANTS = {(16, 16, 2), (16, 16, 4), (16, 32, 2), (16, 32, 4)} | {(r, c, 1) for r, c in {
+    (32, 32), (32, 128), (64, 32), (64, 64), (64, 128), (96, 128), (128, 32), (128, 64), (128, 128), (192, 128),
+    (256, 128), (256, 256)}}

@@ -20,13 +20,13 @@ def env():
     b.nts_free(ctx)
 
 
-def run_case(env, M, n_out, n_in, tp, rank, split, seed=1, pad=0, dtype="bf16"):
+def run_case(env, M, n_out, n_in, tp, rank, split, seed=1, pad=0, dtype="bf16", pad_y=None):
     torch, b, ctx = env
     k = n_in if split == "out" else n_in // tp
     nn = n_out // tp if split == "out" else n_out
     Xh, Wh = linear_inputs(seed, M, n_out, n_in, x_cols=k, dtype=dtype)
     decode = osl.bf16_to_f64 if dtype == "bf16" else osl.f16_to_f64
-    ldx, ldw, ldy = k + pad, n_in + pad, nn + pad
+    ldx, ldw, ldy = k + pad, n_in + pad, nn + (pad if pad_y is None else pad_y)
     Xp = np.zeros((M, ldx), np.uint16); Xp[:, :k] = Xh
     Wp = np.zeros((n_out, ldw), np.uint16); Wp[:, :n_in] = Wh
     Xd = torch.from_numpy(Xp.view(np.int16)).cuda()
@@ -46,7 +46,7 @@ def run_case(env, M, n_out, n_in, tp, rank, split, seed=1, pad=0, dtype="bf16"):
     tol = osl.tolerance(want, bound, k, out_bits=8 if dtype == "bf16" else 11)
     err = np.abs(got - want)
     assert np.all(err <= tol), (float((err / tol).max()), np.unravel_index(np.argmax(err / tol), err.shape))
-    if pad:
+    if ldy > nn:
         assert np.all(Yg[:, nn:] == 12345)                     # nothing written past the output width
     return float((err / tol).max())
 
@@ -97,21 +97,22 @@ def test_large_batches_tile_edges(env, M, split):
     run_case(env, M, 1024, 2048, 4, 3, split, seed=M + 200)
 
 
-@pytest.mark.parametrize("case", CASES, ids=lambda c: "M%d_N%d_K%d_tile%dx%d%s" % (c[:5] + ("_split" if c[5] else "",)))
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "M%d_N%d_K%d_tile%dx%d%s_kw%d" % (c[:5] + ("_split" if c[5] else "", c[6])))
 @pytest.mark.parametrize("split", ["out", "in"])
 def test_every_kernel_variant(env, case, split):
     """One shard shape per instantiated kernel variant (tile height x workgroup
-    width, with and without a K split, one and several batch tiles), selected at
+    width, with and without a K split, one and several batch tiles; the decode
+    kernel's row blocks x wavefronts per K range), selected at
     TP level 2 from a full matrix twice the shard, as rank 1; the variant each
     shape reaches is pinned by the CPU suite."""
     torch, b, ctx = env
-    M, Nn, K, rows, cols, is_split = case
+    M, Nn, K, rows, cols, is_split, k_waves = case
     n_out, n_in = (2 * Nn, K) if split == "out" else (Nn, 2 * K)
     sp = b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN
     pad = 8 if M % 2 else 0
     l = b.nts_shard_linear_launch(M=M, n_out=n_out, n_in=n_in, tp=2, rank=1, split=sp, ldx=K + pad,
                                   ldw=n_in + pad, ldy=Nn + pad)
-    assert (l.tile_rows, l.tile_cols, l.k_splits > 1) == (rows, cols, is_split)
+    assert (l.tile_rows, l.tile_cols, l.k_splits > 1, l.k_waves) == (rows, cols, is_split, k_waves)
     run_case(env, M, n_out, n_in, 2, 1, split, seed=M + Nn, pad=pad,
              dtype="f16" if (M + Nn // 8) % 3 == 0 else "bf16")
 
@@ -136,6 +137,15 @@ def test_extreme_aspect_ratios(env, M, n_out, n_in, split):
     with a single ragged tile column), one slab of reduction and hundreds."""
     run_case(env, M, n_out * 2 if split == "out" else n_out, n_in if split == "out" else n_in * 2, 2, 1, split,
              seed=M + n_out)
+
+
+@pytest.mark.parametrize("M", [1, 9, 16, 40, 300])
+def test_output_width_not_a_multiple_of_four(env, M):
+    """Output widths of 4k+1, +2, +3 columns in a padded Y (the row stride must be a multiple
+    of eight, the width need not): the scalar edge of the 8-byte and 16-byte stores of the
+    decode, streaming and split-K paths."""
+    for nn, k in ((1001, 1600), (1002, 256), (1743, 12352), (37, 64)):
+        run_case(env, M, nn, k, 1, 0, "out", seed=M + nn, pad_y=8 - nn % 8)
 
 
 @pytest.mark.parametrize("layer", ["8b_qkv", "8b_down", "14b_o"])
