@@ -7,10 +7,11 @@
 // with 16-bit inputs (bfloat16 or float16), fp32 accumulation on the matrix cores and
 // one rounding to the input format.
 //
-// Two kernels: a weight-streaming kernel for batches up to a few hundred rows
-// (decode and short prefill chunks; bound by reading the shard once from HBM)
-// and a 256 x 256 tiled kernel for long prefill batches (bound by the matrix
-// cores).  Both are described where they are defined.
+// Three kernels: a decode kernel for batches of at most 16 rows on mid-size shards (16-row
+// blocks, a workgroup's wavefronts share the K range), a weight-streaming kernel for batches
+// up to a few hundred rows (decode and short prefill chunks; both bound by reading the shard
+// once from HBM) and a 256 x 256 tiled kernel for long prefill batches (bound by the matrix
+// cores).  Each is described where it is defined.
 #include <algorithm>
 
 #include "nts_internal.h"
