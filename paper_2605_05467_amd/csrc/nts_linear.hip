@@ -756,7 +756,7 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
     double best_dec = 0.;
     int dec_ks = 0, dec_rb = 0, dec_splits = 0;
     for (int rb = 1; rb <= 2; ++rb)
-        for (int ks = 2; ks <= 4; ks *= 2)      // eight never came out ahead in this estimate
+        for (int ks = 2 * rb; ks <= 4; ks *= 2)     // eight wavefronts, or two with two blocks, never came out ahead
             for (int splits = 1; splits <= 4; splits *= 2) {
                 const int sps = (n_slabs + splits - 1) / splits;
                 if ((n_slabs + sps - 1) / sps != splits) continue;
@@ -773,6 +773,7 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
                 const double shared = 40. / (1. + double(M) / (16. * rb));
                 if (rate > shared) rate = shared;
                 if (rate > 26.) rate = 26.;
+                if (wg_cu > 1 && rate > 18.) rate = 18.;    // measured: two small workgroups stream less than one of twice the rows
                 double stream_us = bytes / double(wgs) * double(wg_cu) / (rate * 1e3);
                 if (stream_us < hbm_us) stream_us = hbm_us;
                 double t = 2.5 + 1.0 * double(rounds) + stream_us + 0.08 * M + (spw < 16 ? 0.25 * (16 - spw) : 0.);
@@ -815,7 +816,7 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
     if (c.ks == KS && c.rt == RB)                                                                              \
         e = f16 ? launch_decode_one<F16, KS, RB>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st)         \
                 : launch_decode_one<Bf16, KS, RB>(X, ldx, A, lda, Y, ldy, part, c.splits, M, Nn, K, st);
-        NTS_DEC(2, 1) NTS_DEC(4, 1) NTS_DEC(2, 2) NTS_DEC(4, 2)
+        NTS_DEC(2, 1) NTS_DEC(4, 1) NTS_DEC(4, 2)
 #undef NTS_DEC
     } else {
 #define NTS_STR(MT, CW, NS, RT)                                                                                \
