@@ -265,7 +265,7 @@ int nts_run_memcpy_baseline(nts_plan *plan, const void *const *src_layer_ptrs,
  * X, W, Y: device, all bfloat16 (NTS_BF16) or all IEEE float16 (NTS_F16);
  * products are accumulated in fp32 and Y is rounded to nearest even once.  ldx / ldw / ldy: row strides in elements, 0 = dense
  * (n_in or n_in/tp for X, n_in for W, the output width for Y); all strides
- * multiples of 8, all pointers 16-byte aligned.  The shard's reduction length
+ * multiples of 8 and below 2^23 elements, all pointers 16-byte aligned.  The shard's reduction length
  * (n_in or n_in/tp) must be a multiple of 64.  workspace: device scratch of at
  * least nts_shard_linear_workspace() bytes (may be NULL when that is 0); it
  * holds fp32 partial sums when the reduction is split over workgroups, which

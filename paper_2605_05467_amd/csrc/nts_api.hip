@@ -783,9 +783,9 @@ int linear_geom(const nts_linear_desc *d, LinearGeom *g)
     g->ldy = d->ldy ? d->ldy : g->Nn;
     if (g->K % 64 || g->ldx < g->K || g->ldy < g->Nn) return NTS_EINVAL;
     if (g->ldx % 8 || g->lda % 8 || g->ldy % 8 || g->a_off % 8) return NTS_EINVAL;
-    // the tiled kernel addresses operand rows with 32-bit counts of 16-byte units
-    const int64_t lim = int64_t(1) << 35;
-    if (int64_t(g->M) * g->ldx >= lim || int64_t(g->Nn) * g->lda >= lim) return NTS_EINVAL;
+    // the tiled kernel addresses the 256 rows of a tile with 32-bit byte offsets from the tile's first row
+    const int64_t lim = int64_t(1) << 23;
+    if (g->ldx >= lim || g->lda >= lim || g->ldy >= lim) return NTS_EINVAL;
     g->tiled = nts_linear_use_tiled(g->M, g->Nn);
     g->cfg = nts_linear_stream_config(g->M, g->Nn, g->K);
     if (g->tiled) g->cfg.splits = 1;

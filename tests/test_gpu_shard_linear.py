@@ -83,6 +83,7 @@ def test_argument_errors(env):
     assert status(n_in=72) == b.NTS_EINVAL            # reduction length not a multiple of 64
     assert status(split=7) == b.NTS_EINVAL
     assert status(ldw=60) == b.NTS_EINVAL
+    assert status(ldw=1 << 23) == b.NTS_EINVAL          # row strides stay below 2^23 elements
     assert status(M=0) == b.NTS_EINVAL
     torch.cuda.synchronize()
 
