@@ -69,6 +69,8 @@ def parse_args():
                          "8B model's four layers at TP 1/2/4/8, one JSON line each")
     ap.add_argument("--model", default="8b", choices=("8b", "14b"),
                     help="with --linear: whose layer shapes (the paper serves an 8B and a 14B model)")
+    ap.add_argument("--batches", default="1,16,64,256,1024,4096",
+                    help="with --linear: the batch sizes M to time")
     ap.add_argument("--library", action="store_true",
                     help="with --linear: also time torch.matmul (hipBLASLt) on the same shards, graph-replayed alike")
     ap.add_argument("--planner", action="store_true",
@@ -263,7 +265,7 @@ def linear_bench(args, torch, b):
         copies = max(2, (3 << 30) // wbytes + 1)
         W = (torch.rand(copies, n_out, n_in, device="cuda") * 0.08 - 0.04).to(torch.bfloat16)
         for tp in (1, 2, 4, 8):
-            for M in (1, 16, 64, 256, 1024, 4096):
+            for M in [int(x) for x in args.batches.split(",")]:
                 k = n_in if split == "out" else n_in // tp
                 nn = n_out // tp if split == "out" else n_out
                 X = (torch.rand(M, k, device="cuda") * 4 - 2).to(torch.bfloat16)
