@@ -69,6 +69,8 @@ def parse_args():
                          "8B model's four layers at TP 1/2/4/8, one JSON line each")
     ap.add_argument("--model", default="8b", choices=("8b", "14b"),
                     help="with --linear: whose layer shapes (the paper serves an 8B and a 14B model)")
+    ap.add_argument("--layers", default="qkv,o,gate_up,down", help="with --linear: which of the block's layers")
+    ap.add_argument("--tp", default="1,2,4,8", help="with --linear: which TP levels")
     ap.add_argument("--batches", default="1,16,64,256,1024,4096",
                     help="with --linear: the batch sizes M to time")
     ap.add_argument("--library", action="store_true",
@@ -259,12 +261,12 @@ def linear_bench(args, torch, b):
     weight copies, so no shard is served from a cache and launch gaps do not hide the kernels."""
     from workload.linear import LAYERS
     ctx = b.nts_init(0)
-    for layer in (f"{args.model}_qkv", f"{args.model}_o", f"{args.model}_gate_up", f"{args.model}_down"):
+    for layer in [f"{args.model}_{name}" for name in args.layers.split(",")]:
         n_out, n_in, split = LAYERS[layer]
         wbytes = n_out * n_in * 2
         copies = max(2, (3 << 30) // wbytes + 1)
         W = (torch.rand(copies, n_out, n_in, device="cuda") * 0.08 - 0.04).to(torch.bfloat16)
-        for tp in (1, 2, 4, 8):
+        for tp in [int(x) for x in args.tp.split(",")]:
             for M in [int(x) for x in args.batches.split(",")]:
                 k = n_in if split == "out" else n_in // tp
                 nn = n_out // tp if split == "out" else n_out
@@ -330,7 +332,7 @@ def linear_bench(args, torch, b):
                     roof = {"bound": "mfma", "achieved": ach, "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0}
                 print(json.dumps({"linear": layer, "split": split, "tp": tp, "rank": tp - 1, "M": M, "Nn": nn, "K": k,
                                   "shard_MiB": shard_bytes / 2**20, "us_per_call": us, "dtype": "bf16",
-                                  "kernel": "tiled" if how.tiled else "stream",
+                                  "kernel": "tiled" if how.tiled else "decode" if how.tile_rows == 16 else "stream",
                                   "tile": "%dx%d" % (how.tile_rows, how.tile_cols), "k_splits": how.k_splits,
                                   "roofline": roof,
                                   **({"library_us_per_call": lib_us, "vs_library": us / lib_us} if lib_us else {})}),
