@@ -140,8 +140,11 @@ __global__ __launch_bounds__(64 * (CW + 1)) void nts_linear_stream_kernel(
     const int s_lo = split * slabs_per_split, s_hi = min(n_slabs, s_lo + slabs_per_split);
     // Workgroups walk their k range from different starting slabs (and wrap around): rows are
     // a power-of-two number of bytes apart, so workgroups that all read the same k at the same
-    // time would keep hitting the same few memory channels.
-    const int s_cnt = s_hi - s_lo, s_rot = (bx * 5 + by) % s_cnt;
+    // time would keep hitting the same few memory channels (measured: 10 % on a 224 MiB shard at
+    // 64 batch rows).  Tall batch tiles do the opposite: their workgroups should read the same
+    // batch slab at the same time so that it is fetched into the L2 once, and the weight bytes
+    // per workgroup are too few to camp (2 to 5 % the other way at 256 rows).
+    const int s_cnt = s_hi - s_lo, s_rot = MT >= 6 ? 0 : (bx * 5 + by) % s_cnt;
 #define NTS_STR_PHYS(ss) (s_lo + ((min((ss), s_hi - 1) - s_lo + s_rot) % s_cnt))
 
     // Slab s lives in LDS buffer s % 3.  During slab period s the producer writes slab s+1
