@@ -776,7 +776,7 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
                 const double shared = 40. / (1. + double(M) / (16. * rb));
                 if (rate > shared) rate = shared;
                 if (rate > 26.) rate = 26.;
-                if (wg_cu > 1 && rate > 18.) rate = 18.;    // measured: two small workgroups stream less than one of twice the rows
+                if (wg_cu > 1 && rate > 22.) rate = 22.;    // measured: two small workgroups stream less than one of twice the rows
                 double stream_us = bytes / double(wgs) * double(wg_cu) / (rate * 1e3);
                 if (stream_us < hbm_us) stream_us = hbm_us;
                 double t = 2.5 + 1.0 * double(rounds) + stream_us + 0.08 * M + (spw < 16 ? 0.25 * (16 - spw) : 0.);
