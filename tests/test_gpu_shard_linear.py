@@ -194,3 +194,24 @@ def test_bench_shapes_sampled_rows(env, layer):
             err = np.abs(got - want)
             assert got.shape == want.shape == (len(rows), nn)
             assert np.all(err <= tol), (layer, tp, M, float((err / tol).max()))
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_shapes(env, block):
+    """Seeded random batch sizes, output widths (multiples of 8), reduction lengths,
+    TP levels, ranks, split axes and element formats: whichever kernel and
+    configuration each shape gets must stay within the tolerance."""
+    from workload import SplitMix64
+    rng = SplitMix64(9100 + block)
+    u = lambda lo, hi: int(rng.integers(lo, hi, 1)[0])
+    for i in range(12):
+        big = block >= 4                                  # the last blocks aim at the tiled kernel
+        M = ((257, 300, 512, 777, 1024, 1500) if big else
+             (1, 2, 3, 5, 8, 13, 16, 17, 31, 32, 33, 64, 100, 129, 200, 256))[u(0, 5 if big else 15)]
+        tp = (1, 2, 4)[u(0, 2)]
+        split = ("out", "in")[u(0, 1)]
+        nn = 8 * (u(800, 3000) if big else u(1, 700))
+        k = 64 * (u(1, 6) if big else u(1, 40 if M > 64 else 120))
+        n_out, n_in = (nn * tp, k) if split == "out" else (nn, k * tp)
+        run_case(env, M, n_out, n_in, tp, u(0, tp - 1), split, seed=block * 100 + i,
+                 dtype=("bf16", "f16")[u(0, 1)])
