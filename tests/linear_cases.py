@@ -11,7 +11,7 @@ oracle."""
 # tiled kernel: rows = cols = 256; decode kernel: rows = 16, k_waves = wavefronts sharing K
 CASES = [
     (1, 208, 256, 32, 32, False, 1),
-    (7, 208, 2048, 32, 32, True, 1),
+    (7, 208, 2048, 16, 16, False, 2),
     (1, 28680, 1088, 32, 128, False, 1),
     (16, 9000, 3072, 32, 128, True, 1),
     (65, 208, 256, 64, 32, False, 1),
@@ -34,11 +34,13 @@ CASES = [
     (520, 19000, 256, 256, 256, False, 1),
     (1, 184, 1600, 16, 16, False, 2),
     (3, 904, 11904, 16, 16, True, 2),
-    (7, 2104, 3392, 16, 16, False, 4),
+    (7, 2104, 3392, 16, 16, False, 2),
     (1, 904, 12352, 16, 16, True, 4),
-    (1, 4624, 4288, 16, 32, False, 4),
-    (12, 3664, 15488, 16, 32, True, 4),
-    (9, 1744, 16384, 16, 32, True, 4),
+    (17, 208, 2048, 32, 32, True, 1),
+    (1, 4984, 3392, 16, 32, False, 4),
+    (1, 1744, 16384, 16, 32, True, 4),
+    (5, 1264, 3392, 32, 32, True, 1),
+    (3, 1384, 7424, 32, 32, True, 1),
 ]
 
 # every (rows, cols, k_waves) the library instantiates
