@@ -269,7 +269,9 @@ int nts_run_memcpy_baseline(nts_plan *plan, const void *const *src_layer_ptrs,
  * (n_in or n_in/tp) must be a multiple of 64.  workspace: device scratch of at
  * least nts_shard_linear_workspace() bytes (may be NULL when that is 0); it
  * holds fp32 partial sums when the reduction is split over workgroups, which
- * are then added in a fixed order, so results are reproducible.
+ * are then added in a fixed order, so results are reproducible.  Y must not
+ * overlap X, W or the workspace (not checked).  The call only enqueues work on
+ * hip_stream and allocates nothing.
  * Errors: NTS_EINVAL (null pointer, bad split / rank / sizes / alignment,
  * workspace too small), NTS_EHIP.
  */
