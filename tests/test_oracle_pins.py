@@ -277,6 +277,56 @@ def test_migrate_equals_direct_and_closed_form_of_fill(tr):
     assert int(a[0, 0, free, 0, 3]) == (int(fill_words(12, lin // 4, 1)[0]) >> (16 * (lin % 4))) & 0xFFFF
 
 
+@pytest.mark.parametrize("tr", [(2, 1, 4, 2), (4, 1, 2, 0), (2, 1, 4, 3), (1, 0, 1, 0)])
+def test_migrated_element_source_against_dictionary_model(tr):
+    """``migrated_element_source`` names, for one destination (slot, local head),
+    the source (slot, local head) it must hold afterwards.  Expected side: a
+    literal dictionary from global coordinates (token, global head) to where
+    the source GPU keeps them and where the destination GPU must keep them,
+    built from the even head split alone.  Every destination (slot, head) is
+    checked, moved and untouched, with non-zero offsets on both sides."""
+    Ns, rs, Nd, rd = tr
+    H, T, S_src, S_dst = 8, 9, 23, 17
+    Hs, Hd = H // Ns, H // Nd
+    rng = SplitMix64(4100 + 10 * Ns + Nd + rd)
+    sslot = rng.permutation(S_src)[:T].astype(np.int32)
+    dslot = rng.permutation(S_dst)[:T].astype(np.int32)
+    # where the source rank keeps (token j, global head gh), where the destination rank wants it
+    at_src, at_dst = {}, {}
+    for j in range(T):
+        for gh in range(H):
+            if rs * Hs <= gh < (rs + 1) * Hs:
+                at_src[(j, gh)] = (int(sslot[j]), gh - rs * Hs)
+            if rd * Hd <= gh < (rd + 1) * Hd:
+                at_dst[(j, gh)] = (int(dslot[j]), gh - rd * Hd)
+    want = {at_dst[k]: at_src[k] for k in at_dst if k in at_src}
+    so, do, w = orc.route(H, Ns, rs, Nd, rd)
+    assert w > 0 and len(want) == T * w
+    if tr == (2, 1, 4, 2):
+        assert (so, do) == (0, 0)
+    if tr == (2, 1, 4, 3):
+        assert so == 2 and do == 0                      # slice starts inside the source's row
+    if tr == (4, 1, 2, 0):
+        assert so == 0 and do == 2                      # slice lands inside the destination's row
+    j_of = {int(s): j for j, s in enumerate(dslot)}
+    for slot in range(S_dst):
+        for head in range(Hd):
+            got = orc.migrated_element_source(j_of, sslot, slot, head, so, do, w)
+            assert got == want.get((slot, head)), (tr, slot, head)
+    # the same table must describe what migrate() does to a pool of coordinates
+    L, D = 1, 1
+    src = np.zeros((L, 2, S_src, Hs, D), np.uint16)
+    for s in range(S_src):
+        for h in range(Hs):
+            src[0, :, s, h, 0] = 1 + s * Hs + h
+    dst = np.zeros((L, 2, S_dst, Hd, D), np.uint16)
+    orc.migrate(src, dst, sslot, dslot, so, do, w)
+    for slot in range(S_dst):
+        for head in range(Hd):
+            srcpos = want.get((slot, head))
+            assert int(dst[0, 1, slot, head, 0]) == (0 if srcpos is None else 1 + srcpos[0] * Hs + srcpos[1])
+
+
 @pytest.mark.parametrize("p", [1, 2, 4])
 def test_whole_chain_against_dictionary_model(p):
     """Tiny exhaustive check: the chain route -> flatten -> pack -> unpack must
