@@ -324,7 +324,9 @@ int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, cons
  * and nts_plan_cluster assigns the pool greedily by GE * rps / served_rps.
  * Where the paper is silent: a block is the (P, D) in 1..max_inst with the
  * smallest |P*THP - D*THD| / max (ties: fewer instances, then smaller P) and
- * serves min(P*THP, D*THD); Eq. 1 uses the tier's unmet rate; a tier served
+ * serves min(P*THP, D*THD); Eq. 1 is evaluated as printed (prefill rate only;
+ * thd does not enter nts_goodput_efficiency) with the tier's unmet rate, so with
+ * an inexact integer balance a block's score can exceed what it serves; a tier served
  * nothing yet outranks the others; ties: larger GE, then lower tier, prefill
  * TP, decode TP; one block per step until no demand is unmet or nothing fits.
  * out: host array of max_out entries in assignment order; *n_out is the number

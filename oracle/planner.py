@@ -17,8 +17,11 @@ in the library, listed in the design notes):
      with P, D <= max_inst whose stage rates are closest (smallest
      |P*THP - D*THD| / max of the two; ties: fewer instances P+D, then smaller P).
      A block serves min(P*THP, D*THD): both SLOs must hold for goodput.
- R2  Eq. 1 is evaluated on the block with the tier's still unmet rate:
-     GE = min(block rate, unmet_k) / (P*TPi + D*TPj).
+ R2  Eq. 1 is evaluated as printed, on the block's P and D and with the tier's
+     still unmet rate: GE = min(P*THP, unmet_k) / (P*TPi + D*TPj).  Only the
+     prefill rate enters the numerator (the paper drops the decode rate once
+     the stages are balanced); with integer P, D the balance is not exact, so
+     the score of a block can exceed what it serves (R1) by the residual gap.
  R3  WGE weights by rps_k / served_k; a tier that has been given nothing yet
      (served_k = 0) outranks every tier that has, and among such tiers, and
      among equal scores, the order is larger GE, then lower tier index, then
@@ -68,8 +71,10 @@ def balanced_block(thp: float, thd: float, max_inst: int = 8) -> Tuple[int, int]
 
 
 def goodput_efficiency(thp: float, tpi: int, thd: float, tpj: int, P: int, D: int, rps: float) -> float:
-    """Eq. 1 on a block (R2)."""
-    return min(min(P * thp, D * thd), rps) / (P * tpi + D * tpj)
+    """Eq. 1 as printed: the prefill rate of the block, capped by the tier's rate,
+    per GPU of the block.  ``thd`` does not enter (it fixed P : D beforehand)."""
+    del thd
+    return min(P * thp, rps) / (P * tpi + D * tpj)
 
 
 def plan(n_gpus: int, tiers: List[Tier], max_inst: int = 8) -> Tuple[List[Alloc], int]:

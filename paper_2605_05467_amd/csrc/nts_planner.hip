@@ -6,7 +6,8 @@
 // hands out the GPU pool greedily by the weighted score GE * rps / served_rps.
 // The integer details the paper leaves open are fixed as follows: a block is the
 // (P, D) in 1..max_inst with the closest stage rates (ties: fewer instances, then
-// smaller P) and serves min(P*THP, D*THD); Eq. 1 uses the tier's unmet rate; a
+// smaller P) and serves min(P*THP, D*THD); Eq. 1 is taken as printed (prefill rate
+// only in the numerator) on the block's P, D with the tier's unmet rate; a
 // tier that has been given nothing yet outranks the others; ties go to larger GE,
 // then lower tier, lower prefill TP, lower decode TP; a step gives one block to
 // the best configuration that fits, until no demand is unmet or nothing fits.
@@ -66,7 +67,7 @@ int nts_balanced_block(double thp, double thd, int max_inst, int *P, int *D)
 int nts_goodput_efficiency(double thp, int tpi, double thd, int tpj, int P, int D, double rps, double *ge)
 {
     if (!ge || tpi < 1 || tpj < 1 || P < 1 || D < 1 || !(thp > 0) || !(thd > 0) || !(rps >= 0)) return NTS_EINVAL;
-    const double r = block_rate(thp, thd, P, D);
+    const double r = P * thp;                       // Eq. 1: the prefill rate only
     *ge = (r < rps ? r : rps) / double(P * tpi + D * tpj);
     return NTS_OK;
 }
@@ -82,7 +83,7 @@ int nts_plan_cluster(int n_gpus, int n_tiers, const nts_tier *tiers, int max_ins
         for (int i = 0; i < NTS_TP_LEVELS; ++i)
             if (!(tiers[k].thp[i] >= 0) || !(tiers[k].thd[i] >= 0)) return NTS_EINVAL;
     }
-    struct Cfg { int k, i, j, P, D, gpus; double rate; };
+    struct Cfg { int k, i, j, P, D, gpus; double rate, prefill; };   // rate: what a block serves
     std::vector<Cfg> cfgs;
     std::vector<double> served;
     try {
@@ -97,6 +98,7 @@ int nts_plan_cluster(int n_gpus, int n_tiers, const nts_tier *tiers, int max_ins
                     balanced_block(thp, thd, max_inst, &c.P, &c.D);
                     c.gpus = c.P * kTp[i] + c.D * kTp[j];
                     c.rate = block_rate(thp, thd, c.P, c.D);
+                    c.prefill = c.P * thp;
                     cfgs.push_back(c);
                 }
     } catch (...) {
@@ -110,7 +112,7 @@ int nts_plan_cluster(int n_gpus, int n_tiers, const nts_tier *tiers, int max_ins
         for (const Cfg &c : cfgs) {               // enumeration order = (tier, prefill TP, decode TP) ascending
             const double unmet = tiers[c.k].rps - served[c.k];
             if (!(unmet > 0) || c.gpus > left) continue;
-            const double ge = (c.rate < unmet ? c.rate : unmet) / double(c.gpus);
+            const double ge = (c.prefill < unmet ? c.prefill : unmet) / double(c.gpus);
             const bool fresh = served[c.k] == 0.0;
             const double wge = fresh ? ge : ge * (tiers[c.k].rps / served[c.k]);
             bool better = best == nullptr;

@@ -12,8 +12,13 @@ def test_eq1_hand_values():
     assert op.goodput_efficiency(6.0, 2, 3.0, 1, 1, 2, rps=100.0) == 6.0 / 4.0
     # the tier only sends 3 req/s: Eq. 1 caps the numerator at rps
     assert op.goodput_efficiency(6.0, 2, 3.0, 1, 1, 2, rps=3.0) == 3.0 / 4.0
-    # unbalanced block: the slower stage bounds goodput (both SLOs must hold)
-    assert op.goodput_efficiency(6.0, 2, 3.0, 1, 1, 1, rps=100.0) == 3.0 / 3.0
+    # Eq. 1 by hand on an unbalanced block (P*THP = 6 against D*THD = 3): the printed numerator
+    # holds the prefill rate only, so the score is 6 / 3 GPUs although the block can serve only 3
+    assert op.goodput_efficiency(6.0, 2, 3.0, 1, 1, 1, rps=100.0) == 6.0 / 3.0
+    assert op.goodput_efficiency(6.0, 2, 3.0, 1, 1, 1, rps=4.0) == 4.0 / 3.0
+    # ... and what such a block adds to its tier is the slower stage's rate (both SLOs must hold)
+    allocs, left = op.plan(3, [op.Tier(100.0, [0, 6.0, 0, 0], [3.0, 0, 0, 0])], max_inst=1)
+    assert [(a.P, a.D, a.gpus, a.served) for a in allocs] == [(1, 1, 3, 3.0)] and left == 0
 
 
 def test_balanced_block_is_the_rate_ratio_when_it_is_integral():
