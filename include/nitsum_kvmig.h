@@ -200,8 +200,11 @@ int nts_run_unpack_chunk(nts_plan *plan, const void *chunk_in, int64_t k,
  * whose workgroups alternate between packing chunk k into buffer k&1 and
  * unpacking chunk k-1 from the other buffer, so the two copies overlap; the
  * n_chunks + 1 launches go to hip_stream in order, which hands each buffer
- * from its producer to its consumer.  NTS_EALIAS if a source layer range
- * overlaps a destination layer range or the staging area.
+ * from its producer to its consumer.  The kernels access the pools with
+ * non-temporal loads and stores and the staging buffers with ordinary ones, so
+ * that buffers which together fit the GPU's memory-side cache (256 MiB on
+ * MI355X) are served from it.  NTS_EALIAS if a source layer range overlaps a
+ * destination layer range or the staging area.
  */
 int nts_run_migrate(nts_plan *plan, const void *const *src_layer_ptrs,
                     void *const *dst_layer_ptrs, void *staging, void *hip_stream);
@@ -219,7 +222,8 @@ int nts_run_migrate(nts_plan *plan, const void *const *src_layer_ptrs,
  *   plans           host array of n plans of one context (zero-token plans are skipped)
  *   src_layer_ptrs  host array of n host arrays of 2L device pointers (plan i's source pool)
  *   dst_layer_ptrs  likewise, plan i's destination pool; several plans may share a pool
- *   staging         device, 2 * (largest chunk_bytes among the plans)
+ *   staging         device, 16-byte aligned, nts_batch_staging_bytes() bytes: twice the
+ *                   largest chunk_bytes among the plans rounded up to a multiple of 16
  * Every plan reads its source pool as it was before the call: NTS_EALIAS if any
  * plan's destination layer range overlaps any plan's source layer range or the
  * staging area.  Destinations of different plans that overlap each other are
@@ -229,11 +233,16 @@ int nts_run_migrate(nts_plan *plan, const void *const *src_layer_ptrs,
 int nts_run_migrate_batch(int n, nts_plan *const *plans, const void *const *const *src_layer_ptrs,
                           void *const *const *dst_layer_ptrs, void *staging, void *hip_stream);
 
+/* Size in bytes of the staging area nts_run_migrate_batch needs for these plans
+ * (host arithmetic only): 2 * (largest chunk_bytes, rounded up to 16).  The
+ * rounding keeps the second buffer aligned for plans of every vector width. */
+int nts_batch_staging_bytes(int n, nts_plan *const *plans, int64_t *bytes);
+
 /*
  * The same migration as one kernel from pool to pool, never forming the stream:
  * dst[l][c][dslot[j]][dst_head_off+h][x] = src[l][c][sslot[j]][src_head_off+h][x].
- * Within one address space this is what the paper's "sends it directly to the
- * other GPUs" (Sec. 3.2.2) becomes when the destination pool is mapped into the
+ * Within one address space this is what the direct transfer to the new group's
+ * GPUs (Sec. 3.2.2) becomes when the destination pool is mapped into the
  * sender; it moves each payload byte once instead of twice.  NTS_EALIAS if the
  * pools overlap.
  */

@@ -43,6 +43,7 @@ EXPORTS = (
     "nts_plan_create", "nts_plan_free", "nts_plan_info", "nts_plan_slots", "nts_plan_runs",
     "nts_run_pack", "nts_run_pack_chunk", "nts_run_unpack", "nts_run_unpack_chunk",
     "nts_run_migrate", "nts_run_migrate_batch", "nts_run_migrate_direct", "nts_run_memcpy_baseline",
+    "nts_batch_staging_bytes",
     "nts_shard_linear", "nts_shard_linear_workspace", "nts_shard_linear_launch",
     "nts_balanced_block", "nts_goodput_efficiency", "nts_plan_cluster",
 )
@@ -118,6 +119,7 @@ _lib.nts_run_unpack_chunk.argtypes = [_vp, _vp, _i64, _vp, _vp]
 _lib.nts_run_migrate.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.nts_run_migrate_batch.argtypes = [_i, _vp, _vp, _vp, _vp, _vp]
 _lib.nts_run_migrate_direct.argtypes = [_vp, _vp, _vp, _vp]
+_lib.nts_batch_staging_bytes.argtypes = [_i, _vp, ctypes.POINTER(_i64)]
 _lib.nts_run_memcpy_baseline.argtypes = [_vp, _vp, _vp, _i, _vp, ctypes.POINTER(_i64)]
 _lib.nts_shard_linear_workspace.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(ctypes.c_size_t)]
 _lib.nts_shard_linear_launch.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(nts_linear_launch)]
@@ -267,6 +269,15 @@ def nts_run_migrate_batch(plans, src_layer_ptrs, dst_layer_ptrs, staging: int, h
     _run(_lib.nts_run_migrate_batch(n, arr(*[int(p) for p in plans]),
                                     arr(*[ctypes.addressof(t) for t in stabs]),
                                     arr(*[ctypes.addressof(t) for t in dtabs]), staging, hip_stream))
+
+
+def nts_batch_staging_bytes(plans) -> int:
+    n = len(plans)
+    out = _i64(0)
+    st = _lib.nts_batch_staging_bytes(n, (ctypes.c_void_p * max(n, 1))(*[int(p) for p in plans]), ctypes.byref(out))
+    if st != NTS_OK:
+        raise NtsError(st, "nts_batch_staging_bytes")
+    return out.value
 
 
 def nts_run_migrate_direct(plan: int, src_layer_ptrs, dst_layer_ptrs, hip_stream: int = 0) -> None:

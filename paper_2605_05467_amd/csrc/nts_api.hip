@@ -546,6 +546,49 @@ static int check_pools(nts_plan *pl, const void *const *src_layer_ptrs, void *co
     return NTS_OK;
 }
 
+namespace {
+
+// One pair of a pipeline run: a plan that moves something, with its two pointer tables.
+struct PipeItem {
+    nts_plan *pl;
+    NtsLayerTab stab, dtab;
+};
+
+// The double-buffered pipeline of Sec. 3.2.2 over the chunks of `items`, taken as one
+// sequence g = 0, 1, ...: stage g packs chunk g into buffer g&1 and unpacks chunk g-1 from
+// the other buffer, across pair boundaries too.  The launches go to `st` in order, which
+// hands each buffer from its producer to its consumer.  `stride`: distance of the buffers.
+int run_pipeline(nts_ctx *ctx, PipeItem *items, size_t n_items, char *staging, int64_t stride, hipStream_t st)
+{
+    DeviceGuard guard(ctx->device);
+    for (size_t i = 0; i < n_items; ++i) note_stream(items[i].pl, st);
+    char *buf[2] = {staging, staging + stride};
+    size_t pi = 0;              // pair and chunk being packed
+    int64_t pk = 0;
+    const PipeItem *ui = nullptr;   // pair and chunk packed by the previous stage
+    int64_t uk = 0;
+    for (int64_t g = 0;; ++g) {
+        const PipeItem *ai = pi < n_items ? &items[pi] : nullptr;
+        if (!ai && !ui) break;
+        int64_t pq = 0, pn = 0, uq = 0, un = 0;
+        if (ai) chunk_range(ai->pl, pk, &pq, &pn);
+        if (ui) chunk_range(ui->pl, uk, &uq, &un);
+        const PipeItem *any = ai ? ai : ui;
+        NTS_HIP(ctx, nts_launch_stage(ai ? ai->pl : nullptr, pq, pn, buf[g & 1], ai ? ai->stab : any->stab,
+                                      ui ? ui->pl : nullptr, uq, un, buf[(g - 1) & 1],
+                                      ui ? ui->dtab : any->dtab, st));
+        ui = ai;
+        uk = pk;
+        if (ai && ++pk == ai->pl->n_chunks) {
+            ++pi;
+            pk = 0;
+        }
+    }
+    return NTS_OK;
+}
+
+}  // namespace
+
 int nts_run_migrate(nts_plan *pl, const void *const *src_layer_ptrs, void *const *dst_layer_ptrs,
                     void *staging, void *hip_stream)
 {
@@ -553,30 +596,31 @@ int nts_run_migrate(nts_plan *pl, const void *const *src_layer_ptrs, void *const
     nts_ctx *ctx = pl->ctx;
     if (!src_layer_ptrs || !dst_layer_ptrs) return fail(ctx, NTS_EINVAL, "null layer pointer table");
     if (pl->F == 0) return NTS_OK;
-    NtsLayerTab stab, dtab;
-    const int rc = check_pools(pl, src_layer_ptrs, dst_layer_ptrs, stab, dtab);
+    PipeItem item;
+    item.pl = pl;
+    const int rc = check_pools(pl, src_layer_ptrs, dst_layer_ptrs, item.stab, item.dtab);
     if (rc != NTS_OK) return rc;
     if (!staging) return fail(ctx, NTS_EINVAL, "null staging area");
     if (reinterpret_cast<uintptr_t>(staging) % uintptr_t(pl->vec)) return fail(ctx, NTS_EINVAL, "staging area misaligned");
-    // chunk_bytes is a multiple of the vector width, so the second buffer stays aligned
-    const int64_t buf_stride = pl->chunk_bytes;
-    const char *stg = static_cast<const char *>(staging);
+    char *stg = static_cast<char *>(staging);
     const int64_t src_span = pl->S_src * pl->src_stride, dst_span = pl->S_dst * pl->dst_stride;
     for (int i = 0; i < 2 * pl->L; ++i)
-        if (overlaps(stab.p[i], src_span, stg, 2 * pl->chunk_bytes) || overlaps(dtab.p[i], dst_span, stg, 2 * pl->chunk_bytes))
+        if (overlaps(item.stab.p[i], src_span, stg, 2 * pl->chunk_bytes) ||
+            overlaps(item.dtab.p[i], dst_span, stg, 2 * pl->chunk_bytes))
             return fail(ctx, NTS_EALIAS, "staging area overlaps a pool");
+    // chunk_bytes is a multiple of the vector width, so the second buffer stays aligned
+    return run_pipeline(ctx, &item, 1, stg, pl->chunk_bytes, static_cast<hipStream_t>(hip_stream));
+}
 
-    DeviceGuard guard(ctx->device);
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    note_stream(pl, st);
-    char *buf[2] = {static_cast<char *>(staging), static_cast<char *>(staging) + buf_stride};
-    // stage k: pack chunk k into buffer k&1 while chunk k-1 is unpacked from the other buffer
-    for (int64_t k = 0; k <= pl->n_chunks; ++k) {
-        int64_t pq = 0, pn = 0, uq = 0, un = 0;
-        if (k < pl->n_chunks) chunk_range(pl, k, &pq, &pn);
-        if (k >= 1) chunk_range(pl, k - 1, &uq, &un);
-        NTS_HIP(ctx, nts_launch_stage(pl, pq, pn, buf[k & 1], stab, pl, uq, un, buf[(k - 1) & 1], dtab, st));
+int nts_batch_staging_bytes(int n, nts_plan *const *plans, int64_t *bytes)
+{
+    if (n < 0 || !bytes || (n > 0 && !plans)) return NTS_EINVAL;
+    int64_t largest = 0;
+    for (int i = 0; i < n; ++i) {
+        if (!plans[i]) return NTS_EINVAL;
+        if (plans[i]->F > 0 && plans[i]->chunk_bytes > largest) largest = plans[i]->chunk_bytes;
     }
+    *bytes = 2 * align_up(largest, 16);
     return NTS_OK;
 }
 
@@ -593,24 +637,19 @@ int nts_run_migrate_batch(int n, nts_plan *const *plans, const void *const *cons
     if (!ctx) return NTS_OK;
 
     // the pairs that move something, with their pointer tables
-    struct Item {
-        nts_plan *pl;
-        NtsLayerTab stab, dtab;
-    };
-    std::vector<Item> items;
+    std::vector<PipeItem> items;
     struct Range {
         const char *lo, *hi;
         int is_dst;
     };
     std::vector<Range> ranges;
-    int64_t buf_stride = 0;
     try {
         items.reserve(size_t(n));
         for (int i = 0; i < n; ++i) {
             nts_plan *pl = plans[i];
             if (pl->F == 0) continue;
             items.emplace_back();
-            Item &it = items.back();
+            PipeItem &it = items.back();
             it.pl = pl;
             const int rc = check_pools(pl, src_layer_ptrs[i], dst_layer_ptrs[i], it.stab, it.dtab);
             if (rc != NTS_OK) return rc;
@@ -619,7 +658,6 @@ int nts_run_migrate_batch(int n, nts_plan *const *plans, const void *const *cons
                 ranges.push_back({it.stab.p[k], it.stab.p[k] + src_span, 0});
                 ranges.push_back({it.dtab.p[k], it.dtab.p[k] + dst_span, 1});
             }
-            if (pl->chunk_bytes > buf_stride) buf_stride = pl->chunk_bytes;
         }
     } catch (...) {
         return fail(ctx, NTS_ENOMEM, "host allocation failed");
@@ -627,8 +665,9 @@ int nts_run_migrate_batch(int n, nts_plan *const *plans, const void *const *cons
     if (items.empty()) return NTS_OK;
     if (!staging) return fail(ctx, NTS_EINVAL, "null staging area");
     if (reinterpret_cast<uintptr_t>(staging) % 16u) return fail(ctx, NTS_EINVAL, "staging area misaligned");
-    buf_stride = (buf_stride + 15) / 16 * 16;   // keeps the second buffer aligned for every plan
-    char *buf[2] = {static_cast<char *>(staging), static_cast<char *>(staging) + buf_stride};
+    int64_t staging_bytes = 0;
+    (void)nts_batch_staging_bytes(n, plans, &staging_bytes);
+    char *stg = static_cast<char *>(staging);
 
     // No destination range may meet a source range of ANY plan, nor the staging area: sort
     // by start and sweep, remembering how far the sources and the destinations seen so far reach.
@@ -637,38 +676,12 @@ int nts_run_migrate_batch(int n, nts_plan *const *plans, const void *const *cons
     for (const Range &r : ranges) {
         if (reach[1 - r.is_dst] && r.lo < reach[1 - r.is_dst])
             return fail(ctx, NTS_EALIAS, "a destination pool of the batch overlaps a source pool of the batch");
-        if (overlaps(r.lo, r.hi - r.lo, buf[0], 2 * buf_stride))
+        if (overlaps(r.lo, r.hi - r.lo, stg, staging_bytes))
             return fail(ctx, NTS_EALIAS, "staging area overlaps a pool");
         if (!reach[r.is_dst] || r.hi > reach[r.is_dst]) reach[r.is_dst] = r.hi;
     }
-
-    DeviceGuard guard(ctx->device);
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    for (Item &it : items) note_stream(it.pl, st);
-    // The chunks of all pairs form one sequence g = 0, 1, ...; stage g packs chunk g into
-    // buffer g&1 and unpacks chunk g-1 from the other buffer, across pair boundaries too.
-    size_t pi = 0;          // pair and chunk being packed
-    int64_t pk = 0;
-    const Item *ui = nullptr;   // pair and chunk packed by the previous stage
-    int64_t uk = 0;
-    for (int64_t g = 0;; ++g) {
-        const Item *ai = pi < items.size() ? &items[pi] : nullptr;
-        if (!ai && !ui) break;
-        int64_t pq = 0, pn = 0, uq = 0, un = 0;
-        if (ai) chunk_range(ai->pl, pk, &pq, &pn);
-        if (ui) chunk_range(ui->pl, uk, &uq, &un);
-        const Item *any = ai ? ai : ui;
-        NTS_HIP(ctx, nts_launch_stage(ai ? ai->pl : nullptr, pq, pn, buf[g & 1], ai ? ai->stab : any->stab,
-                                      ui ? ui->pl : nullptr, uq, un, buf[(g - 1) & 1],
-                                      ui ? ui->dtab : any->dtab, st));
-        ui = ai;
-        uk = pk;
-        if (ai && ++pk == ai->pl->n_chunks) {
-            ++pi;
-            pk = 0;
-        }
-    }
-    return NTS_OK;
+    // the second buffer starts 16-byte aligned whatever the plans' vector widths
+    return run_pipeline(ctx, items.data(), items.size(), stg, staging_bytes / 2, static_cast<hipStream_t>(hip_stream));
 }
 
 int nts_run_migrate_direct(nts_plan *pl, const void *const *src_layer_ptrs, void *const *dst_layer_ptrs,

@@ -31,6 +31,9 @@ def _check_pair(h, dst_d, tag):
 
 @pytest.mark.parametrize("first", [0, 7, 14, 21, 28, 35])
 def test_batch_of_unrelated_pairs_equals_the_oracle_pair_by_pair(env, first):
+    """The staging area has exactly the size nts_batch_staging_bytes names (the
+    documented contract, mixed vector widths included) and is followed by guard
+    bytes that must stay as they were."""
     torch, b, ctx = env
     st = torch.cuda.current_stream().cuda_stream
     plans, stabs, dtabs, hosts, dsts, keep = [], [], [], [], [], []
@@ -51,15 +54,59 @@ def test_batch_of_unrelated_pairs_equals_the_oracle_pair_by_pair(env, first):
             dsts.append(dst_d)
             keep.append(src_d)
         infos = [b.nts_plan_info(p) for p in plans]
-        need = 2 * max((i.chunk_bytes + 15) // 16 * 16 for i in infos)
-        staging = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        need = b.nts_batch_staging_bytes(plans)
+        assert need == 2 * max((i.chunk_bytes + 15) // 16 * 16 for i in infos if i.F)
+        guard = 4096
+        staging = torch.full((need + guard,), 0xA5, dtype=torch.uint8, device="cuda")
         b.nts_run_migrate_batch(plans, stabs, dtabs, staging.data_ptr(), st)
         torch.cuda.synchronize()
+        assert bool((staging[need:] == 0xA5).all()), "wrote past the documented staging size"
         for k, (h, dst_d) in enumerate(zip(hosts, dsts)):
             _check_pair(h, dst_d, (first, k))
         for h, src_d in zip(hosts, keep):                              # sources untouched
             for a, t in zip(h["src_arr"], src_d):
                 assert t.cpu().numpy().tobytes() == a.tobytes()
+    finally:
+        for p in plans:
+            b.nts_plan_free(p)
+
+
+def test_batch_staging_contract_with_a_12_byte_fragment(env):
+    """A 12-byte fragment forces 4-byte vectors and a chunk size that is no
+    multiple of 16; next to a plan with 16-byte vectors the second buffer must
+    still start aligned and end inside nts_batch_staging_bytes."""
+    torch, b, ctx = env
+    st = torch.cuda.current_stream().cuda_stream
+    L, S, T = 2, 64, 40
+    rng = SplitMix64(515)
+    plans, stabs, dtabs, want, dsts = [], [], [], [], []
+    try:
+        for D, e, H, B in ((3, 4, 1, 60), (8, 2, 2, 64)):          # 12-byte and 32-byte fragments
+            dt = {2: np.uint16, 4: np.uint32}[e]
+            src = (rng.words(L * 2 * S * H * D) & np.uint64(np.iinfo(dt).max)).astype(dt).reshape(L, 2, S, H, D)
+            dst = (rng.words(L * 2 * S * H * D) & np.uint64(np.iinfo(dt).max)).astype(dt).reshape(L, 2, S, H, D)
+            ss, ds = rng.permutation(S)[:T].astype(np.int32), rng.permutation(S)[:T].astype(np.int32)
+            exp = dst.copy()
+            orc.migrate(src, exp, ss, ds, 0, 0, H)
+            sd = torch.from_numpy(src.view(np.uint8).reshape(-1)).cuda()
+            dd = torch.from_numpy(dst.view(np.uint8).reshape(-1)).cuda()
+            plans.append(b.nts_plan_create(ctx, L=L, D=D, elem_bytes=e, page_size=1, Hs=H, Hd=H, src_head_off=0,
+                                           dst_head_off=0, w=H, S_src=S, S_dst=S, ctx_len=[T], src_pages=ss,
+                                           dst_pages=ds, staging_bytes=B, flags=b.NTS_VALIDATE_UNIQUE_DST))
+            stabs.append(b.layer_ptrs(sd.data_ptr(), L, S * H * D * e))
+            dtabs.append(b.layer_ptrs(dd.data_ptr(), L, S * H * D * e))
+            want.append((dst, exp))
+            dsts.append((sd, dd))
+        infos = [b.nts_plan_info(p) for p in plans]
+        assert infos[0].vec_bytes == 4 and infos[0].chunk_bytes == 60 and infos[1].vec_bytes == 16
+        need = b.nts_batch_staging_bytes(plans)
+        assert need == 2 * 64
+        staging = torch.full((need + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+        b.nts_run_migrate_batch(plans, stabs, dtabs, staging.data_ptr(), st)
+        torch.cuda.synchronize()
+        assert bool((staging[need:] == 0xA5).all())
+        for (sd, dd), (dst, exp) in zip(dsts, want):
+            assert dd.cpu().numpy().tobytes() == exp.tobytes()
     finally:
         for p in plans:
             b.nts_plan_free(p)
@@ -122,8 +169,7 @@ def test_whole_tp_switch_as_one_batch_matches_the_oracle_cluster(env):
                 stabs.append(b.layer_ptrs(dev[s].data_ptr(), L, S * Hs * D * 2))
                 dtabs.append(b.layer_ptrs(new_dev[d].data_ptr(), L, S * Hn * D * 2))
             assert len(plans) >= G
-            need = 2 * max((b.nts_plan_info(p).chunk_bytes + 15) // 16 * 16 for p in plans)
-            staging = torch.empty(need, dtype=torch.uint8, device="cuda")
+            staging = torch.empty(b.nts_batch_staging_bytes(plans), dtype=torch.uint8, device="cuda")
             b.nts_run_migrate_batch(plans, stabs, dtabs, staging.data_ptr(), st)
             torch.cuda.synchronize()
         finally:
