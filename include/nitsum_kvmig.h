@@ -64,7 +64,8 @@ enum {
     NTS_MAX_LAYERS = 96,          /* 2*L base pointers travel as kernel arguments */
     NTS_VALIDATE_UNIQUE_DST = 1u, /* plan flag: check destination slots are distinct */
     NTS_DETECT_RUNS = 2u,         /* plan flag: also find the runs of neighbouring slots */
-    NTS_DEFAULT_STAGING_BYTES = 64 << 20
+    NTS_DEFAULT_STAGING_BYTES = 64 << 20,
+    NTS_STATIC_STAGING_BYTES = 32 << 20   /* both buffers of nts_run_migrate_static together */
 };
 
 /*
@@ -208,6 +209,23 @@ int nts_run_unpack_chunk(nts_plan *plan, const void *chunk_in, int64_t k,
  */
 int nts_run_migrate(nts_plan *plan, const void *const *src_layer_ptrs,
                     void *const *dst_layer_ptrs, void *staging, void *hip_stream);
+
+/*
+ * nts_run_migrate for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  The two staging buffers live in a static device array of
+ * NTS_STATIC_STAGING_BYTES that the library holds on every GPU it runs on from
+ * load until the process ends; the call itself allocates nothing and frees
+ * nothing on the device.  The plan must have been created with staging_bytes <=
+ * NTS_STATIC_STAGING_BYTES / 2 (so that 2 * chunk_bytes fits): NTS_EINVAL with an
+ * explanatory message otherwise.  Result, other errors and stream semantics
+ * as nts_run_migrate.  All calls on one GPU share the one array, whatever their
+ * context or stream, and it keeps the bytes of the last call (nothing in it
+ * needs to start at zero): calls that overlap in time on one GPU race on it and
+ * must be ordered by the caller (one stream, or events).
+ */
+int nts_run_migrate_static(nts_plan *plan, const void *const *src_layer_ptrs,
+                           void *const *dst_layer_ptrs, void *hip_stream);
 
 /*
  * Several (source, destination) pairs as ONE pipeline.  A TP switch moves KV

@@ -37,13 +37,14 @@ NTS_MAX_LAYERS = 96
 NTS_VALIDATE_UNIQUE_DST = 1
 NTS_DETECT_RUNS = 2
 NTS_DEFAULT_STAGING_BYTES = 64 << 20
+NTS_STATIC_STAGING_BYTES = 32 << 20
 
 EXPORTS = (
     "nts_init", "nts_free", "nts_last_error", "nts_strerror", "nts_route",
     "nts_plan_create", "nts_plan_free", "nts_plan_info", "nts_plan_slots", "nts_plan_runs",
     "nts_run_pack", "nts_run_pack_chunk", "nts_run_unpack", "nts_run_unpack_chunk",
     "nts_run_migrate", "nts_run_migrate_batch", "nts_run_migrate_direct", "nts_run_memcpy_baseline",
-    "nts_batch_staging_bytes",
+    "nts_batch_staging_bytes", "nts_run_migrate_static",
     "nts_shard_linear", "nts_shard_linear_workspace", "nts_shard_linear_launch",
     "nts_balanced_block", "nts_goodput_efficiency", "nts_plan_cluster",
 )
@@ -119,6 +120,7 @@ _lib.nts_run_unpack_chunk.argtypes = [_vp, _vp, _i64, _vp, _vp]
 _lib.nts_run_migrate.argtypes = [_vp, _vp, _vp, _vp, _vp]
 _lib.nts_run_migrate_batch.argtypes = [_i, _vp, _vp, _vp, _vp, _vp]
 _lib.nts_run_migrate_direct.argtypes = [_vp, _vp, _vp, _vp]
+_lib.nts_run_migrate_static.argtypes = [_vp, _vp, _vp, _vp]
 _lib.nts_batch_staging_bytes.argtypes = [_i, _vp, ctypes.POINTER(_i64)]
 _lib.nts_run_memcpy_baseline.argtypes = [_vp, _vp, _vp, _i, _vp, ctypes.POINTER(_i64)]
 _lib.nts_shard_linear_workspace.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(ctypes.c_size_t)]
@@ -269,6 +271,10 @@ def nts_run_migrate_batch(plans, src_layer_ptrs, dst_layer_ptrs, staging: int, h
     _run(_lib.nts_run_migrate_batch(n, arr(*[int(p) for p in plans]),
                                     arr(*[ctypes.addressof(t) for t in stabs]),
                                     arr(*[ctypes.addressof(t) for t in dtabs]), staging, hip_stream))
+
+
+def nts_run_migrate_static(plan: int, src_layer_ptrs, dst_layer_ptrs, hip_stream: int = 0) -> None:
+    _run(_lib.nts_run_migrate_static(plan, _tab(src_layer_ptrs), _tab(dst_layer_ptrs), hip_stream))
 
 
 def nts_batch_staging_bytes(plans) -> int:

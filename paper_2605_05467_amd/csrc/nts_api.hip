@@ -8,6 +8,11 @@
 
 #include "nts_internal.h"
 
+// Staging area of nts_run_migrate_static: device memory that exists from the moment the
+// library is loaded, one copy per GPU.  Host code never uses this name as an address: each
+// context asks the runtime for its device's copy once (nts_init) and passes that pointer on.
+static __device__ __align__(256) unsigned char scratch[NTS_STATIC_STAGING_BYTES];
+
 namespace {
 
 struct DeviceGuard {
@@ -111,6 +116,8 @@ int nts_init(int device_id, nts_ctx **out)
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking);
     for (int i = 0; i < nts_ctx::kSpares && e == hipSuccess; ++i)
         e = hipEventCreateWithFlags(&ctx->spare[i].ev, hipEventDisableTiming);
+    // this device's copy of the static staging area (the device is current here)
+    if (e == hipSuccess) e = hipGetSymbolAddress(&ctx->static_staging, HIP_SYMBOL(scratch));
     if (e != hipSuccess) {
         nts_free(ctx);
         (void)hipGetLastError();
@@ -610,6 +617,18 @@ int nts_run_migrate(nts_plan *pl, const void *const *src_layer_ptrs, void *const
             return fail(ctx, NTS_EALIAS, "staging area overlaps a pool");
     // chunk_bytes is a multiple of the vector width, so the second buffer stays aligned
     return run_pipeline(ctx, &item, 1, stg, pl->chunk_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int nts_run_migrate_static(nts_plan *pl, const void *const *src_layer_ptrs, void *const *dst_layer_ptrs,
+                           void *hip_stream)
+{
+    if (!pl) return NTS_EINVAL;
+    nts_ctx *ctx = pl->ctx;
+    if (2 * pl->chunk_bytes > int64_t(NTS_STATIC_STAGING_BYTES))
+        return fail(ctx, NTS_EINVAL, "the plan's two staging buffers exceed NTS_STATIC_STAGING_BYTES: "
+                                     "create the plan with staging_bytes <= NTS_STATIC_STAGING_BYTES / 2");
+    if (!ctx->static_staging) return fail(ctx, NTS_EHIP, "static staging area unavailable");
+    return nts_run_migrate(pl, src_layer_ptrs, dst_layer_ptrs, ctx->static_staging, hip_stream);
 }
 
 int nts_batch_staging_bytes(int n, nts_plan *const *plans, int64_t *bytes)

@@ -14,6 +14,7 @@
 struct nts_ctx {
     int device = 0;
     hipStream_t aux = nullptr;          // planning work (copies, flatten kernel)
+    void *static_staging = nullptr;     // this device's copy of the library's static staging array
     void *h_pinned = nullptr;           // pinned host staging for plan metadata
     size_t h_pinned_bytes = 0;
     // Device blocks of freed plans, kept for reuse.  A block may still be read by kernels of
