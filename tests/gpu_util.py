@@ -6,8 +6,11 @@ import ctypes
 
 import numpy as np
 
+import threading
+from concurrent.futures import ThreadPoolExecutor
+
 from oracle import kvmig as orc
-from workload import SplitMix64, fill_words
+from workload import SplitMix64, fill_words, fill_words_fast
 from workload.configs import PairCase
 
 
@@ -40,6 +43,61 @@ def device_pool(case: PairCase, side: str, L=None, D=None):
     t = torch.empty(L * 2 * S * Hl * D * sh.e, dtype=torch.uint8, device="cuda")
     wdev.fill_tensor(t, seed)
     return t
+
+
+def compare_every_layer(case: PairCase, dst_d, sslot, dslot, workers: int = 10, label: str = "",
+                        direct: bool = False) -> float:
+    """Every byte of the destination pool against the oracle, layer by layer.
+
+    The oracle's loops are independent per layer, so each layer is one job of a
+    thread pool: regenerate that layer of the source pool and of the
+    destination's sentinel fill on the host (stateless fill), run the oracle's
+    migration on the pair, copy the GPU's layer back and compare all bytes,
+    untouched ones included.  Host memory stays at three layers per worker
+    whatever the pool size.  ``direct`` picks the oracle's pool-to-pool loop
+    instead of unpack-after-pack (they are pinned to each other; the former
+    needs no stream-sized temporary).  Returns the seconds the oracle's
+    migration calls took, summed over layers."""
+    import torch
+    sh = case.shape
+    so, do, w = orc.route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
+    dt = np_dtype(sh.e)
+    src_words = 2 * case.S_src * case.Hs * sh.D * sh.e // 8
+    dst_words = 2 * case.S_dst * case.Hd * sh.D * sh.e // 8
+    assert (2 * case.S_src * case.Hs * sh.D * sh.e) % 8 == 0 and (2 * case.S_dst * case.Hd * sh.D * sh.e) % 8 == 0
+    local = threading.local()
+    oracle_seconds = [0.0]
+    lock = threading.Lock()
+    dst_bytes = dst_d.view(torch.uint8).reshape(-1)
+
+    def one_layer(l):
+        import time
+        if not hasattr(local, "src"):
+            local.src = np.empty(src_words, dtype="<u8")
+            local.want = np.empty(dst_words, dtype="<u8")
+            local.got = np.empty(dst_words, dtype="<u8")
+        fill_words_fast(case.seed_src, l * src_words, src_words, local.src)
+        fill_words_fast(case.seed_dst, l * dst_words, dst_words, local.want)
+        src = local.src.view(dt).reshape(1, 2, case.S_src, case.Hs, sh.D)
+        want = local.want.view(dt).reshape(1, 2, case.S_dst, case.Hd, sh.D)
+        t0 = time.perf_counter()
+        (orc.migrate_direct if direct else orc.migrate)(src, want, sslot, dslot, so, do, w)
+        dt_oracle = time.perf_counter() - t0
+        torch.from_numpy(local.got.view(np.uint8)).copy_(dst_bytes[l * dst_words * 8:(l + 1) * dst_words * 8])
+        same = np.array_equal(local.got, local.want)
+        with lock:
+            oracle_seconds[0] += dt_oracle
+        return l, same
+
+    bad = []
+    with ThreadPoolExecutor(max_workers=min(workers, sh.L)) as ex:
+        for l, same in ex.map(one_layer, range(sh.L)):
+            if l % 8 == 7 or not same:
+                print(f"    {label or case.name}: layers ..{l} compared with the oracle", flush=True)
+            if not same:
+                bad.append(l)
+    assert not bad, (label or case.name, "layers differ from the oracle", bad)
+    return oracle_seconds[0]
 
 
 def slab_bytes(case: PairCase, side: str, D=None) -> int:

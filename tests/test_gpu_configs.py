@@ -1,12 +1,17 @@
 """GPU parity at the benchmark configurations, in the launch configuration
 bench.py times (route + plan + double-buffered migrate, 64 MiB staging).
 
-Configuration 2 is compared whole.  The larger ones are compared (a) whole
-layers at a time against the oracle run on those layers (layers are independent
-in the oracle's loops), (b) on randomly sampled single elements the oracle
-locates one by one, with the value taken from the stateless fill's closed form,
-and (c) through properties that hold at any size: the source pool is unchanged
-and exactly payload-many words of the destination differ from its sentinel fill.
+Every configuration is compared whole: all bytes of the destination pool,
+untouched ones included, against the oracle.  Configuration 2 holds both pools
+on the host at once; the larger ones (3, its companions, 4, and the two 92 GiB
+pools of 5) go layer by layer through a thread pool (layers are independent in
+the oracle's loops; each job regenerates its layer of both pools from the
+stateless fill, runs the oracle and compares that layer of the GPU's pool), so
+host memory stays at a few layers.  Before that, as fast pre-checks: randomly
+sampled single elements the oracle locates one by one, with the value taken
+from the stateless fill's closed form, and two properties that hold at any
+size (the source pool is unchanged; exactly payload-many words of the
+destination differ from its sentinel fill).
 """
 import numpy as np
 import pytest
@@ -58,22 +63,6 @@ def check_properties(env, case, src_d, dst_d, info):
     assert changed == info.X // 8, (changed, info.X // 8)
 
 
-def check_layers(env, case, dst_d, layers, sslot, dslot):
-    from gpu_util import host_layers
-    torch = env[0]
-    sh = case.shape
-    so, do, w = orc.route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
-    layer_bytes = 2 * case.S_dst * case.Hd * sh.D * sh.e
-    for l in layers:
-        print(f"  {case.name}: oracle on layer {l}", flush=True)
-        src_h = host_layers(case, "src", [l])
-        want = host_layers(case, "dst", [l]).copy()
-        orc.migrate(src_h, want, sslot, dslot, so, do, w)
-        got = dst_d[l * layer_bytes:(l + 1) * layer_bytes].cpu().numpy()
-        assert got.tobytes() == want.tobytes(), (case.name, l)
-        del src_h, want, got
-
-
 def _fill_elem(seed, lin):
     word = int(fill_words(seed, lin // 4, 1)[0])
     return (word >> (16 * (lin % 4))) & 0xFFFF
@@ -113,7 +102,7 @@ def check_samples(env, case, dst_d, sslot, dslot, n=400, seed=99):
 
 
 def test_config2_whole_outputs(env):
-    from gpu_util import host_layers, oracle_slots
+    from gpu_util import compare_every_layer, oracle_slots
     for case in make_case("c2"):
         print(f"  {case.name}", flush=True)
         sh = case.shape
@@ -122,17 +111,13 @@ def test_config2_whole_outputs(env):
         assert np.array_equal(s, es) and np.array_equal(d, ed)
         assert info.F == case.T * sh.L * 2
         check_properties(env, case, src_d, dst_d, info)
-        so, do, w = orc.route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
-        src_h = host_layers(case, "src", range(sh.L))
-        want = host_layers(case, "dst", range(sh.L)).copy()
-        orc.migrate(src_h, want, es, ed, so, do, w)
-        assert dst_d.cpu().numpy().tobytes() == want.tobytes()
-        del src_h, want, src_d, dst_d
+        compare_every_layer(case, dst_d, es, ed)
+        del src_d, dst_d
 
 
 @pytest.mark.parametrize("name", ["c3", "c3b", "c3c", "c3d"])
 def test_config3_headline_and_companions(env, name):
-    from gpu_util import oracle_slots
+    from gpu_util import compare_every_layer, oracle_slots
     for case in make_case(name):
         src_d, dst_d, info, s, d = migrate_on_gpu(env, case)
         es, ed = oracle_slots(case)
@@ -142,13 +127,13 @@ def test_config3_headline_and_companions(env, name):
         if name == "c3b":
             assert info.X == 2 ** 29
         check_properties(env, case, src_d, dst_d, info)
-        check_layers(env, case, dst_d, [0, 31] if name == "c3" else [17], es, ed)
         check_samples(env, case, dst_d, es, ed)
+        compare_every_layer(case, dst_d, es, ed)
         del src_d, dst_d
 
 
 def test_config4_skewed_four_destinations(env):
-    from gpu_util import oracle_slots
+    from gpu_util import compare_every_layer, oracle_slots
     cases = make_case("c4")
     src_d = None
     total_F = 0
@@ -158,16 +143,17 @@ def test_config4_skewed_four_destinations(env):
         assert np.array_equal(s, es) and np.array_equal(d, ed)
         total_F += info.F
         check_properties(env, case, src_d, dst_d, info)
-        check_layers(env, case, dst_d, [5], es, ed)
         check_samples(env, case, dst_d, es, ed, n=200)
+        compare_every_layer(case, dst_d, es, ed)
         del dst_d
     assert total_F == 2621440
 
 
 def test_config5_roofline_size(env):
-    """Two 92 GiB pools, 88 GiB payload: one whole layer, sampled elements, and
-    the any-size properties."""
-    from gpu_util import oracle_slots
+    """Two 92 GiB pools, 88 GiB payload: every byte of the destination pool
+    against the oracle, layer by layer, for the double-buffered pipeline and for
+    the pool-to-pool kernel; sampled elements and the any-size properties first."""
+    from gpu_util import compare_every_layer, oracle_slots
     torch = env[0]
     free, total = torch.cuda.mem_get_info()
     case = make_case("c5")[0]
@@ -180,7 +166,7 @@ def test_config5_roofline_size(env):
     assert info.F == 46137344 and info.X == 88 * 2 ** 30
     check_properties(env, case, src_d, dst_d, info)
     check_samples(env, case, dst_d, es, ed, n=600)
-    check_layers(env, case, dst_d, [19], es, ed)
+    compare_every_layer(case, dst_d, es, ed, label="c5 pipeline", direct=True)
     # the pool-to-pool kernel at this size needs three launches (fewer than 2^31 lanes each)
     from gpu_util import slab_bytes
     from workload import device as wdev
@@ -196,7 +182,7 @@ def test_config5_roofline_size(env):
         torch.cuda.synchronize()
         check_properties(env, case, src_d, dst_d, info)
         check_samples(env, case, dst_d, es, ed, n=600, seed=7)
-        check_layers(env, case, dst_d, [31], es, ed)
+        compare_every_layer(case, dst_d, es, ed, label="c5 pool-to-pool", direct=True)
         # one chunk of the stream, far into it, against the oracle's pack of that layer
         k = info.n_chunks - 3
         buf = torch.empty(info.chunk_bytes, dtype=torch.uint8, device="cuda")
@@ -219,7 +205,7 @@ def test_config5_roofline_size(env):
 @pytest.mark.parametrize("variant", ["p16", "fp8", "70b"])
 def test_other_kv_geometries_at_size(env, variant):
     """16-token pages, 1-byte elements and an 80-layer model at 8192 tokens."""
-    from gpu_util import oracle_slots
+    from gpu_util import compare_every_layer, oracle_slots
     from workload import M8B, ModelShape
     if variant == "p16":
         case = make_case("c3", shape=M8B, p=16, tokens=8192)[0]
@@ -231,7 +217,7 @@ def test_other_kv_geometries_at_size(env, variant):
     es, ed = oracle_slots(case)
     assert np.array_equal(s, es) and np.array_equal(d, ed)
     check_properties(env, case, src_d, dst_d, info)
-    check_layers(env, case, dst_d, [case.shape.L - 1], es, ed)
+    compare_every_layer(case, dst_d, es, ed)
     if case.shape.e == 2:
         check_samples(env, case, dst_d, es, ed, n=200)
 
@@ -241,7 +227,7 @@ def test_back_to_back_pairs_without_synchronising(env):
     synchronisation in between (what bench.py does for configuration 4): a freed
     plan's device block is recycled by the next plan only after the kernels
     that still read it have finished."""
-    from gpu_util import device_pool, make_plan, oracle_slots, slab_bytes
+    from gpu_util import compare_every_layer, device_pool, make_plan, oracle_slots, slab_bytes
     torch, b, wdev, ctx, staging = env
     cases = make_case("c4", tokens=8192)
     assert len({c.T for c in cases}) > 1
@@ -263,5 +249,5 @@ def test_back_to_back_pairs_without_synchronising(env):
     for case, dst_d, info in zip(cases, dsts, infos):
         es, ed = oracle_slots(case)
         check_properties(env, case, src_d, dst_d, info)
-        check_layers(env, case, dst_d, [11], es, ed)
+        compare_every_layer(case, dst_d, es, ed)
         check_samples(env, case, dst_d, es, ed, n=100)

@@ -1,12 +1,21 @@
 """GPU parity of the TP-shard-selecting linear layer against its fp64 oracle.
-Tolerance (derived in oracle.shard_linear.tolerance): fp32 accumulation of K
-products in any order plus one rounding to bfloat16."""
+
+Random inputs: two tolerances, both from oracle.shard_linear.  `tolerance` is
+the worst-case bound (fp32 accumulation of K products in any order plus one
+rounding); it grows with K and no longer notices a dropped product from
+K = 4096 on.  `tight_tolerance` is half an output ulp plus the error fp32
+accumulation typically makes (random-walk model, eight-fold margin); a dropped
+or doubled product exceeds it at every K.  Every element must be inside both.
+
+Integer inputs (|x|, |w| <= 8, exact in bf16 / fp16): every product and every
+fp32 partial sum is exact whatever the order, so the result must equal the
+oracle's fp64 result rounded once to nearest even, bit for bit."""
 import numpy as np
 import pytest
 
 from linear_cases import CASES
 from oracle import shard_linear as osl
-from workload.linear import LAYERS, linear_inputs
+from workload.linear import LAYERS, linear_inputs, linear_inputs_int
 
 pytestmark = pytest.mark.gpu
 
@@ -20,11 +29,13 @@ def env():
     b.nts_free(ctx)
 
 
-def run_case(env, M, n_out, n_in, tp, rank, split, seed=1, pad=0, dtype="bf16", pad_y=None):
+def run_case(env, M, n_out, n_in, tp, rank, split, seed=1, pad=0, dtype="bf16", pad_y=None, exact=False):
+    """exact=False: random real inputs, result inside both tolerances.
+    exact=True: integer inputs, result bit-identical to the once-rounded oracle."""
     torch, b, ctx = env
     k = n_in if split == "out" else n_in // tp
     nn = n_out // tp if split == "out" else n_out
-    Xh, Wh = linear_inputs(seed, M, n_out, n_in, x_cols=k, dtype=dtype)
+    Xh, Wh = (linear_inputs_int if exact else linear_inputs)(seed, M, n_out, n_in, x_cols=k, dtype=dtype)
     decode = osl.bf16_to_f64 if dtype == "bf16" else osl.f16_to_f64
     ldx, ldw, ldy = k + pad, n_in + pad, nn + (pad if pad_y is None else pad_y)
     Xp = np.zeros((M, ldx), np.uint16); Xp[:, :k] = Xh
@@ -41,14 +52,23 @@ def run_case(env, M, n_out, n_in, tp, rank, split, seed=1, pad=0, dtype="bf16", 
                        workspace_bytes=ws_bytes, hip_stream=torch.cuda.current_stream().cuda_stream, **kw)
     torch.cuda.synchronize()
     Yg = Yd.cpu().numpy().view(np.uint16)
-    want, bound = osl.shard_linear(decode(Xh), decode(Wh), tp, rank, split)
-    got = decode(Yg[:, :nn])
-    tol = osl.tolerance(want, bound, k, out_bits=8 if dtype == "bf16" else 11)
-    err = np.abs(got - want)
-    assert np.all(err <= tol), (float((err / tol).max()), np.unravel_index(np.argmax(err / tol), err.shape))
+    X64, W64 = decode(Xh), decode(Wh)
+    want, bound = osl.shard_linear(X64, W64, tp, rank, split)
     if ldy > nn:
         assert np.all(Yg[:, nn:] == 12345)                     # nothing written past the output width
-    return float((err / tol).max())
+    if exact:
+        assert k * 64 < 2 ** 24                                 # every partial sum is an exact fp32 integer
+        want_bits = osl.round_to_bits(want, dtype)
+        same = Yg[:, :nn] == want_bits
+        assert same.all(), (int((~same).sum()), np.argwhere(~same)[:4].tolist())
+        return 0.0
+    got = decode(Yg[:, :nn])
+    tol = osl.tolerance(want, bound, k, out_bits=8 if dtype == "bf16" else 11)
+    tight = osl.tight_tolerance(want, osl.product_norm(X64, W64, tp, rank, split), k, dtype)
+    err = np.abs(got - want)
+    assert np.all(err <= tol), (float((err / tol).max()), np.unravel_index(np.argmax(err / tol), err.shape))
+    assert np.all(err <= tight), (float((err / tight).max()), np.unravel_index(np.argmax(err / tight), err.shape))
+    return float((err / tight).max())
 
 
 @pytest.mark.parametrize("M", [1, 7, 16, 33, 64])
@@ -116,6 +136,9 @@ def test_every_kernel_variant(env, case, split):
     assert (l.tile_rows, l.tile_cols, l.k_splits > 1, l.k_waves) == (rows, cols, is_split, k_waves)
     run_case(env, M, n_out, n_in, 2, 1, split, seed=M + Nn, pad=pad,
              dtype="f16" if (M + Nn // 8) % 3 == 0 else "bf16")
+    # and bit-exact on integer inputs, in both element formats
+    run_case(env, M, n_out, n_in, 2, 1, split, seed=M + Nn + 1, pad=pad, dtype="bf16", exact=True)
+    run_case(env, M, n_out, n_in, 2, 1, split, seed=M + Nn + 2, pad=pad, dtype="f16", exact=True)
 
 
 @pytest.mark.parametrize("M", [520, 777])
@@ -188,12 +211,58 @@ def test_bench_shapes_sampled_rows(env, layer):
                                workspace_bytes=ws_bytes, hip_stream=torch.cuda.current_stream().cuda_stream, **kw)
             torch.cuda.synchronize()
             rows = np.unique(np.concatenate([[0, 1, M // 2, M - 1], rng.integers(0, M, 4)]))
-            want, bound = osl.shard_linear(osl.bf16_to_f64(Xm[rows]), Wf, tp, tp - 1, split)
+            Xr = osl.bf16_to_f64(Xm[rows])
+            want, bound = osl.shard_linear(Xr, Wf, tp, tp - 1, split)
             got = osl.bf16_to_f64(Yd[torch.from_numpy(rows).cuda()].cpu().numpy().view(np.uint16))
             tol = osl.tolerance(want, bound, k, out_bits=8)
+            tight = osl.tight_tolerance(want, osl.product_norm(Xr, Wf, tp, tp - 1, split), k, "bf16")
             err = np.abs(got - want)
             assert got.shape == want.shape == (len(rows), nn)
             assert np.all(err <= tol), (layer, tp, M, float((err / tol).max()))
+            assert np.all(err <= tight), (layer, tp, M, float((err / tight).max()))
+
+
+@pytest.mark.parametrize("layer", ["8b_qkv", "8b_o", "8b_gate_up", "8b_down", "14b_qkv", "14b_down"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_bench_shapes_bit_exact_on_integer_inputs(env, layer, dtype):
+    """Full 8B / 14B layers (reductions of 4096 ... 14336 terms at TP1), every batch
+    size bench.py --linear times, TP 1 and 4: integer inputs, so the sampled whole
+    output rows must equal the once-rounded oracle bit for bit.  The batches must
+    between them reach the decode, streaming and tiled kernels, with and without a
+    split reduction."""
+    torch, b, ctx = env
+    n_out, n_in, split = LAYERS[layer]
+    Xh, Wh = linear_inputs_int(91, 4096, n_out, n_in, dtype=dtype)
+    decode = osl.bf16_to_f64 if dtype == "bf16" else osl.f16_to_f64
+    Wf = decode(Wh)
+    Wd = torch.from_numpy(Wh.view(np.int16)).cuda()
+    sp = b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN
+    rng = np.random.default_rng(6)
+    seen = set()
+    for tp in (1, 4):
+        k = n_in if split == "out" else n_in // tp
+        nn = n_out // tp if split == "out" else n_out
+        for M in (1, 16, 64, 256, 1024, 4096):
+            Xm = np.ascontiguousarray(Xh[:M, :k])
+            Xd = torch.from_numpy(Xm.view(np.int16)).cuda()
+            Yd = torch.full((M, nn), 12345, dtype=torch.int16, device="cuda")
+            kw = dict(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=tp - 1, split=sp,
+                      dtype=b.NTS_BF16 if dtype == "bf16" else b.NTS_F16)
+            how = b.nts_shard_linear_launch(**kw)
+            seen.add(("tiled" if how.tiled else "decode" if how.tile_rows == 16 else "stream", how.k_splits > 1))
+            ws_bytes = b.nts_shard_linear_workspace(**kw)
+            ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+            b.nts_shard_linear(ctx, Xd.data_ptr(), Wd.data_ptr(), Yd.data_ptr(), workspace=ws.data_ptr(),
+                               workspace_bytes=ws_bytes, hip_stream=torch.cuda.current_stream().cuda_stream, **kw)
+            torch.cuda.synchronize()
+            rows = np.unique(np.concatenate([[0, M // 2, M - 1], rng.integers(0, M, 5)]))
+            want, _ = osl.shard_linear(decode(Xm[rows]), Wf, tp, tp - 1, split)
+            got = Yd[torch.from_numpy(rows).cuda()].cpu().numpy().view(np.uint16)
+            same = got == osl.round_to_bits(want, dtype)
+            assert same.all(), (layer, tp, M, int((~same).sum()), np.argwhere(~same)[:4].tolist())
+    assert {kind for kind, _ in seen} >= {"stream", "tiled"}
+    if layer == "8b_down":
+        assert ("stream", True) in seen and ("decode", False) in seen
 
 
 @pytest.mark.parametrize("block", range(6))

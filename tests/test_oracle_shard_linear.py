@@ -76,3 +76,100 @@ def test_tolerance_covers_fp32_accumulation_in_any_order():
             acc = np.float32(acc + np.float32(xb[i]) * np.float32(wb[i]))
         assert abs(float(acc) - exact) <= tol
     assert tol < 0.02 * bound                                   # and it is not vacuous
+
+
+def test_round_to_bits_hand_values_and_ties_to_even():
+    """bfloat16 keeps 8 significant bits: integers in [256, 512) are 2 apart, so
+    257 and 259 are exact ties; float16 keeps 11: integers in [2048, 4096)."""
+    got = osl.round_to_bits(np.array([1.0, 257.0, 258.0, 259.0, -0.0, 1e40, 65520.0, 1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8]), "bf16")
+    assert got.tolist() == [0x3F80, 0x4380, 0x4381, 0x4382, 0x8000, 0x7F80, 0x4780, 0x3F80, 0x3F82]
+    got = osl.round_to_bits(np.array([1.0, 2049.0, 2051.0, 65519.0, 65520.0, 2.0 ** -25, 3 * 2.0 ** -25, -2.0 ** -14]), "f16")
+    assert got.tolist() == [0x3C00, 0x6800, 0x6802, 0x7BFF, 0x7C00, 0x0000, 0x0002, 0x8400]
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_round_to_bits_is_the_nearest_value_on_every_interval(fmt):
+    """Every finite value of the format rounds to itself; every midpoint between
+    two neighbours rounds to the one with the even pattern; points a quarter of
+    the way round to the nearer neighbour.  (Exhaustive over all positive patterns.)"""
+    decode = osl.bf16_to_f64 if fmt == "bf16" else osl.f16_to_f64
+    top = 0x7F80 if fmt == "bf16" else 0x7C00                 # pattern of +infinity
+    pats = np.arange(0, top, dtype=np.uint16)
+    vals = decode(pats)
+    assert np.array_equal(osl.round_to_bits(vals, fmt), pats)
+    assert np.array_equal(osl.round_to_bits(-vals, fmt), pats | np.uint16(0x8000))
+    lo, hi = vals[:-1], vals[1:]
+    mid = (lo + hi) / 2                                         # exact in float64
+    even = np.where(pats[:-1] % 2 == 0, pats[:-1], pats[1:])
+    assert np.array_equal(osl.round_to_bits(mid, fmt), even)
+    assert np.array_equal(osl.round_to_bits(lo + (hi - lo) / 4, fmt), pats[:-1])
+    assert np.array_equal(osl.round_to_bits(lo + 3 * (hi - lo) / 4, fmt), pats[1:])
+    assert np.array_equal(osl.ulp(lo, fmt), hi - lo)
+
+
+def test_round_to_bits_agrees_with_library_conversions():
+    """float16: NumPy's own float64 -> float16 conversion.  bfloat16: the input
+    generator's float32 -> bfloat16 routine (separate code) on float32 values."""
+    from workload.linear import f32_to_bf16_bits
+    rng = SplitMix64(8)
+    y = (rng.uniform(200000) - 0.5) * np.exp((rng.uniform(200000) - 0.5) * 40)
+    with np.errstate(over="ignore"):
+        assert np.array_equal(osl.round_to_bits(y, "f16"), y.astype(np.float16).view(np.uint16))
+    y32 = y.astype(np.float32)
+    assert np.array_equal(osl.round_to_bits(y32.astype(np.float64), "bf16"), f32_to_bf16_bits(y32))
+
+
+@pytest.mark.parametrize("k", [256, 4096, 14336])
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_tight_tolerance_admits_fp32_accumulation_and_rejects_a_dropped_product(k, fmt):
+    """fp32 accumulation simulated on the CPU in three orders (forward, backward,
+    64-wide slabs whose partial sums are then added), rounded once: always
+    inside the tight tolerance.  The same sums with ONE product left out, or with
+    a 64-wide slab left out: outside it for nearly every output, while the
+    worst-case tolerance lets most of them pass at long reductions (a dropped
+    product from 4096 terms on, a dropped slab at 14336)."""
+    from workload.linear import linear_inputs
+    n = 200
+    Xh, Wh = linear_inputs(21 + k, 1, n, k, dtype=fmt)
+    decode = osl.bf16_to_f64 if fmt == "bf16" else osl.f16_to_f64
+    X, W = decode(Xh), decode(Wh)
+    want, bound = osl.shard_linear(X, W, 1, 0, "out")
+    norm = osl.product_norm(X, W, 1, 0, "out")
+    tight = osl.tight_tolerance(want, norm, k, fmt)
+    loose = osl.tolerance(want, bound, k, out_bits=8 if fmt == "bf16" else 11)
+    assert np.all(tight < loose)
+    prod = (X.astype(np.float32) * W.astype(np.float32))          # [n][k], each product exact in fp32
+    assert np.array_equal(prod.astype(np.float64), X * W)
+
+    def rounded(sums32):
+        return decode(osl.round_to_bits(sums32.astype(np.float64), fmt))
+
+    orders = [np.cumsum(prod, axis=1, dtype=np.float32)[:, -1],
+              np.cumsum(prod[:, ::-1], axis=1, dtype=np.float32)[:, -1],
+              np.cumsum(np.cumsum(prod.reshape(n, k // 64, 64), axis=2, dtype=np.float32)[:, :, -1], axis=1,
+                        dtype=np.float32)[:, -1]]
+    for s32 in orders:
+        assert np.all(np.abs(rounded(s32) - want[0]) <= tight[0])
+    i = int(np.argmin(np.abs(np.abs(X[0]) - 1.0)))                               # an activation of typical size
+    one_less = np.cumsum(np.delete(prod, i, axis=1), axis=1, dtype=np.float32)[:, -1]   # product i dropped
+    slab_less = np.cumsum(prod[:, 64:], axis=1, dtype=np.float32)[:, -1]        # slab 0 dropped
+    big = np.abs(prod[:, i]) > 0.5 * np.abs(prod).mean()                         # outputs whose dropped product is of typical size
+    assert big.sum() > n // 3
+    caught_one = np.abs(rounded(one_less) - want[0]) > tight[0]
+    caught_slab = np.abs(rounded(slab_less) - want[0]) > tight[0]
+    assert caught_one[big].mean() > 0.9 and caught_slab.mean() > 0.95
+    if k >= 4096:                                   # the worst-case bound alone lets these mistakes through
+        assert (np.abs(rounded(one_less) - want[0]) > loose[0])[big].mean() < 0.5
+    if k == 14336:
+        assert (np.abs(rounded(slab_less) - want[0]) > loose[0]).mean() < 0.5
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_integer_inputs_are_exact_small_integers(fmt):
+    from workload.linear import linear_inputs_int
+    Xh, Wh = linear_inputs_int(4, 3, 40, 128, dtype=fmt)
+    decode = osl.bf16_to_f64 if fmt == "bf16" else osl.f16_to_f64
+    for a in (decode(Xh), decode(Wh)):
+        assert np.array_equal(a, np.rint(a)) and np.abs(a).max() == 8 and len(np.unique(a)) == 17
+    y, _ = osl.shard_linear(decode(Xh), decode(Wh), 1, 0, "out")
+    assert np.array_equal(y, np.rint(y))                        # so the exact result is an integer

@@ -46,3 +46,24 @@ def linear_inputs(seed: int, M: int, n_out: int, n_in: int, x_cols: int | None =
         n = min(step, W.size - s)
         W[s:s + n] = f32_to_bf16_bits_((rng.uniform(n) * 0.08 - 0.04).astype(np.float32))
     return X, W.reshape(n_out, n_in)
+
+
+def linear_inputs_int(seed: int, M: int, n_out: int, n_in: int, x_cols: int | None = None, dtype: str = "bf16",
+                      amax: int = 8):
+    """Integer-valued inputs: X and W uniform over the integers -amax .. amax, stored
+    as bfloat16 (or float16), which holds them exactly.  Every product is then an
+    integer of at most amax^2 and every partial sum of up to 2^24 / amax^2 of
+    them is exact in fp32 in any order, so a layer that accumulates in fp32 and
+    rounds once has exactly one correct 16-bit result."""
+    if not 1 <= amax <= 16:
+        raise ValueError("amax must be in 1..16")
+    rng = SplitMix64(seed)
+    x_cols = x_cols or n_in
+    to_bits = f32_to_bf16_bits if dtype == "bf16" else f32_to_f16_bits
+    X = to_bits((rng.integers(-amax, amax, M * x_cols)).astype(np.float32)).reshape(M, x_cols)
+    W = np.empty(n_out * n_in, dtype=np.uint16)
+    step = 1 << 22
+    for s in range(0, W.size, step):
+        n = min(step, W.size - s)
+        W[s:s + n] = to_bits(rng.integers(-amax, amax, n).astype(np.float32))
+    return X, W.reshape(n_out, n_in)
