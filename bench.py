@@ -148,38 +148,74 @@ def copy_ceiling(torch, b, ctx, stream):
 
 
 def measured_traffic(workload: str):
-    """HBM bytes per stage-kernel launch from the committed rocprofv3 --pmc summary, if any."""
+    """Bytes per stage-kernel launch that leave the L2s, from the committed rocprofv3 --pmc
+    summary of this workload (counters cannot be read inside a timing run).  The summary
+    records the hash of the kernel source it was taken with; a summary taken with another
+    version of the kernel is not reported.  Returns (bytes or None, note)."""
+    import hashlib
     path = os.path.join(ROOT, "profiles", f"nts_stage_kernel_{workload}_pmc.txt")
     try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
-        return float(m.group(1)) if m else None
+        text = open(path).read()
     except OSError:
-        return None
+        return None, "no rocprofv3 --pmc summary committed for this workload"
+    src = os.path.join(ROOT, "paper_2605_05467_amd", "csrc", "nts_move.hip")
+    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    m_sha = re.search(r"^kernel_source_sha256:\s*([0-9a-f]{64})", text, flags=re.M)
+    if not m_sha or m_sha.group(1) != sha:
+        return None, f"profiles/{os.path.basename(path)} was taken with another version of nts_move.hip"
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, flags=re.M)
+    return (float(m.group(1)) if m else None), (
+        f"FETCH_SIZE x2 + WRITE_SIZE per dispatch from profiles/{os.path.basename(path)} (same kernel source); "
+        "counted where the L2s meet the fabric, so staging bytes served by the memory-side cache are included")
 
 
 def cpu_baseline(workload: str):
-    """The oracle's unpack-after-pack, single thread, on a 16384-token instance of the same recipe
-    (about ten seconds of single-thread work)."""
+    """The CPU oracle timed on this host, on a bounded sample of the workload: the
+    whole configuration when it has at most 40960 tokens (config 3, the headline,
+    runs whole), else 40960 tokens of the same recipe (config 5); the first pair of
+    a multi-pair workload.  Two figures: the plain single-thread oracle (flatten +
+    pack + unpack over the whole sample in one call), and the same oracle with the
+    layers dealt to all host cores (layers are independent in its loops; one
+    unchanged oracle call per layer from a thread pool).  Both pools are generated
+    before the clock starts."""
     import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
     from oracle import kvmig as orc
-    from workload import fill_pool_u16, make_case
-    case = make_case(workload if workload in ("c5", "c3", "c2", "c4") else "c3", tokens=16384)[0]
+    from workload import fill_words_fast, make_case
+    name = workload if workload in ("c5", "c3", "c3b", "c3c", "c3d", "c2", "c4") else "c3"
+    full = make_case(name)[0]
+    case = full if full.T <= 40960 else make_case(name, tokens=40960)[0]
     sh = case.shape
     so, do, w = orc.route(sh.H, case.Ns, case.rs, case.Nd, case.rd)
-    src = fill_pool_u16(case.seed_src, case.pool_elems("src")).reshape(sh.L, 2, case.S_src, case.Hs, sh.D)
-    dst = fill_pool_u16(case.seed_dst, case.pool_elems("dst")).reshape(sh.L, 2, case.S_dst, case.Hd, sh.D).copy()
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32}[sh.e]
+    src = fill_words_fast(case.seed_src, 0, case.pool_bytes("src") // 8).view(dt).reshape(sh.L, 2, case.S_src, case.Hs, sh.D)
+    dst = fill_words_fast(case.seed_dst, 0, case.pool_bytes("dst") // 8).view(dt).reshape(sh.L, 2, case.S_dst, case.Hd, sh.D)
+    F = case.T * sh.L * 2
+    # (i) one thread
+    t0 = time.perf_counter()
+    sslot = orc.flatten(case.ctx_len, case.src_pages, case.p)
+    dslot = orc.flatten(case.ctx_len, case.dst_pages, case.p)
+    t_flat = time.perf_counter() - t0
+    orc.migrate(src, dst, sslot, dslot, so, do, w)
+    t_one = time.perf_counter() - t0
+    # (ii) all cores: one oracle call per layer
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    workers = max(1, min(cores, sh.L))
     reps = 3
     t0 = time.perf_counter()
     for _ in range(reps):
-        sslot = orc.flatten(case.ctx_len, case.src_pages, case.p)
-        dslot = orc.flatten(case.ctx_len, case.dst_pages, case.p)
-        orc.migrate(src, dst, sslot, dslot, so, do, w)
-    dt = (time.perf_counter() - t0) / reps
-    F = case.T * sh.L * 2
-    return {"value": F / dt, "unit": "fragments/s", "cores": 1, "kind": "oracle",
-            "sample": f"{case.T} tokens of the {workload} recipe ({F} fragments of {w * sh.D * sh.e} B, "
-                      f"{F * w * sh.D * sh.e / 2**30:.2f} GiB payload), flatten + pack + unpack, "
-                      f"{reps} passes of {dt:.2f} s each"}
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(lambda l: orc.migrate(src[l:l + 1], dst[l:l + 1], sslot, dslot, so, do, w), range(sh.L)))
+    t_all = (time.perf_counter() - t0) / reps + t_flat
+    sample = (f"{case.T} tokens of the {workload} recipe ({F} fragments of {w * sh.D * sh.e} B, "
+              f"{F * w * sh.D * sh.e / 2**30:.2f} GiB payload; "
+              + ("the whole configuration" if case.T == full.T else f"the configuration has {full.T} tokens") + ")")
+    return {"value": F / t_all, "unit": "fragments/s", "cores": workers, "kind": "oracle",
+            "sample": sample + f", flatten + pack + unpack, layers dealt to {workers} threads, "
+                               f"{reps} passes of {t_all:.2f} s each",
+            "host_cores": cores,
+            "single_thread": {"value": F / t_one, "unit": "fragments/s", "cores": 1, "kind": "oracle",
+                              "sample": sample + f", flatten + pack + unpack in one call, one pass of {t_one:.2f} s"}}
 
 
 def copy_calibration(torch):
@@ -473,7 +509,7 @@ def main():
     alg_bytes_per_launch = 4.0 * X / launches
     avg_launch_ms = kernel_ms / launches
     achieved = alg_bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
-    traffic = measured_traffic(args.workload)
+    traffic, traffic_note = measured_traffic(args.workload)
     n_pairs = len(pairs)
     del pairs, staging
     torch.cuda.empty_cache()
@@ -495,7 +531,7 @@ def main():
         "payload_GBps": X / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "kernel": "nts_stage_kernel<16> (pack chunk k || unpack chunk k-1)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_how": traffic_note,
                      "copy_ceiling": ceiling, "frac_of_copy_ceiling": achieved / ceiling,
                      "copy_ceiling_how": "plain 1 GiB linear copy through the same mover (identity slot list), "
                                          "measured in this run",
