@@ -6,6 +6,7 @@
 #include <new>
 #include <vector>
 
+#include "nts_host.h"
 #include "nts_internal.h"
 
 // Staging area of nts_run_migrate_static: device memory that exists from the moment the
@@ -148,22 +149,7 @@ int nts_free(nts_ctx *ctx)
 
 int nts_route(int H, int Ns, int rs, int Nd, int rd, int *src_head_off, int *dst_head_off, int *w)
 {
-    if (!src_head_off || !dst_head_off || !w) return NTS_EINVAL;
-    if (H <= 0 || Ns <= 0 || Nd <= 0 || H % Ns || H % Nd) return NTS_EINVAL;
-    if (rs < 0 || rs >= Ns || rd < 0 || rd >= Nd) return NTS_EINVAL;
-    const int hs = H / Ns, hd = H / Nd;
-    const int s_lo = rs * hs, s_hi = s_lo + hs;
-    const int d_lo = rd * hd, d_hi = d_lo + hd;
-    const int lo = s_lo > d_lo ? s_lo : d_lo;
-    const int hi = s_hi < d_hi ? s_hi : d_hi;
-    if (hi <= lo) {
-        *src_head_off = *dst_head_off = *w = 0;
-        return NTS_OK;
-    }
-    *src_head_off = lo - s_lo;
-    *dst_head_off = lo - d_lo;
-    *w = hi - lo;
-    return NTS_OK;
+    return nts_host_route(H, Ns, rs, Nd, rd, src_head_off, dst_head_off, w);
 }
 
 int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
@@ -171,61 +157,14 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     if (!ctx) return NTS_EINVAL;
     if (!d || !out) return fail(ctx, NTS_EINVAL, "null descriptor or output");
     *out = nullptr;
-    if (d->L <= 0 || d->L > NTS_MAX_LAYERS) return fail(ctx, NTS_EINVAL, "L outside 1..NTS_MAX_LAYERS");
-    if (d->D <= 0 || d->page_size <= 0 || d->Hs <= 0 || d->Hd <= 0)
-        return fail(ctx, NTS_EINVAL, "D, page_size, Hs and Hd must be positive");
-    if (d->D > (1 << 20) || d->Hs > (1 << 16) || d->Hd > (1 << 16))
-        return fail(ctx, NTS_EINVAL, "D above 2^20 or more than 65536 heads");
-    if (d->elem_bytes != 1 && d->elem_bytes != 2 && d->elem_bytes != 4)
-        return fail(ctx, NTS_EINVAL, "elem_bytes must be 1, 2 or 4");
-    if (d->w <= 0) return fail(ctx, NTS_EINVAL, "w must be positive");
-    if (d->src_head_off < 0 || d->src_head_off + d->w > d->Hs)
-        return fail(ctx, NTS_EINVAL, "moved heads outside the source's heads");
-    if (d->dst_head_off < 0 || d->dst_head_off + d->w > d->Hd)
-        return fail(ctx, NTS_EINVAL, "moved heads outside the destination's heads");
-    if (d->n_req < 0 || (d->n_req > 0 && !d->ctx_len)) return fail(ctx, NTS_EINVAL, "bad request list");
+    // validation, prefix sums over requests and chunk geometry: host arithmetic (nts_host.hip)
+    NtsGeometry geo;
+    const char *why = "";
+    const int grc = nts_host_plan_geometry(d, &geo, &why);
+    if (grc != NTS_OK) return fail(ctx, grc, why);
     const int p = d->page_size;
-    if (d->S_src <= 0 || d->S_dst <= 0 || d->S_src % p || d->S_dst % p)
-        return fail(ctx, NTS_EINVAL, "pool capacities must be positive multiples of the page size");
-    if (d->S_src > INT32_MAX || d->S_dst > INT32_MAX)
-        return fail(ctx, NTS_EINVAL, "pool capacity above 2^31-1 slots");
-
-    const int64_t head_bytes = int64_t(d->D) * d->elem_bytes;
-    const int64_t frag = head_bytes * d->w;
-    const int64_t src_row = head_bytes * d->Hs, dst_row = head_bytes * d->Hd;
-    const int64_t src_stride = d->src_token_stride ? d->src_token_stride : src_row;
-    const int64_t dst_stride = d->dst_token_stride ? d->dst_token_stride : dst_row;
-    if (src_stride < src_row || dst_stride < dst_row)
-        return fail(ctx, NTS_EINVAL, "token stride smaller than a token row");
-    // keeps slot * stride, the pool spans and the payload size inside 64 bits
-    if (src_stride > (int64_t(1) << 30) || dst_stride > (int64_t(1) << 30))
-        return fail(ctx, NTS_EINVAL, "token stride above 1 GiB");
-    const int64_t so = head_bytes * d->src_head_off, dof = head_bytes * d->dst_head_off;
-    int vec = 16;
-    while (vec >= 4 && (frag % vec || src_stride % vec || dst_stride % vec || so % vec || dof % vec)) vec >>= 1;
-    if (vec < 4) return fail(ctx, NTS_EINVAL, "fragment size, head offsets and strides must be multiples of 4 bytes");
-
-    // host prefix sums over requests
-    std::vector<int32_t> tok_off, pg_off;
-    try {
-        tok_off.resize(size_t(d->n_req) + 1);
-        pg_off.resize(size_t(d->n_req) + 1);
-    } catch (...) {
-        return fail(ctx, NTS_ENOMEM, "host allocation failed");
-    }
-    int64_t T = 0, NP = 0;
-    for (int r = 0; r < d->n_req; ++r) {
-        const int32_t n = d->ctx_len[r];
-        if (n < 0) return fail(ctx, NTS_EINVAL, "negative context length");
-        tok_off[r] = int32_t(T);
-        pg_off[r] = int32_t(NP);
-        T += n;
-        NP += (int64_t(n) + p - 1) / p;
-        if (T > INT32_MAX) return fail(ctx, NTS_EINVAL, "more than 2^31-1 tokens");
-    }
-    tok_off[d->n_req] = int32_t(T);
-    pg_off[d->n_req] = int32_t(NP);
-    if (T > 0 && (!d->src_pages || !d->dst_pages)) return fail(ctx, NTS_EINVAL, "null page table");
+    const int64_t T = geo.T, NP = geo.NP;
+    const std::vector<int32_t> &tok_off = geo.tok_off, &pg_off = geo.pg_off;
 
     nts_plan *pl = new (std::nothrow) nts_plan;
     if (!pl) return fail(ctx, NTS_ENOMEM, "host allocation failed");
@@ -234,25 +173,16 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     pl->Hs = d->Hs; pl->Hd = d->Hd;
     pl->src_head_off = d->src_head_off; pl->dst_head_off = d->dst_head_off; pl->w = d->w;
     pl->S_src = d->S_src; pl->S_dst = d->S_dst;
-    pl->src_stride = src_stride; pl->dst_stride = dst_stride;
+    pl->src_stride = geo.src_stride; pl->dst_stride = geo.dst_stride;
     pl->T = T;
     pl->has_runs = (d->flags & NTS_DETECT_RUNS) != 0;
-    pl->F = T * 2 * d->L;
-    pl->frag_bytes = frag;
-    if (pl->F > INT64_MAX / frag) {
-        delete pl;
-        return fail(ctx, NTS_EINVAL, "payload size does not fit 64 bits");
-    }
-    pl->X = pl->F * frag;
-    pl->vec = vec;
-    int64_t B = d->staging_bytes > 0 ? d->staging_bytes : int64_t(NTS_DEFAULT_STAGING_BYTES);
-    int64_t cf = B / frag;
-    if (cf < 1) cf = 1;
-    const int64_t cf_max = nts_max_frags_per_launch(pl) / 2;   // a stage launch packs one chunk and unpacks another
-    if (cf > cf_max) cf = cf_max > 1 ? cf_max : 1;
-    pl->chunk_frags = cf;
-    pl->chunk_bytes = cf * frag;
-    pl->n_chunks = (pl->F + cf - 1) / cf;
+    pl->F = geo.F;
+    pl->frag_bytes = geo.frag_bytes;
+    pl->X = geo.X;
+    pl->vec = geo.vec;
+    pl->chunk_frags = geo.chunk_frags;
+    pl->chunk_bytes = geo.chunk_bytes;
+    pl->n_chunks = geo.n_chunks;
 
     if (T == 0) {
         ++ctx->n_plans;
@@ -514,10 +444,7 @@ int nts_run_unpack(nts_plan *pl, const void *stream_in, void *const *dst_layer_p
 
 static int chunk_range(const nts_plan *pl, int64_t k, int64_t *q0, int64_t *n)
 {
-    if (k < 0 || k >= pl->n_chunks) return NTS_EINVAL;
-    *q0 = k * pl->chunk_frags;
-    *n = pl->F - *q0 < pl->chunk_frags ? pl->F - *q0 : pl->chunk_frags;
-    return NTS_OK;
+    return nts_host_chunk_range(pl->F, pl->chunk_frags, pl->n_chunks, k, q0, n);
 }
 
 int nts_run_pack_chunk(nts_plan *pl, const void *const *src_layer_ptrs, int64_t k, void *chunk_out, void *hip_stream)
@@ -634,12 +561,16 @@ int nts_run_migrate_static(nts_plan *pl, const void *const *src_layer_ptrs, void
 int nts_batch_staging_bytes(int n, nts_plan *const *plans, int64_t *bytes)
 {
     if (n < 0 || !bytes || (n > 0 && !plans)) return NTS_EINVAL;
-    int64_t largest = 0;
-    for (int i = 0; i < n; ++i) {
-        if (!plans[i]) return NTS_EINVAL;
-        if (plans[i]->F > 0 && plans[i]->chunk_bytes > largest) largest = plans[i]->chunk_bytes;
+    std::vector<int64_t> cb;
+    try {
+        for (int i = 0; i < n; ++i) {
+            if (!plans[i]) return NTS_EINVAL;
+            if (plans[i]->F > 0) cb.push_back(plans[i]->chunk_bytes);
+        }
+    } catch (...) {
+        return NTS_ENOMEM;
     }
-    *bytes = 2 * align_up(largest, 16);
+    *bytes = nts_host_batch_staging_bytes(cb.data(), int(cb.size()));
     return NTS_OK;
 }
 
@@ -657,11 +588,7 @@ int nts_run_migrate_batch(int n, nts_plan *const *plans, const void *const *cons
 
     // the pairs that move something, with their pointer tables
     std::vector<PipeItem> items;
-    struct Range {
-        const char *lo, *hi;
-        int is_dst;
-    };
-    std::vector<Range> ranges;
+    std::vector<NtsByteRange> ranges;
     try {
         items.reserve(size_t(n));
         for (int i = 0; i < n; ++i) {
@@ -674,8 +601,9 @@ int nts_run_migrate_batch(int n, nts_plan *const *plans, const void *const *cons
             if (rc != NTS_OK) return rc;
             const int64_t src_span = pl->S_src * pl->src_stride, dst_span = pl->S_dst * pl->dst_stride;
             for (int k = 0; k < 2 * pl->L; ++k) {
-                ranges.push_back({it.stab.p[k], it.stab.p[k] + src_span, 0});
-                ranges.push_back({it.dtab.p[k], it.dtab.p[k] + dst_span, 1});
+                const uintptr_t sl = reinterpret_cast<uintptr_t>(it.stab.p[k]), dl = reinterpret_cast<uintptr_t>(it.dtab.p[k]);
+                ranges.push_back({sl, sl + uintptr_t(src_span), 0});
+                ranges.push_back({dl, dl + uintptr_t(dst_span), 1});
             }
         }
     } catch (...) {
@@ -688,17 +616,10 @@ int nts_run_migrate_batch(int n, nts_plan *const *plans, const void *const *cons
     (void)nts_batch_staging_bytes(n, plans, &staging_bytes);
     char *stg = static_cast<char *>(staging);
 
-    // No destination range may meet a source range of ANY plan, nor the staging area: sort
-    // by start and sweep, remembering how far the sources and the destinations seen so far reach.
-    std::sort(ranges.begin(), ranges.end(), [](const Range &x, const Range &y) { return x.lo < y.lo; });
-    const char *reach[2] = {nullptr, nullptr};
-    for (const Range &r : ranges) {
-        if (reach[1 - r.is_dst] && r.lo < reach[1 - r.is_dst])
-            return fail(ctx, NTS_EALIAS, "a destination pool of the batch overlaps a source pool of the batch");
-        if (overlaps(r.lo, r.hi - r.lo, stg, staging_bytes))
-            return fail(ctx, NTS_EALIAS, "staging area overlaps a pool");
-        if (!reach[r.is_dst] || r.hi > reach[r.is_dst]) reach[r.is_dst] = r.hi;
-    }
+    // No destination range may meet a source range of ANY plan, nor the staging area.
+    const char *why = "";
+    const int arc = nts_host_alias_sweep(ranges, reinterpret_cast<uintptr_t>(stg), staging_bytes, &why);
+    if (arc != NTS_OK) return fail(ctx, arc, why);
     // the second buffer starts 16-byte aligned whatever the plans' vector widths
     return run_pipeline(ctx, items.data(), items.size(), stg, staging_bytes / 2, static_cast<hipStream_t>(hip_stream));
 }

@@ -26,6 +26,7 @@
 // fit the memory-side cache (256 MiB) are then served from it, where
 // non-temporal accesses go round it.  Measured on the 88 GiB migration with
 // 2 x 64 MiB staging: 57.7 ms against 67.2 ms (one box, same run).
+#include "nts_host.h"
 #include "nts_internal.h"
 
 namespace {
@@ -171,9 +172,8 @@ uint64_t magic_of(uint32_t d) { return d > 1 ? UINT64_MAX / d + 1 : 0; }
 // Largest fragment count one launch may cover: lanes = vectors < 2^31.
 int64_t nts_max_frags_per_launch(const nts_plan *pl)
 {
-    const int64_t V = pl->frag_bytes / pl->vec;
-    int64_t n = ((int64_t(1) << 31) - kThreads) / V;
-    return n < 1 ? 1 : n;
+    static_assert(kThreads == kNtsLanes, "the host geometry assumes single-wavefront workgroups");
+    return nts_host_max_frags_per_launch(pl->frag_bytes, pl->vec);
 }
 
 void nts_make_job(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int64_t n_frag, char *linear,
