@@ -73,6 +73,9 @@ def parse_args():
     ap.add_argument("--tp", default="1,2,4,8", help="with --linear: which TP levels")
     ap.add_argument("--batches", default="1,16,64,256,1024,4096",
                     help="with --linear: the batch sizes M to time")
+    ap.add_argument("--tune", action="store_true",
+                    help="with --linear: let nts_shard_linear_tune pick each shape's configuration by timing the "
+                         "candidates once, and report the default's time beside the tuned one")
     ap.add_argument("--library", action="store_true",
                     help="with --linear: also time torch.matmul (hipBLASLt) on the same shards, graph-replayed alike")
     ap.add_argument("--planner", action="store_true",
@@ -320,23 +323,39 @@ def linear_bench(args, torch, b):
                                        hip_stream=torch.cuda.current_stream().cuda_stream, **kw)
 
                 n_launch = copies * 2 if M <= 256 else max(4, copies)
-                launch(0)
-                torch.cuda.synchronize()
-                graph = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(graph):
-                    for i in range(n_launch):
-                        launch(i)
-                graph.replay()
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                ts = []
-                for _ in range(5):
-                    e0.record()
-                    graph.replay()
-                    e1.record()
+
+                def replay_us():
+                    launch(0)
                     torch.cuda.synchronize()
-                    ts.append(e0.elapsed_time(e1) * 1e3 / n_launch)
-                us = sorted(ts)[2]
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph):
+                        for i in range(n_launch):
+                            launch(i)
+                    graph.replay()
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    ts = []
+                    for _ in range(5):
+                        e0.record()
+                        graph.replay()
+                        e1.record()
+                        torch.cuda.synchronize()
+                        ts.append(e0.elapsed_time(e1) * 1e3 / n_launch)
+                    del graph
+                    return sorted(ts)[2]
+
+                us = replay_us()
+                default_us = None
+                if args.tune:
+                    default_us, default_how = us, how
+                    wsb = max(wsb, 8 * M * nn * 4)         # room for up to eight K splits
+                    ws = torch.empty(wsb + 16, dtype=torch.uint8, device="cuda")
+                    how = b.nts_shard_linear_tune(ctx, X.data_ptr(), [W[i].data_ptr() for i in range(copies)], Y.data_ptr(), workspace=ws.data_ptr(),
+                                                  workspace_bytes=wsb,
+                                                  hip_stream=torch.cuda.current_stream().cuda_stream, **kw)
+                    torch.cuda.synchronize()
+                    us = replay_us()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 lib_us = None
                 if args.library:
                     # the same shard through torch.matmul (hipBLASLt), replayed from a graph in the same way
@@ -371,9 +390,12 @@ def linear_bench(args, torch, b):
                                   "kernel": "tiled" if how.tiled else "decode" if how.tile_rows == 16 else "stream",
                                   "tile": "%dx%d" % (how.tile_rows, how.tile_cols), "k_splits": how.k_splits,
                                   "roofline": roof,
+                                  **({"default_us_per_call": default_us,
+                                      "default_kernel": "tiled" if default_how.tiled else "decode" if default_how.tile_rows == 16 else "stream",
+                                      "default_tile": "%dx%d" % (default_how.tile_rows, default_how.tile_cols),
+                                      "default_k_splits": default_how.k_splits} if default_us else {}),
                                   **({"library_us_per_call": lib_us, "vs_library": us / lib_us} if lib_us else {})}),
                       flush=True)
-                del graph
         del W
     b.nts_free(ctx)
     if not args.no_cpu_baseline:

@@ -340,6 +340,42 @@ int nts_shard_linear_launch(const nts_linear_desc *d, nts_linear_launch *out);
 int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, const void *W_full,
                      void *Y, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Opt-in tuning of nts_shard_linear for one shape.  The default choice of kernel
+ * and launch shape comes from a cost estimate fitted on one MI355X and is good to
+ * about 10 %; this call instead runs, on the caller's operands, every
+ * configuration whose estimate is within 1.4 x of the best (at most eight, the
+ * default first; those that need more workspace than given are skipped), times
+ * each with HIP events and remembers the fastest in the context; a configuration
+ * other than the default has to beat it by 3 %.
+ *   W_list, n_weights  host array of device pointers to full weight matrices of
+ *        the descriptor's shape: typically the same layer of every transformer
+ *        block.  A timed pass runs the layer once on each, back to back (one
+ *        untimed launch, then the shortest of five passes).  In service weights
+ *        come from HBM every time; when the given matrices' shards together are
+ *        smaller than 512 MiB the call allocates a buffer of that size, sweeps
+ *        it before every pass and frees it.  More matrices give a measurement
+ *        closer to service; one is enough.
+ * Later nts_shard_linear calls on this context with the same M, shard shape
+ * (rows and reduction length after the TP cut) and element format use the
+ * remembered configuration whenever their workspace is large enough for it, and
+ * the default otherwise; strides, rank and split axis do not enter the key.
+ * Other arguments as nts_shard_linear; on return Y holds the layer's result on
+ * W_list[0].  *picked (may be NULL) receives the chosen configuration.  The call
+ * synchronises with hip_stream several times: it is meant for set-up, not for a
+ * captured or latency-critical path.  Every configuration is held to the same
+ * parity bar, so tuning changes speed only.  nts_shard_linear_tuned reports the
+ * remembered configuration for a descriptor (NTS_ERANGE when there is none);
+ * nts_shard_linear_workspace stays the size the default needs: give
+ * nts_shard_linear_tune the largest workspace you are willing to keep (M * rows
+ * * 4 bytes per K split, at most 32 splits).
+ * Errors: as nts_shard_linear; NTS_ENOMEM when the flush buffer cannot be allocated.
+ */
+int nts_shard_linear_tune(nts_ctx *ctx, const nts_linear_desc *d, const void *X,
+                          const void *const *W_list, int n_weights, void *Y, void *workspace,
+                          size_t workspace_bytes, void *hip_stream, nts_linear_launch *picked);
+int nts_shard_linear_tuned(const nts_ctx *ctx, const nts_linear_desc *d, nts_linear_launch *out);
+
 /* ------------------------------------------------------------------------
  * Goodput-efficiency planner (paper Sec. 3.3.1; host only, no GPU needed).
  * For SLO tier k, thp[i] / thd[i] are the profiled maximum prefill / decode

@@ -46,6 +46,7 @@ EXPORTS = (
     "nts_run_migrate", "nts_run_migrate_batch", "nts_run_migrate_direct", "nts_run_memcpy_baseline",
     "nts_batch_staging_bytes", "nts_run_migrate_static",
     "nts_shard_linear", "nts_shard_linear_workspace", "nts_shard_linear_launch",
+    "nts_shard_linear_tune", "nts_shard_linear_tuned",
     "nts_balanced_block", "nts_goodput_efficiency", "nts_plan_cluster",
 )
 NTS_TP_LEVELS = 4
@@ -126,6 +127,9 @@ _lib.nts_run_memcpy_baseline.argtypes = [_vp, _vp, _vp, _i, _vp, ctypes.POINTER(
 _lib.nts_shard_linear_workspace.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(ctypes.c_size_t)]
 _lib.nts_shard_linear_launch.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(nts_linear_launch)]
 _lib.nts_shard_linear.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.nts_shard_linear_tune.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), _vp, _vp, _i, _vp, _vp, ctypes.c_size_t, _vp,
+                                       ctypes.POINTER(nts_linear_launch)]
+_lib.nts_shard_linear_tuned.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), ctypes.POINTER(nts_linear_launch)]
 _d = ctypes.c_double
 _lib.nts_balanced_block.argtypes = [_d, _d, _i, _pi, _pi]
 _lib.nts_goodput_efficiency.argtypes = [_d, _i, _d, _i, _i, _i, _d, ctypes.POINTER(_d)]
@@ -328,6 +332,31 @@ def nts_shard_linear(ctx: int, X: int, W_full: int, Y: int, *, M: int, n_out: in
                      workspace: int = 0, workspace_bytes: int = 0, hip_stream: int = 0) -> None:
     d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy, dtype)
     _check(_lib.nts_shard_linear(ctx, ctypes.byref(d), X, W_full, Y, workspace, workspace_bytes, hip_stream), ctx)
+
+
+def nts_shard_linear_tune(ctx: int, X: int, W_list, Y: int, *, M: int, n_out: int, n_in: int, tp: int,
+                          rank: int, split: int, ldx: int = 0, ldw: int = 0, ldy: int = 0, dtype: int = 0,
+                          workspace: int = 0, workspace_bytes: int = 0, hip_stream: int = 0) -> "nts_linear_launch":
+    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy, dtype)
+    out = nts_linear_launch()
+    ws = [W_list] if isinstance(W_list, int) else list(W_list)
+    tab = (ctypes.c_void_p * len(ws))(*[int(w) for w in ws])
+    _check(_lib.nts_shard_linear_tune(ctx, ctypes.byref(d), X, tab, len(ws), Y, workspace, workspace_bytes, hip_stream,
+                                      ctypes.byref(out)), ctx)
+    return out
+
+
+def nts_shard_linear_tuned(ctx: int, *, M: int, n_out: int, n_in: int, tp: int, rank: int, split: int,
+                           ldx: int = 0, ldw: int = 0, ldy: int = 0, dtype: int = 0) -> Optional["nts_linear_launch"]:
+    """The configuration remembered for this shape, or None when it has not been tuned."""
+    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy, dtype)
+    out = nts_linear_launch()
+    st = _lib.nts_shard_linear_tuned(ctx, ctypes.byref(d), ctypes.byref(out))
+    if st == NTS_ERANGE:
+        return None
+    if st != NTS_OK:
+        raise NtsError(st, "nts_shard_linear_tuned")
+    return out
 
 
 def nts_balanced_block(thp: float, thd: float, max_inst: int = 8) -> Tuple[int, int]:

@@ -754,10 +754,8 @@ int nts_shard_linear_workspace(const nts_linear_desc *d, size_t *bytes)
     return NTS_OK;
 }
 
-int nts_shard_linear_launch(const nts_linear_desc *d, nts_linear_launch *out)
+static void describe_launch(const LinearGeom &g, nts_linear_launch *out)
 {
-    LinearGeom g;
-    if (!out || linear_geom(d, &g) != NTS_OK) return NTS_EINVAL;
     *out = nts_linear_launch{};
     out->tiled = g.tiled ? 1 : 0;
     const bool decode = !g.tiled && g.cfg.ks > 0;
@@ -766,6 +764,63 @@ int nts_shard_linear_launch(const nts_linear_desc *d, nts_linear_launch *out)
     out->k_splits = g.cfg.splits;
     out->slabs_ahead = g.tiled ? 2 : g.cfg.nsets - 1;
     out->k_waves = decode ? g.cfg.ks : 1;
+}
+
+static size_t linear_workspace_need(const LinearGeom &g)
+{
+    return g.cfg.splits > 1 ? size_t(g.cfg.splits) * g.M * g.Nn * sizeof(float) : 0;
+}
+
+// Replace the default configuration of `g` by the one nts_shard_linear_tune remembered for this
+// shape, when there is one and the workspace at hand is large enough for it.
+static void apply_tuned(const nts_ctx *ctx, int dtype, size_t workspace_bytes, bool have_workspace, LinearGeom *g)
+{
+    const auto it = ctx->tuned_linear.find(std::make_tuple(g->M, g->Nn, g->K, dtype));
+    if (it == ctx->tuned_linear.end()) return;
+    const nts_ctx::TunedLinear &t = it->second;
+    LinearGeom h = *g;
+    h.tiled = t.tiled;
+    h.cfg.mt = t.mt; h.cfg.cw = t.cw; h.cfg.rt = t.rt; h.cfg.nsets = t.nsets; h.cfg.splits = t.splits; h.cfg.ks = t.ks;
+    const size_t need = linear_workspace_need(h);
+    if (need && (!have_workspace || workspace_bytes < need)) return;
+    *g = h;
+}
+
+static hipError_t launch_linear(const LinearGeom &g, int dtype, const void *X, const void *W_full, void *Y,
+                                void *workspace, hipStream_t st)
+{
+    const uint16_t *A = static_cast<const uint16_t *>(W_full) + g.a_off;
+    if (!g.tiled)
+        return nts_launch_linear_stream(static_cast<const uint16_t *>(X), g.ldx, A, g.lda, static_cast<uint16_t *>(Y),
+                                        g.ldy, static_cast<float *>(workspace), g.cfg, g.M, g.Nn, g.K,
+                                        dtype == NTS_F16, st);
+    return nts_launch_linear_tiled(static_cast<const uint16_t *>(X), g.ldx, A, g.lda, static_cast<uint16_t *>(Y),
+                                   g.ldy, g.M, g.Nn, g.K, dtype == NTS_F16, st);
+}
+
+int nts_shard_linear_launch(const nts_linear_desc *d, nts_linear_launch *out)
+{
+    LinearGeom g;
+    if (!out || linear_geom(d, &g) != NTS_OK) return NTS_EINVAL;
+    describe_launch(g, out);
+    return NTS_OK;
+}
+
+int nts_shard_linear_tuned(const nts_ctx *ctx, const nts_linear_desc *d, nts_linear_launch *out)
+{
+    LinearGeom g;
+    if (!ctx || !out || linear_geom(d, &g) != NTS_OK) return NTS_EINVAL;
+    if (ctx->tuned_linear.find(std::make_tuple(g.M, g.Nn, g.K, int(d->dtype))) == ctx->tuned_linear.end()) return NTS_ERANGE;
+    apply_tuned(ctx, d->dtype, SIZE_MAX, true, &g);
+    describe_launch(g, out);
+    return NTS_OK;
+}
+
+static int check_linear_operands(nts_ctx *ctx, const void *X, const void *W_full, const void *Y)
+{
+    if (!X || !W_full || !Y) return fail(ctx, NTS_EINVAL, "null operand");
+    if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W_full) | reinterpret_cast<uintptr_t>(Y)) % 16)
+        return fail(ctx, NTS_EINVAL, "operands must be 16-byte aligned");
     return NTS_OK;
 }
 
@@ -775,23 +830,105 @@ int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, cons
     if (!ctx) return NTS_EINVAL;
     LinearGeom g;
     if (linear_geom(d, &g) != NTS_OK) return fail(ctx, NTS_EINVAL, "bad linear-layer descriptor");
-    if (!X || !W_full || !Y) return fail(ctx, NTS_EINVAL, "null operand");
-    if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W_full) | reinterpret_cast<uintptr_t>(Y)) % 16)
-        return fail(ctx, NTS_EINVAL, "operands must be 16-byte aligned");
-    const size_t need = g.cfg.splits > 1 ? size_t(g.cfg.splits) * g.M * g.Nn * sizeof(float) : 0;
-    if (need && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16))
+    const int rc = check_linear_operands(ctx, X, W_full, Y);
+    if (rc != NTS_OK) return rc;
+    const bool ws_ok = workspace && reinterpret_cast<uintptr_t>(workspace) % 16 == 0;
+    apply_tuned(ctx, d->dtype, workspace_bytes, ws_ok, &g);
+    const size_t need = linear_workspace_need(g);
+    if (need && (!ws_ok || workspace_bytes < need))
         return fail(ctx, NTS_EINVAL, "workspace missing, misaligned or too small");
     DeviceGuard guard(ctx->device);
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const uint16_t *A = static_cast<const uint16_t *>(W_full) + g.a_off;
-    if (!g.tiled) {
-        NTS_HIP(ctx, nts_launch_linear_stream(static_cast<const uint16_t *>(X), g.ldx, A, g.lda,
-                                              static_cast<uint16_t *>(Y), g.ldy, static_cast<float *>(workspace),
-                                              g.cfg, g.M, g.Nn, g.K, d->dtype == NTS_F16, st));
-        return NTS_OK;
+    NTS_HIP(ctx, launch_linear(g, d->dtype, X, W_full, Y, workspace, static_cast<hipStream_t>(hip_stream)));
+    return NTS_OK;
+}
+
+int nts_shard_linear_tune(nts_ctx *ctx, const nts_linear_desc *d, const void *X, const void *const *W_list, int n_weights,
+                          void *Y, void *workspace, size_t workspace_bytes, void *hip_stream, nts_linear_launch *picked)
+{
+    if (!ctx) return NTS_EINVAL;
+    LinearGeom g;
+    if (linear_geom(d, &g) != NTS_OK) return fail(ctx, NTS_EINVAL, "bad linear-layer descriptor");
+    if (!W_list || n_weights < 1 || n_weights > 4096) return fail(ctx, NTS_EINVAL, "need 1..4096 weight matrices");
+    for (int i = 0; i < n_weights; ++i) {
+        const int rc = check_linear_operands(ctx, X, W_list[i], Y);
+        if (rc != NTS_OK) return rc;
     }
-    NTS_HIP(ctx, nts_launch_linear_tiled(static_cast<const uint16_t *>(X), g.ldx, A, g.lda,
-                                         static_cast<uint16_t *>(Y), g.ldy, g.M, g.Nn, g.K, d->dtype == NTS_F16, st));
+    const bool ws_ok = workspace && reinterpret_cast<uintptr_t>(workspace) % 16 == 0;
+    if (linear_workspace_need(g) && (!ws_ok || workspace_bytes < linear_workspace_need(g)))
+        return fail(ctx, NTS_EINVAL, "workspace missing, misaligned or too small");
+    constexpr int kMaxCand = 8, kReps = 5;
+    NtsLinearCand cand[kMaxCand];
+    const int n = nts_linear_candidates(g.M, g.Nn, g.K, 1.4, cand, kMaxCand);
+    DeviceGuard guard(ctx->device);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    // In service a layer's weights come from HBM every time (a model is far larger than the caches).  A
+    // timed pass runs the layer once on each of the given matrices, back to back; when those together are
+    // smaller than twice the memory-side cache, a sweep over a buffer of that size comes before each pass.
+    constexpr size_t kFlushBytes = size_t(512) << 20;
+    const bool need_flush = double(n_weights) * g.Nn * g.K * 2. < double(kFlushBytes);
+    void *flush = nullptr;
+    if (need_flush && hipMalloc(&flush, kFlushBytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, NTS_ENOMEM, "no room for the 512 MiB cache-flush buffer of the tuning run");
+    }
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    int best = -1;
+    float best_ms = 0.f, default_ms = 0.f;
+    for (int i = 0; i < n && e == hipSuccess; ++i) {
+        LinearGeom h = g;
+        h.tiled = cand[i].tiled;
+        h.cfg = cand[i].cfg;
+        const size_t need = linear_workspace_need(h);
+        if (need && (!ws_ok || workspace_bytes < need)) continue;       // does not fit the caller's workspace
+        // one untimed launch, then the shortest of kReps timed passes
+        if ((e = launch_linear(h, d->dtype, X, W_list[0], Y, workspace, st)) != hipSuccess) break;
+        float ms_min = 0.f;
+        for (int r = 0; r < kReps && e == hipSuccess; ++r) {
+            if (flush && (e = hipMemsetAsync(flush, r, kFlushBytes, st)) != hipSuccess) break;
+            if ((e = hipEventRecord(e0, st)) != hipSuccess) break;
+            for (int k = 0; k < n_weights && e == hipSuccess; ++k)
+                e = launch_linear(h, d->dtype, X, W_list[k], Y, workspace, st);
+            if (e != hipSuccess) break;
+            if ((e = hipEventRecord(e1, st)) != hipSuccess) break;
+            if ((e = hipEventSynchronize(e1)) != hipSuccess) break;
+            float ms = 0.f;
+            if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) break;
+            if (r == 0 || ms < ms_min) ms_min = ms;
+        }
+        if (e != hipSuccess) break;
+        if (i == 0) default_ms = ms_min;                 // candidate 0 is the default configuration
+        // another configuration has to beat the default by 3 % (timing noise), and the best so far at all
+        const bool ok = i == 0 || default_ms == 0.f || ms_min < 0.97f * default_ms;
+        if (ok && (best < 0 || ms_min < best_ms)) {
+            best = i;
+            best_ms = ms_min;
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipStreamSynchronize(st);
+    if (flush) (void)hipFree(flush);
+    if (e != hipSuccess) return fail_hip(ctx, e, "nts_shard_linear_tune");
+    if (best < 0) return fail(ctx, NTS_EINVAL, "no configuration fits the workspace");
+    // leave Y holding the result of the chosen configuration on the first matrix
+    {
+        LinearGeom h = g;
+        h.tiled = cand[best].tiled;
+        h.cfg = cand[best].cfg;
+        NTS_HIP(ctx, launch_linear(h, d->dtype, X, W_list[0], Y, workspace, st));
+        if (picked) describe_launch(h, picked);
+    }
+    nts_ctx::TunedLinear t;
+    t.tiled = cand[best].tiled;
+    t.mt = cand[best].cfg.mt; t.cw = cand[best].cfg.cw; t.rt = cand[best].cfg.rt; t.nsets = cand[best].cfg.nsets;
+    t.splits = cand[best].cfg.splits; t.ks = cand[best].cfg.ks;
+    try {
+        ctx->tuned_linear[std::make_tuple(g.M, g.Nn, g.K, int(d->dtype))] = t;
+    } catch (...) {
+        return fail(ctx, NTS_ENOMEM, "host allocation failed");
+    }
     return NTS_OK;
 }
 

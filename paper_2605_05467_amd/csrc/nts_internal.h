@@ -4,7 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <map>
 #include <string>
+#include <tuple>
 #include <vector>
 
 #include "nitsum_kvmig.h"
@@ -32,6 +34,12 @@ struct nts_ctx {
     uint64_t free_count = 0;
     int n_plans = 0;
     std::string err;
+    // configurations nts_shard_linear_tune found fastest, by (M, shard rows, reduction length, format)
+    struct TunedLinear {
+        bool tiled;
+        int mt, cw, rt, nsets, splits, ks;
+    };
+    std::map<std::tuple<int, int, int, int>, TunedLinear> tuned_linear;
 };
 
 struct nts_plan {
@@ -123,6 +131,13 @@ struct NtsStreamCfg {
 };
 NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K);
 bool nts_linear_use_tiled(int M, int Nn);
+// one way of running a problem: the tiled kernel, or the streaming / decode kernel with `cfg`
+struct NtsLinearCand {
+    bool tiled = false;
+    NtsStreamCfg cfg;
+    double est_us = 0.;
+};
+int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out, int max_out);
 hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda, uint16_t *Y,
                                     int64_t ldy, float *part, const NtsStreamCfg &c, int M, int Nn, int K,
                                     bool f16, hipStream_t st);

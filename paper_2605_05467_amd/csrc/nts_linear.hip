@@ -848,6 +848,120 @@ bool nts_linear_use_tiled(int M, int Nn)
     return M > 256 && tiles >= 160;
 }
 
+// Every configuration that may be fastest for a problem, for nts_shard_linear_tune to time: the
+// streaming kernel's variants with each K split that is valid for them, the decode kernel's
+// (row blocks, wavefronts per K range, K split) combinations for M <= 16, and the tiled kernel
+// for M > 256.  Each gets the same estimate nts_linear_stream_config uses (the tiled kernel:
+// 11 us per round of tiles plus 1.57 us per slab); the list is cut to those within `slack` of
+// the smallest estimate, sorted by estimate, at most `max_out`.  The configuration
+// nts_shard_linear uses by default is always first.
+int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out, int max_out)
+{
+    std::vector<NtsLinearCand> all;
+    const int rows = M < 256 ? M : 256;
+    const int mt_min = rows <= 32 ? 1 : rows <= 64 ? 2 : rows <= 96 ? 3 : rows <= 128 ? 4 : rows <= 192 ? 6 : 8;
+    const int n_slabs = K / kStrK;
+    const double out_elems = double(M) * Nn;
+    const double hbm_us = double(Nn) * K * 2. / 6.1e6;
+    NtsLinearCand def;
+    def.tiled = nts_linear_use_tiled(M, Nn);
+    def.cfg = nts_linear_stream_config(M, Nn, K);
+    if (def.tiled) def.cfg.splits = 1;
+    def.est_us = 0.;
+    for (const StreamVariant &v : kStreamVariants) {
+        if (v.mt > mt_min || (v.mt == 1 && mt_min > 1)) continue;
+        const int tiles_m = (M + 32 * v.mt - 1) / (32 * v.mt);
+        const int lds_fit = (160 * 1024) / (3 * 32 * v.mt * kStrPitch);
+        const int per_cu = 4 / v.cw < lds_fit ? 4 / v.cw : lds_fit;
+        const int64_t wgs = int64_t(tiles_m) * ((Nn + 32 * v.cw - 1) / (32 * v.cw));
+        for (int splits = 1; splits <= 32 && splits <= (n_slabs >= 4 ? n_slabs / 4 : 1); ++splits) {
+            const int sps = (n_slabs + splits - 1) / splits;
+            if ((n_slabs + sps - 1) / sps != splits) continue;
+            if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) break;
+            const int64_t total = wgs * splits;
+            const int64_t rounds = (total + 255) / 256, seq_rounds = (total + 256 * per_cu - 1) / (256 * per_cu);
+            const double cu_us = double(rounds) * sps * v.slab_us;
+            double t = 2.5 + (cu_us > hbm_us ? cu_us : hbm_us) + v.round_us * double(seq_rounds) +
+                       0.7 * double(rounds - seq_rounds);
+            if (splits > 1) t += 2.5 + out_elems * splits * 8. / 4.0e6;
+            NtsLinearCand c;
+            c.tiled = false;
+            c.cfg.mt = v.mt;
+            c.cfg.cw = v.cw;
+            c.cfg.rt = 1;
+            c.cfg.splits = splits;
+            c.cfg.ks = 0;
+            c.cfg.nsets = v.mt <= 4 ? 4 : 3;
+            if (v.cw == 1 && v.mt == 1) c.cfg.nsets = 8;
+            c.est_us = t;
+            all.push_back(c);
+        }
+    }
+    if (M <= 16) {
+        const double bytes = double(Nn) * K * 2.;
+        for (int rb = 1; rb <= 2; ++rb)
+            for (int ks = 2 * rb; ks <= 4; ks *= 2)
+                for (int splits = 1; splits <= 4; splits *= 2) {
+                    const int sps = (n_slabs + splits - 1) / splits;
+                    if ((n_slabs + sps - 1) / sps != splits) continue;
+                    const int spw = sps / ks;
+                    if (spw < 4) continue;
+                    if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) continue;
+                    const int64_t wgs = int64_t((Nn + 16 * rb - 1) / (16 * rb)) * splits;
+                    const int per_cu = 12 / ks;
+                    const int64_t rounds = (wgs + 256 * per_cu - 1) / (256 * per_cu);
+                    const int64_t wg_cu = (wgs + 255) / 256;
+                    double rate = 10. * double(ks * (wg_cu < per_cu ? wg_cu : per_cu));
+                    const double cap = 26. - 0.4 * M;
+                    if (rate > cap) rate = cap;
+                    if (wg_cu > 1 && rate > 22.) rate = 22.;
+                    double stream_us = bytes / double(wgs) * double(wg_cu) / (rate * 1e3);
+                    if (stream_us < hbm_us) stream_us = hbm_us;
+                    double t = 2.5 + 1.0 * double(rounds) + stream_us + 0.08 * M + (spw < 16 ? 0.25 * (16 - spw) : 0.);
+                    if (splits > 1) t += 2.5 + out_elems * splits * 8. / 4.0e6;
+                    NtsLinearCand c;
+                    c.tiled = false;
+                    c.cfg.mt = 1;
+                    c.cfg.cw = 4;
+                    c.cfg.ks = ks;
+                    c.cfg.rt = rb;
+                    c.cfg.splits = splits;
+                    c.cfg.nsets = rb == 1 ? 8 : 6;
+                    c.est_us = t;
+                    all.push_back(c);
+                }
+    }
+    if (M > 256) {
+        const int64_t tiles = int64_t((M + kTileM - 1) / kTileM) * ((Nn + kTileN - 1) / kTileN);
+        NtsLinearCand c;
+        c.tiled = true;
+        c.cfg = def.cfg;
+        c.cfg.splits = 1;
+        c.est_us = 2.5 + double((tiles + 255) / 256) * (11. + 1.57 * n_slabs);
+        all.push_back(c);
+    }
+    auto same = [](const NtsLinearCand &a, const NtsLinearCand &b) {
+        if (a.tiled != b.tiled) return false;
+        if (a.tiled) return true;
+        return a.cfg.mt == b.cfg.mt && a.cfg.cw == b.cfg.cw && a.cfg.rt == b.cfg.rt && a.cfg.splits == b.cfg.splits &&
+               a.cfg.ks == b.cfg.ks && a.cfg.nsets == b.cfg.nsets;
+    };
+    double best = 0.;
+    for (const NtsLinearCand &c : all) {
+        if (same(c, def)) def.est_us = c.est_us;
+        if (best == 0. || c.est_us < best) best = c.est_us;
+    }
+    std::sort(all.begin(), all.end(), [](const NtsLinearCand &a, const NtsLinearCand &b) { return a.est_us < b.est_us; });
+    int n = 0;
+    if (max_out > 0) out[n++] = def;
+    for (const NtsLinearCand &c : all) {
+        if (n >= max_out) break;
+        if (same(c, def) || c.est_us > slack * best) continue;
+        out[n++] = c;
+    }
+    return n;
+}
+
 hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
                                    uint16_t *Y, int64_t ldy, int M, int Nn, int K, bool f16, hipStream_t st)
 {

@@ -284,3 +284,66 @@ def test_random_shapes(env, block):
         n_out, n_in = (nn * tp, k) if split == "out" else (nn, k * tp)
         run_case(env, M, n_out, n_in, tp, u(0, tp - 1), split, seed=block * 100 + i,
                  dtype=("bf16", "f16")[u(0, 1)])
+
+
+@pytest.mark.parametrize("M,n_out,n_in,tp,split", [(16, 6144, 4096, 1, "out"), (16, 4096, 14336, 2, "in"), (1, 4096, 14336, 1, "in"),
+                                                   (64, 4096, 4096, 4, "in"), (300, 2048, 2048, 1, "out"),
+                                                   (1024, 6144, 4096, 1, "out")])
+def test_tuned_configuration_keeps_parity(env, M, n_out, n_in, tp, split):
+    """nts_shard_linear_tune times the candidate configurations and remembers the
+    fastest; whichever it picks, the layer's result must stay inside both tolerances
+    on random inputs and bit-exact on integer inputs, the tuning call itself must
+    leave the right result in Y, and later calls must use what was remembered
+    (and fall back to the default when their workspace is too small for it)."""
+    torch, b, _ = env
+    ctx = b.nts_init(0)                                   # a context of its own: tuning is remembered per context
+    try:
+        sp = b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN
+        k = n_in if split == "out" else n_in // tp
+        nn = n_out // tp if split == "out" else n_out
+        kw = dict(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=tp - 1, split=sp)
+        assert b.nts_shard_linear_tuned(ctx, **kw) is None
+        ws = torch.empty(8 * M * nn * 4 + 16, dtype=torch.uint8, device="cuda")      # room for up to eight K splits
+        st = torch.cuda.current_stream().cuda_stream
+        for exact in (False, True):
+            Xh, Wh = (linear_inputs_int if exact else linear_inputs)(60 + M, M, n_out, n_in, x_cols=k)
+            Xd = torch.from_numpy(Xh.view(np.int16)).cuda()
+            Wd = torch.from_numpy(Wh.view(np.int16)).cuda()
+            X64, W64 = osl.bf16_to_f64(Xh), osl.bf16_to_f64(Wh)
+            want, bound = osl.shard_linear(X64, W64, tp, tp - 1, split)
+            tight = osl.tight_tolerance(want, osl.product_norm(X64, W64, tp, tp - 1, split), k, "bf16")
+
+            def check(Yd, tag):
+                got_bits = Yd.cpu().numpy().view(np.uint16)
+                if exact:
+                    assert np.array_equal(got_bits, osl.round_to_bits(want, "bf16")), tag
+                else:
+                    assert np.all(np.abs(osl.bf16_to_f64(got_bits) - want) <= tight), tag
+
+            Yd = torch.full((M, nn), 12345, dtype=torch.int16, device="cuda")
+            if not exact:
+                more = [Wd.clone() for _ in range(M % 3)]               # one, two or three weight matrices
+                picked = b.nts_shard_linear_tune(ctx, Xd.data_ptr(), [Wd.data_ptr()] + [w.data_ptr() for w in more],
+                                                 Yd.data_ptr(), workspace=ws.data_ptr(),
+                                                 workspace_bytes=ws.numel() - 16, hip_stream=st, **kw)
+                torch.cuda.synchronize()
+                check(Yd, "result left by the tuning call")
+                kept = b.nts_shard_linear_tuned(ctx, **kw)
+                assert kept is not None
+                assert [getattr(kept, f) for f in ("tiled", "tile_rows", "tile_cols", "k_splits", "k_waves")] == \
+                       [getattr(picked, f) for f in ("tiled", "tile_rows", "tile_cols", "k_splits", "k_waves")]
+                assert picked.k_splits <= 8
+                Yd.fill_(12345)
+            b.nts_shard_linear(ctx, Xd.data_ptr(), Wd.data_ptr(), Yd.data_ptr(), workspace=ws.data_ptr(),
+                               workspace_bytes=ws.numel() - 16, hip_stream=st, **kw)
+            torch.cuda.synchronize()
+            check(Yd, "tuned configuration")
+            # with only the default's workspace the call still works (tuned if it fits, default otherwise)
+            need = b.nts_shard_linear_workspace(**kw)
+            Yd.fill_(12345)
+            b.nts_shard_linear(ctx, Xd.data_ptr(), Wd.data_ptr(), Yd.data_ptr(), workspace=ws.data_ptr() if need else 0,
+                               workspace_bytes=need, hip_stream=st, **kw)
+            torch.cuda.synchronize()
+            check(Yd, "default-sized workspace")
+    finally:
+        b.nts_free(ctx)
