@@ -180,7 +180,11 @@ int nts_run_pack(nts_plan *plan, const void *const *src_layer_ptrs, void *stream
                  void *hip_stream);
 
 /* Pack chunk k only, into a device buffer of chunk_bytes (the last chunk may
- * be shorter).  This is what a sender calls once per staging buffer. */
+ * be shorter).  This is what a sender calls once per staging buffer.  The chunk
+ * calls treat their buffer as staging that is consumed (or was produced) moments
+ * later: ordinary, cache-allocating accesses on that side, where nts_run_pack /
+ * nts_run_unpack stream past the caches (pack -> unpack through two 64 MiB
+ * buffers on one GPU: 6.3 against 5.4 TB/s). */
 int nts_run_pack_chunk(nts_plan *plan, const void *const *src_layer_ptrs, int64_t k,
                        void *chunk_out, void *hip_stream);
 

@@ -407,7 +407,7 @@ int nts_plan_runs(nts_plan *pl, int32_t *run_start_host)
 }
 
 static int run_range(nts_plan *pl, NtsMoveMode mode, const void *const *layer_ptrs, int64_t q0,
-                     int64_t n_frag, void *linear, void *hip_stream)
+                     int64_t n_frag, void *linear, bool staging, void *hip_stream)
 {
     if (!pl) return NTS_EINVAL;
     nts_ctx *ctx = pl->ctx;
@@ -425,7 +425,7 @@ static int run_range(nts_plan *pl, NtsMoveMode mode, const void *const *layer_pt
     char *lin = static_cast<char *>(linear);
     for (int64_t done = 0; done < n_frag; done += lim) {
         const int64_t n = n_frag - done < lim ? n_frag - done : lim;
-        NTS_HIP(ctx, nts_launch_move(mode, pl, q0 + done, n, tab, lin + done * pl->frag_bytes, st));
+        NTS_HIP(ctx, nts_launch_move(mode, pl, q0 + done, n, tab, lin + done * pl->frag_bytes, staging, st));
     }
     return NTS_OK;
 }
@@ -433,13 +433,13 @@ static int run_range(nts_plan *pl, NtsMoveMode mode, const void *const *layer_pt
 int nts_run_pack(nts_plan *pl, const void *const *src_layer_ptrs, void *stream_out, void *hip_stream)
 {
     if (!pl) return NTS_EINVAL;
-    return run_range(pl, NTS_MOVE_PACK, src_layer_ptrs, 0, pl->F, stream_out, hip_stream);
+    return run_range(pl, NTS_MOVE_PACK, src_layer_ptrs, 0, pl->F, stream_out, false, hip_stream);
 }
 
 int nts_run_unpack(nts_plan *pl, const void *stream_in, void *const *dst_layer_ptrs, void *hip_stream)
 {
     if (!pl) return NTS_EINVAL;
-    return run_range(pl, NTS_MOVE_UNPACK, dst_layer_ptrs, 0, pl->F, const_cast<void *>(stream_in), hip_stream);
+    return run_range(pl, NTS_MOVE_UNPACK, dst_layer_ptrs, 0, pl->F, const_cast<void *>(stream_in), false, hip_stream);
 }
 
 static int chunk_range(const nts_plan *pl, int64_t k, int64_t *q0, int64_t *n)
@@ -452,7 +452,7 @@ int nts_run_pack_chunk(nts_plan *pl, const void *const *src_layer_ptrs, int64_t 
     if (!pl) return NTS_EINVAL;
     int64_t q0, n;
     if (chunk_range(pl, k, &q0, &n) != NTS_OK) return fail(pl->ctx, NTS_EINVAL, "chunk index out of range");
-    return run_range(pl, NTS_MOVE_PACK, src_layer_ptrs, q0, n, chunk_out, hip_stream);
+    return run_range(pl, NTS_MOVE_PACK, src_layer_ptrs, q0, n, chunk_out, true, hip_stream);
 }
 
 int nts_run_unpack_chunk(nts_plan *pl, const void *chunk_in, int64_t k, void *const *dst_layer_ptrs, void *hip_stream)
@@ -460,7 +460,7 @@ int nts_run_unpack_chunk(nts_plan *pl, const void *chunk_in, int64_t k, void *co
     if (!pl) return NTS_EINVAL;
     int64_t q0, n;
     if (chunk_range(pl, k, &q0, &n) != NTS_OK) return fail(pl->ctx, NTS_EINVAL, "chunk index out of range");
-    return run_range(pl, NTS_MOVE_UNPACK, dst_layer_ptrs, q0, n, const_cast<void *>(chunk_in), hip_stream);
+    return run_range(pl, NTS_MOVE_UNPACK, dst_layer_ptrs, q0, n, const_cast<void *>(chunk_in), true, hip_stream);
 }
 
 static int check_pools(nts_plan *pl, const void *const *src_layer_ptrs, void *const *dst_layer_ptrs,

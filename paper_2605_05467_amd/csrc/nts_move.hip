@@ -119,10 +119,12 @@ __device__ __forceinline__ void move_vector(const NtsMoveJob &job, const NtsLaye
     }
 }
 
-template <int BYTES, bool PACK>
+// LIN_NT = false: the stream side is a staging buffer that is read back (or was written) a
+// moment ago, so it is accessed like the stage kernel's buffers, through the memory-side cache
+template <int BYTES, bool PACK, bool LIN_NT>
 __global__ __launch_bounds__(kThreads) void nts_move_kernel(NtsMoveJob job, NtsLayerTab tab)
 {
-    move_vector<BYTES, PACK, true>(job, tab, blockIdx.x, threadIdx.x);
+    move_vector<BYTES, PACK, LIN_NT>(job, tab, blockIdx.x, threadIdx.x);
 }
 
 // Workgroups take turns in runs of kStageRun: a run packs (job a), the next run unpacks
@@ -220,21 +222,25 @@ void nts_make_job(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int64_t n_fr
 }
 
 hipError_t nts_launch_move(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int64_t n_frag,
-                           const NtsLayerTab &tab, char *linear, hipStream_t st)
+                           const NtsLayerTab &tab, char *linear, bool linear_is_staging, hipStream_t st)
 {
     if (n_frag <= 0) return hipSuccess;
     NtsMoveJob job;
     nts_make_job(mode, pl, q0, n_frag, linear, &job);
     const dim3 grid((job.n_vec + kThreads - 1) / kThreads), block(kThreads);
-#define NTS_LAUNCH(B, P) hipLaunchKernelGGL((nts_move_kernel<B, P>), grid, block, 0, st, job, tab)
+#define NTS_LAUNCH(B, P)                                                                              \
+    {                                                                                                 \
+        if (linear_is_staging) hipLaunchKernelGGL((nts_move_kernel<B, P, false>), grid, block, 0, st, job, tab); \
+        else hipLaunchKernelGGL((nts_move_kernel<B, P, true>), grid, block, 0, st, job, tab);         \
+    }
     if (mode == NTS_MOVE_PACK) {
-        if (pl->vec == 16) NTS_LAUNCH(16, true);
-        else if (pl->vec == 8) NTS_LAUNCH(8, true);
-        else NTS_LAUNCH(4, true);
+        if (pl->vec == 16) NTS_LAUNCH(16, true)
+        else if (pl->vec == 8) NTS_LAUNCH(8, true)
+        else NTS_LAUNCH(4, true)
     } else {
-        if (pl->vec == 16) NTS_LAUNCH(16, false);
-        else if (pl->vec == 8) NTS_LAUNCH(8, false);
-        else NTS_LAUNCH(4, false);
+        if (pl->vec == 16) NTS_LAUNCH(16, false)
+        else if (pl->vec == 8) NTS_LAUNCH(8, false)
+        else NTS_LAUNCH(4, false)
     }
 #undef NTS_LAUNCH
     return hipGetLastError();
@@ -248,9 +254,9 @@ hipError_t nts_launch_stage(const nts_plan *ppl, int64_t pack_q0, int64_t pack_n
     if (!has_a && !has_b) return hipSuccess;
     if (has_a && has_b && ppl->vec != upl->vec) {
         // two plans whose vector widths differ cannot share the kernel instance
-        const hipError_t e = nts_launch_move(NTS_MOVE_UNPACK, upl, unpack_q0, unpack_n, dtab, unpack_buf, st);
+        const hipError_t e = nts_launch_move(NTS_MOVE_UNPACK, upl, unpack_q0, unpack_n, dtab, unpack_buf, true, st);
         if (e != hipSuccess) return e;
-        return nts_launch_move(NTS_MOVE_PACK, ppl, pack_q0, pack_n, stab, pack_buf, st);
+        return nts_launch_move(NTS_MOVE_PACK, ppl, pack_q0, pack_n, stab, pack_buf, true, st);
     }
     NtsMoveJob a = {}, b = {};   // an absent side is a job of zero vectors
     if (has_a) nts_make_job(NTS_MOVE_PACK, ppl, pack_q0, pack_n, pack_buf, &a);
