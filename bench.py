@@ -286,6 +286,14 @@ def strategies(args, torch, b, wdev, make_case):
                 lambda: b.nts_run_migrate(plan, pr.sp, pr.dp, staging.data_ptr(), stream), 10)
             res["direct_pool_to_pool"] = timed(lambda: b.nts_run_migrate_direct(plan, pr.sp, pr.dp, stream), 10)
             b.nts_plan_free(plan)
+            # the same kernel walking the tokens in ascending destination-slot order (plan flag)
+            plan = b.nts_plan_create(ctx, L=sh.L, D=sh.D, elem_bytes=sh.e, page_size=case.p, Hs=case.Hs, Hd=case.Hd,
+                                     src_head_off=so, dst_head_off=do, w=w, S_src=case.S_src, S_dst=case.S_dst,
+                                     ctx_len=case.ctx_len, src_pages=case.src_pages, dst_pages=case.dst_pages,
+                                     staging_bytes=staging_bytes,
+                                     flags=b.NTS_VALIDATE_UNIQUE_DST | b.NTS_ORDER_BY_DST)
+            res["direct_pool_to_pool_dst_order"] = timed(lambda: b.nts_run_migrate_direct(plan, pr.sp, pr.dp, stream), 10)
+            b.nts_plan_free(plan)
             del whole, pr
             print(json.dumps(res), flush=True)
     del staging

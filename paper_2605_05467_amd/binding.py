@@ -36,6 +36,7 @@ NTS_OK, NTS_EINVAL, NTS_ERANGE, NTS_EDUP, NTS_EALIAS, NTS_ENOMEM, NTS_EHIP = 0, 
 NTS_MAX_LAYERS = 96
 NTS_VALIDATE_UNIQUE_DST = 1
 NTS_DETECT_RUNS = 2
+NTS_ORDER_BY_DST = 4
 NTS_DEFAULT_STAGING_BYTES = 64 << 20
 NTS_STATIC_STAGING_BYTES = 32 << 20
 

@@ -204,7 +204,12 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
     const int64_t b_bitmap = align_up(bitmap_words * 4, 256);
     const bool want_runs = (d->flags & NTS_DETECT_RUNS) != 0;
     const int64_t b_runs = want_runs ? align_up((T + 1) * 4, 256) + align_up(((T + 255) / 256) * 4, 256) : 0;
-    const int64_t total = 2 * b_slots + b_meta + b_bitmap + 256 + b_runs;
+    // NTS_ORDER_BY_DST: per-word popcount prefix | per-block counts | both slot lists in rank order
+    const bool want_order = (d->flags & NTS_ORDER_BY_DST) != 0;
+    const int64_t b_wprefix = want_order ? align_up(bitmap_words * 4, 256) : 0;
+    const int64_t b_wblocks = want_order ? align_up(((bitmap_words + 255) / 256) * 4, 256) : 0;
+    const int64_t b_order = b_wprefix + b_wblocks + (want_order ? 2 * b_slots : 0);
+    const int64_t total = 2 * b_slots + b_meta + b_bitmap + 256 + b_runs + b_order;
 
     hipError_t e = hipSuccess;
     if (ctx->h_pinned_bytes < size_t(b_meta + 256)) {
@@ -298,6 +303,16 @@ int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out)
             int32_t *d_counts = pl->d_run_start + align_up((T + 1) * 4, 256) / 4;
             if ((e = nts_launch_detect_runs(pl->d_sslot, pl->d_dslot, uint32_t(T), d_counts, pl->d_run_start,
                                             d_err + 2, st)) != hipSuccess) break;
+        }
+        if (want_order) {
+            char *at = reinterpret_cast<char *>(d_err) + 256 + b_runs;
+            int32_t *d_wprefix = reinterpret_cast<int32_t *>(at);
+            int32_t *d_wblocks = reinterpret_cast<int32_t *>(at + b_wprefix);
+            pl->d_sslot_by_dst = reinterpret_cast<int32_t *>(at + b_wprefix + b_wblocks);
+            pl->d_dslot_by_dst = reinterpret_cast<int32_t *>(at + b_wprefix + b_wblocks + b_slots);
+            if ((e = nts_launch_rank_by_dst(pl->d_sslot, pl->d_dslot, uint32_t(T), reinterpret_cast<const uint32_t *>(d_bm),
+                                            uint32_t(bitmap_words), d_wprefix, d_wblocks, pl->d_sslot_by_dst,
+                                            pl->d_dslot_by_dst, st)) != hipSuccess) break;
         }
         if ((e = hipMemcpyAsync(const_cast<int32_t *>(h_err), d_err, 12, hipMemcpyDeviceToHost, st)) != hipSuccess) break;
         e = hipStreamSynchronize(st);

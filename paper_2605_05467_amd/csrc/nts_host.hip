@@ -49,6 +49,8 @@ int nts_host_plan_geometry(const nts_desc *d, NtsGeometry *g, const char **why)
     if (d->src_head_off < 0 || d->src_head_off > d->Hs - d->w) NTS_BAD("moved heads outside the source's heads");
     if (d->dst_head_off < 0 || d->dst_head_off > d->Hd - d->w) NTS_BAD("moved heads outside the destination's heads");
     if (d->n_req < 0 || (d->n_req > 0 && !d->ctx_len)) NTS_BAD("bad request list");
+    if ((d->flags & NTS_ORDER_BY_DST) && !(d->flags & NTS_VALIDATE_UNIQUE_DST))
+        NTS_BAD("NTS_ORDER_BY_DST needs NTS_VALIDATE_UNIQUE_DST (the ranking relies on distinct destination slots)");
     const int p = d->page_size;
     if (d->S_src <= 0 || d->S_dst <= 0 || d->S_src % p || d->S_dst % p)
         NTS_BAD("pool capacities must be positive multiples of the page size");

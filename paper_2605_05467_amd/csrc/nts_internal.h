@@ -54,6 +54,9 @@ struct nts_plan {
     size_t d_block_bytes = 0;
     int32_t *d_sslot = nullptr;
     int32_t *d_dslot = nullptr;
+    // both slot lists in ascending destination-slot order (plan flag NTS_ORDER_BY_DST), else null
+    int32_t *d_sslot_by_dst = nullptr;
+    int32_t *d_dslot_by_dst = nullptr;
     // run list (plan flag NTS_DETECT_RUNS): n_runs + 1 token indices, the last one T
     bool has_runs = false;
     int32_t *d_run_start = nullptr;
@@ -120,6 +123,12 @@ hipError_t nts_launch_flatten(const int32_t *d_tok_off, const int32_t *d_pg_off,
 hipError_t nts_launch_detect_runs(const int32_t *d_sslot, const int32_t *d_dslot, uint32_t T,
                                   int32_t *d_block_count, int32_t *d_run_start, int32_t *d_n_runs,
                                   hipStream_t st);
+
+// tokens in ascending destination-slot order (plan flag NTS_ORDER_BY_DST): both slot lists scattered
+// into rank order; d_word_prefix: n_words entries, d_block_count: ceil(n_words / 256) entries of scratch
+hipError_t nts_launch_rank_by_dst(const int32_t *d_sslot, const int32_t *d_dslot, uint32_t T,
+                                  const uint32_t *d_bitmap, uint32_t n_words, int32_t *d_word_prefix,
+                                  int32_t *d_block_count, int32_t *d_ss_sorted, int32_t *d_ds_sorted, hipStream_t st);
 
 // nts_linear.hip: Y[M][Nn] = X[M][K] . A[Nn][K]^T, bf16 or f16 in, fp32 accumulate, same format out
 struct NtsStreamCfg {

@@ -277,6 +277,10 @@ hipError_t nts_launch_direct(const nts_plan *pl, int64_t q0, int64_t n_frag, con
     NtsMoveJob a, b;
     nts_make_job(NTS_MOVE_PACK, pl, q0, n_frag, nullptr, &a);
     nts_make_job(NTS_MOVE_UNPACK, pl, q0, n_frag, nullptr, &b);
+    if (pl->d_sslot_by_dst) {                // walk the tokens in ascending destination-slot order
+        a.slots = pl->d_sslot_by_dst;
+        b.slots = pl->d_dslot_by_dst;
+    }
     const dim3 grid((a.n_vec + kThreads - 1) / kThreads), block(kThreads);
     if (pl->vec == 16) hipLaunchKernelGGL((nts_direct_kernel<16>), grid, block, 0, st, a, stab, b, dtab);
     else if (pl->vec == 8) hipLaunchKernelGGL((nts_direct_kernel<8>), grid, block, 0, st, a, stab, b, dtab);

@@ -62,19 +62,16 @@ __global__ __launch_bounds__(256) void nts_run_count_kernel(const int32_t *__res
     if (threadIdx.x == 0) block_count[blockIdx.x] = n;
 }
 
-// one workgroup: block_count[0..nb) -> exclusive offsets in place; the total goes to *n_runs and
-// the closing entry run_start[total] = T is written here
-__global__ __launch_bounds__(256) void nts_run_scan_kernel(int32_t *__restrict__ block_count, uint32_t nb,
-                                                           uint32_t T, int32_t *__restrict__ run_start,
-                                                           int32_t *__restrict__ n_runs)
+// One 256-thread workgroup: counts[0..n) -> exclusive prefix sums in place; returns the total
+// (to every thread).  `part` and `carry` are the caller's shared memory.
+__device__ __forceinline__ int32_t nts_scan_in_place(int32_t *__restrict__ counts, uint32_t n, int32_t *part,
+                                                     int32_t *carry)
 {
-    __shared__ int32_t part[256];
-    __shared__ int32_t carry;
-    if (threadIdx.x == 0) carry = 0;
+    if (threadIdx.x == 0) *carry = 0;
     __syncthreads();
-    for (uint32_t base = 0; base < nb; base += 256u) {
+    for (uint32_t base = 0; base < n; base += 256u) {
         const uint32_t i = base + threadIdx.x;
-        const int32_t v = i < nb ? block_count[i] : 0;
+        const int32_t v = i < n ? counts[i] : 0;
         part[threadIdx.x] = v;
         __syncthreads();
         for (int d = 1; d < 256; d <<= 1) {                 // inclusive scan of the 256 entries
@@ -83,15 +80,27 @@ __global__ __launch_bounds__(256) void nts_run_scan_kernel(int32_t *__restrict__
             part[threadIdx.x] += add;
             __syncthreads();
         }
-        const int32_t before = carry;
-        if (i < nb) block_count[i] = before + part[threadIdx.x] - v;
+        const int32_t before = *carry;
+        if (i < n) counts[i] = before + part[threadIdx.x] - v;
         __syncthreads();
-        if (threadIdx.x == 255) carry = before + part[255];
+        if (threadIdx.x == 255) *carry = before + part[255];
         __syncthreads();
     }
+    return *carry;
+}
+
+// one workgroup: block_count[0..nb) -> exclusive offsets in place; the total goes to *n_runs and
+// the closing entry run_start[total] = T is written here
+__global__ __launch_bounds__(256) void nts_run_scan_kernel(int32_t *__restrict__ block_count, uint32_t nb,
+                                                           uint32_t T, int32_t *__restrict__ run_start,
+                                                           int32_t *__restrict__ n_runs)
+{
+    __shared__ int32_t part[256];
+    __shared__ int32_t carry;
+    const int32_t total = nts_scan_in_place(block_count, nb, part, &carry);
     if (threadIdx.x == 0) {
-        run_start[carry] = int32_t(T);
-        *n_runs = carry;
+        run_start[total] = int32_t(T);
+        *n_runs = total;
     }
 }
 
@@ -113,7 +122,72 @@ __global__ __launch_bounds__(256) void nts_run_scatter_kernel(const int32_t *__r
     run_start[at] = int32_t(j);
 }
 
+// Tokens ranked by destination slot (plan flag NTS_ORDER_BY_DST).  Destination slots are
+// distinct and the uniqueness bitmap has exactly their bits set, so the rank of a token among
+// the destination slots is the number of set bits below its own: popcounts per bitmap word,
+// scanned within blocks of 256 words (this kernel), across blocks (one workgroup), and a
+// scatter of both slot lists into rank order.  The pool-to-pool kernel walks the tokens in
+// that order: its writes then sweep the destination pool upwards instead of landing at random.
+__global__ __launch_bounds__(256) void nts_rank_count_kernel(const uint32_t *__restrict__ bitmap, uint32_t n_words,
+                                                             int32_t *__restrict__ word_prefix,
+                                                             int32_t *__restrict__ block_count)
+{
+    __shared__ int32_t part[256];
+    const uint32_t w = blockIdx.x * 256u + threadIdx.x;
+    const int32_t v = w < n_words ? __popc(bitmap[w]) : 0;
+    part[threadIdx.x] = v;
+    __syncthreads();
+    for (int d = 1; d < 256; d <<= 1) {                     // inclusive scan of the 256 popcounts
+        const int32_t add = int(threadIdx.x) >= d ? part[threadIdx.x - d] : 0;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    if (w < n_words) word_prefix[w] = part[threadIdx.x] - v;   // set bits before word w inside its block
+    if (threadIdx.x == 255) block_count[blockIdx.x] = part[255];
+}
+
+// one workgroup: block_count[0..nb) -> exclusive offsets in place
+__global__ __launch_bounds__(256) void nts_rank_scan_kernel(int32_t *__restrict__ block_count, uint32_t nb)
+{
+    __shared__ int32_t part[256];
+    __shared__ int32_t carry;
+    (void)nts_scan_in_place(block_count, nb, part, &carry);
+}
+
+__global__ __launch_bounds__(256) void nts_rank_scatter_kernel(const int32_t *__restrict__ ss,
+                                                               const int32_t *__restrict__ ds, uint32_t T,
+                                                               const uint32_t *__restrict__ bitmap,
+                                                               const int32_t *__restrict__ word_prefix,
+                                                               const int32_t *__restrict__ block_off,
+                                                               int32_t *__restrict__ ss_sorted,
+                                                               int32_t *__restrict__ ds_sorted)
+{
+    const uint32_t j = blockIdx.x * 256u + threadIdx.x;
+    if (j >= T) return;
+    const uint32_t d = uint32_t(ds[j]), w = d >> 5;
+    const uint32_t rank = uint32_t(block_off[w >> 8]) + uint32_t(word_prefix[w]) +
+                          uint32_t(__popc(bitmap[w] & ((1u << (d & 31u)) - 1u)));
+    if (rank < T) {                                         // always, for distinct slots inside the pool
+        ss_sorted[rank] = ss[j];
+        ds_sorted[rank] = int32_t(d);
+    }
+}
+
 }  // namespace
+
+hipError_t nts_launch_rank_by_dst(const int32_t *d_sslot, const int32_t *d_dslot, uint32_t T,
+                                  const uint32_t *d_bitmap, uint32_t n_words, int32_t *d_word_prefix,
+                                  int32_t *d_block_count, int32_t *d_ss_sorted, int32_t *d_ds_sorted, hipStream_t st)
+{
+    if (T == 0 || n_words == 0) return hipSuccess;
+    const uint32_t nb = (n_words + 255u) / 256u;
+    hipLaunchKernelGGL(nts_rank_count_kernel, dim3(nb), dim3(256), 0, st, d_bitmap, n_words, d_word_prefix, d_block_count);
+    hipLaunchKernelGGL(nts_rank_scan_kernel, dim3(1), dim3(256), 0, st, d_block_count, nb);
+    hipLaunchKernelGGL(nts_rank_scatter_kernel, dim3((T + 255u) / 256u), dim3(256), 0, st, d_sslot, d_dslot, T, d_bitmap,
+                       d_word_prefix, d_block_count, d_ss_sorted, d_ds_sorted);
+    return hipGetLastError();
+}
 
 hipError_t nts_launch_detect_runs(const int32_t *d_sslot, const int32_t *d_dslot, uint32_t T,
                                   int32_t *d_block_count, int32_t *d_run_start, int32_t *d_n_runs,

@@ -129,6 +129,21 @@ def test_config3_headline_and_companions(env, name):
         check_properties(env, case, src_d, dst_d, info)
         check_samples(env, case, dst_d, es, ed)
         compare_every_layer(case, dst_d, es, ed)
+        # the pool-to-pool kernel on the same pools, in token order and in destination order
+        from gpu_util import make_plan, slab_bytes
+        torch, b, wdev, ctx, _ = env
+        sh = case.shape
+        sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+        dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
+        for flags in (b.NTS_VALIDATE_UNIQUE_DST, b.NTS_VALIDATE_UNIQUE_DST | b.NTS_ORDER_BY_DST):
+            wdev.fill_tensor(dst_d, case.seed_dst)
+            plan = make_plan(b, ctx, case, staging_bytes=STAGING, flags=flags)
+            try:
+                b.nts_run_migrate_direct(plan, sp, dp, torch.cuda.current_stream().cuda_stream)
+                torch.cuda.synchronize()
+            finally:
+                b.nts_plan_free(plan)
+            compare_every_layer(case, dst_d, es, ed, label=f"{case.name} pool-to-pool flags={flags}", direct=True)
         del src_d, dst_d
 
 
@@ -176,7 +191,8 @@ def test_config5_roofline_size(env):
     sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
     dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
     from gpu_util import make_plan
-    plan = make_plan(b, ctx, case, staging_bytes=STAGING)
+    # ... walking the tokens in ascending destination-slot order (the flag changes no result)
+    plan = make_plan(b, ctx, case, staging_bytes=STAGING, flags=b.NTS_VALIDATE_UNIQUE_DST | b.NTS_ORDER_BY_DST)
     try:
         b.nts_run_migrate_direct(plan, sp, dp, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()

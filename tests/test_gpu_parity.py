@@ -287,6 +287,46 @@ def test_error_paths_and_empty_plans(b, ctx, torch):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_direct_in_destination_order_matches_oracle_on_drawn_cases(b, ctx, torch, seed):
+    """NTS_ORDER_BY_DST: the pool-to-pool kernel walks the tokens in ascending
+    destination-slot order.  The result must not change: drawn geometries (1-, 2- and
+    4-byte elements, pages of 1 to 16 tokens, padded rows, 2L separate allocations,
+    shared source pages, pools whose slot count is no multiple of 32 or of 256 x 32),
+    every pool byte compared, and every other run call of such a plan unaffected."""
+    from gpu_util import draw_case, random_case_host, random_case_plan_args
+    c = draw_case(500 + seed)
+    h = random_case_host(c, b.nts_route(c["H"], c["Ns"], c["rs"], c["Nd"], c["rd"]))
+    args = random_case_plan_args(b, c, h)
+    with pytest.raises(b.NtsError) as ei:                    # the ranking needs validated, distinct slots
+        b.nts_plan_create(ctx, **{**args, "flags": b.NTS_ORDER_BY_DST})
+    assert ei.value.status == b.NTS_EINVAL
+    args["flags"] = b.NTS_VALIDATE_UNIQUE_DST | b.NTS_ORDER_BY_DST | (b.NTS_DETECT_RUNS if seed % 2 else 0)
+    plan = b.nts_plan_create(ctx, **args)
+    st = torch.cuda.current_stream().cuda_stream
+    try:
+        s, d = b.nts_plan_slots(plan)
+        assert np.array_equal(s, h["sslot"]) and np.array_equal(d, h["dslot"])      # the lists themselves keep token order
+        src_d = [torch.from_numpy(a).cuda() for a in h["src_arr"]]
+        for call in ("direct", "staged"):
+            dst_d = [torch.from_numpy(a).cuda() for a in h["dst_arr"]]
+            stab, dtab = [t.data_ptr() for t in src_d], [t.data_ptr() for t in dst_d]
+            if call == "direct":
+                b.nts_run_migrate_direct(plan, stab, dtab, st)
+            else:
+                info = b.nts_plan_info(plan)
+                staging = torch.empty(2 * info.chunk_bytes, dtype=torch.uint8, device="cuda")
+                b.nts_run_migrate(plan, stab, dtab, staging.data_ptr(), st)
+            torch.cuda.synchronize()
+            L, S_d, st_d, row_d = h["L"], h["S_d"], h["st_d"], h["row_d"]
+            for i in range(2 * L):
+                got = dst_d[i].cpu().numpy().reshape(S_d, st_d)
+                assert got[:, :row_d].tobytes() == h["want"].reshape(2 * L, S_d, -1)[i].tobytes(), (call, seed, i)
+                assert np.array_equal(got[:, row_d:], h["dst_arr"][i].reshape(S_d, st_d)[:, row_d:]), (call, seed, i)
+    finally:
+        b.nts_plan_free(plan)
+
+
 @pytest.mark.parametrize("idx", [0, 1, 3, 4])
 def test_direct_and_memcpy_baseline_match_oracle(b, ctx, torch, idx):
     """The pool-to-pool kernel and the per-fragment memcpy baseline produce the
