@@ -110,7 +110,7 @@ class Pair:
         return b.nts_plan_create(ctx, L=sh.L, D=sh.D, elem_bytes=sh.e, page_size=c.p, Hs=c.Hs, Hd=c.Hd,
                                  src_head_off=so, dst_head_off=do, w=w, S_src=c.S_src, S_dst=c.S_dst,
                                  ctx_len=c.ctx_len, src_pages=c.src_pages, dst_pages=c.dst_pages,
-                                 staging_bytes=staging_bytes, flags=b.NTS_VALIDATE_UNIQUE_DST)
+                                 staging_bytes=staging_bytes, flags=b.NTS_VALIDATE_UNIQUE_DST | b.NTS_ORDER_BY_DST)
 
     def step(self, ctx, staging, staging_bytes, hip_stream, ev=None):
         """route + plan + migrate + plan_free; returns the plan's info."""

@@ -64,7 +64,8 @@ enum {
     NTS_MAX_LAYERS = 96,          /* 2*L base pointers travel as kernel arguments */
     NTS_VALIDATE_UNIQUE_DST = 1u, /* plan flag: check destination slots are distinct */
     NTS_DETECT_RUNS = 2u,         /* plan flag: also find the runs of neighbouring slots */
-    NTS_ORDER_BY_DST = 4u,        /* plan flag: also rank the tokens by destination slot, for nts_run_migrate_direct */
+    NTS_ORDER_BY_DST = 4u,        /* plan flag: also rank the tokens by destination slot; nts_run_migrate[_batch, _static]
+                                     and nts_run_migrate_direct then move them in that order */
     NTS_DEFAULT_STAGING_BYTES = 64 << 20,
     NTS_STATIC_STAGING_BYTES = 32 << 20   /* both buffers of nts_run_migrate_static together */
 };
@@ -209,8 +210,10 @@ int nts_run_unpack_chunk(nts_plan *plan, const void *chunk_in, int64_t k,
  * from its producer to its consumer.  The kernels access the pools with
  * non-temporal loads and stores and the staging buffers with ordinary ones, so
  * that buffers which together fit the GPU's memory-side cache (256 MiB on
- * MI355X) are served from it.  NTS_EALIAS if a source layer range overlaps a
- * destination layer range or the staging area.
+ * MI355X) are served from it.  The order of the fragments inside the staging
+ * buffers is not defined (see NTS_ORDER_BY_DST); only the destination pool is
+ * an output.  NTS_EALIAS if a source layer range overlaps a destination layer
+ * range or the staging area.
  */
 int nts_run_migrate(nts_plan *plan, const void *const *src_layer_ptrs,
                     void *const *dst_layer_ptrs, void *staging, void *hip_stream);
@@ -271,8 +274,10 @@ int nts_batch_staging_bytes(int n, nts_plan *const *plans, int64_t *bytes);
  * (which needs NTS_VALIDATE_UNIQUE_DST: the plan ranks the tokens by counting the
  * bits of the uniqueness bitmap below each destination slot) lets this call walk
  * them in ascending destination-slot order, so that its writes sweep the pool
- * upwards: 10-14 % faster on fully fragmented pools.  No other call looks at the
- * flag.  NTS_EALIAS if the pools overlap.
+ * upwards: 10-14 % faster on fully fragmented pools.  nts_run_migrate and its
+ * batch and static variants use the same order inside their staging buffers,
+ * whose contents are no output (1-2 %); pack, unpack and the chunk calls, whose
+ * stream is an output, never look at the flag.  NTS_EALIAS if the pools overlap.
  */
 int nts_run_migrate_direct(nts_plan *plan, const void *const *src_layer_ptrs,
                            void *const *dst_layer_ptrs, void *hip_stream);

@@ -261,6 +261,10 @@ hipError_t nts_launch_stage(const nts_plan *ppl, int64_t pack_q0, int64_t pack_n
     NtsMoveJob a = {}, b = {};   // an absent side is a job of zero vectors
     if (has_a) nts_make_job(NTS_MOVE_PACK, ppl, pack_q0, pack_n, pack_buf, &a);
     if (has_b) nts_make_job(NTS_MOVE_UNPACK, upl, unpack_q0, unpack_n, unpack_buf, &b);
+    // A plan ranked by destination slot is packed and unpacked in that order: what lies in the
+    // staging buffers is no output of the pipeline, and the unpack half then writes upwards.
+    if (has_a && ppl->d_sslot_by_dst) a.slots = ppl->d_sslot_by_dst;
+    if (has_b && upl->d_dslot_by_dst) b.slots = upl->d_dslot_by_dst;
     const int vec = has_a ? ppl->vec : upl->vec;
     const uint32_t wg_a = (a.n_vec + kThreads - 1) / kThreads, wg_b = (b.n_vec + kThreads - 1) / kThreads;
     const dim3 grid(wg_a + wg_b), block(kThreads);

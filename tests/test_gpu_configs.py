@@ -45,7 +45,8 @@ def migrate_on_gpu(env, case, src_d=None):
     dst_d = device_pool(case, "dst")
     sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
     dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
-    plan = make_plan(b, ctx, case, staging_bytes=STAGING)
+    # bench.py's plan flags: validated destination slots, tokens moved in destination order
+    plan = make_plan(b, ctx, case, staging_bytes=STAGING, flags=b.NTS_VALIDATE_UNIQUE_DST | b.NTS_ORDER_BY_DST)
     try:
         info = b.nts_plan_info(plan)
         s, d = b.nts_plan_slots(plan)
