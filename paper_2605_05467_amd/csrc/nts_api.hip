@@ -566,6 +566,8 @@ int nts_run_migrate_static(nts_plan *pl, const void *const *src_layer_ptrs, void
 {
     if (!pl) return NTS_EINVAL;
     nts_ctx *ctx = pl->ctx;
+    if (!src_layer_ptrs || !dst_layer_ptrs) return fail(ctx, NTS_EINVAL, "null layer pointer table");
+    if (pl->F == 0) return NTS_OK;                    // nothing to move, whatever the chunk geometry
     if (2 * pl->chunk_bytes > int64_t(NTS_STATIC_STAGING_BYTES))
         return fail(ctx, NTS_EINVAL, "the plan's two staging buffers exceed NTS_STATIC_STAGING_BYTES: "
                                      "create the plan with staging_bytes <= NTS_STATIC_STAGING_BYTES / 2");

@@ -77,5 +77,13 @@ def test_static_staging_rejects_plans_that_do_not_fit():
             b.nts_plan_free(plan)
         with pytest.raises(b.NtsError):
             b.nts_run_migrate_static(0, sp, dpa, 0)
+        # a plan with nothing to move is a no-op whatever its (default, 64 MiB) chunk geometry
+        empty = b.nts_plan_create(ctx, L=1, D=32, elem_bytes=2, page_size=1, Hs=2, Hd=2, src_head_off=0, dst_head_off=0,
+                                  w=2, S_src=8, S_dst=8, ctx_len=np.zeros(2, np.int32), src_pages=np.zeros(0, np.int32),
+                                  dst_pages=np.zeros(0, np.int32))
+        try:
+            b.nts_run_migrate_static(empty, sp, dpa, 0)
+        finally:
+            b.nts_plan_free(empty)
     finally:
         b.nts_free(ctx)
