@@ -440,7 +440,7 @@ static int run_range(nts_plan *pl, NtsMoveMode mode, const void *const *layer_pt
     char *lin = static_cast<char *>(linear);
     for (int64_t done = 0; done < n_frag; done += lim) {
         const int64_t n = n_frag - done < lim ? n_frag - done : lim;
-        NTS_HIP(ctx, nts_launch_move(mode, pl, q0 + done, n, tab, lin + done * pl->frag_bytes, staging, st));
+        NTS_HIP(ctx, nts_launch_move(mode, pl, q0 + done, n, tab, lin + done * pl->frag_bytes, staging, false, st));
     }
     return NTS_OK;
 }

@@ -95,9 +95,12 @@ enum NtsMoveMode { NTS_MOVE_PACK = 0, NTS_MOVE_UNPACK = 1 };
 
 // nts_move.hip
 int64_t nts_max_frags_per_launch(const nts_plan *pl);
-// linear_is_staging: the stream side is a small buffer reused within moments (a chunk), not the whole stream
+// linear_is_staging: the stream side is a small buffer reused within moments (a chunk), not the whole stream;
+// rank_order: pipeline-internal move that follows the plan's destination ranking if it has one (the
+// stream handed out by pack / unpack and their chunk calls always keeps the caller's token order)
 hipError_t nts_launch_move(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int64_t n_frag,
-                           const NtsLayerTab &tab, char *linear, bool linear_is_staging, hipStream_t st);
+                           const NtsLayerTab &tab, char *linear, bool linear_is_staging, bool rank_order,
+                           hipStream_t st);
 // pack fragments [pack_q0, +pack_n) of plan `ppl` into pack_buf and unpack fragments
 // [unpack_q0, +unpack_n) of plan `upl` from unpack_buf in one launch (either count may be
 // zero, and then its plan may be null; the two plans may differ)

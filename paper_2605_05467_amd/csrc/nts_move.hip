@@ -221,12 +221,23 @@ void nts_make_job(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int64_t n_fr
     job->wave_in_frag = (V % kThreads) == 0 ? 1 : 0;
 }
 
+// A plan ranked by destination slot is packed and unpacked in that order inside the pipeline:
+// what lies in the staging buffers is no output, and the unpack half then writes upwards.
+// Both halves of a chunk must agree, so every pipeline-internal job goes through here.
+static void use_rank_order(NtsMoveMode mode, const nts_plan *pl, NtsMoveJob *job)
+{
+    if (!pl->d_sslot_by_dst) return;
+    job->slots = mode == NTS_MOVE_PACK ? pl->d_sslot_by_dst : pl->d_dslot_by_dst;
+}
+
 hipError_t nts_launch_move(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int64_t n_frag,
-                           const NtsLayerTab &tab, char *linear, bool linear_is_staging, hipStream_t st)
+                           const NtsLayerTab &tab, char *linear, bool linear_is_staging, bool rank_order,
+                           hipStream_t st)
 {
     if (n_frag <= 0) return hipSuccess;
     NtsMoveJob job;
     nts_make_job(mode, pl, q0, n_frag, linear, &job);
+    if (rank_order) use_rank_order(mode, pl, &job);
     const dim3 grid((job.n_vec + kThreads - 1) / kThreads), block(kThreads);
 #define NTS_LAUNCH(B, P)                                                                              \
     {                                                                                                 \
@@ -254,17 +265,15 @@ hipError_t nts_launch_stage(const nts_plan *ppl, int64_t pack_q0, int64_t pack_n
     if (!has_a && !has_b) return hipSuccess;
     if (has_a && has_b && ppl->vec != upl->vec) {
         // two plans whose vector widths differ cannot share the kernel instance
-        const hipError_t e = nts_launch_move(NTS_MOVE_UNPACK, upl, unpack_q0, unpack_n, dtab, unpack_buf, true, st);
+        const hipError_t e = nts_launch_move(NTS_MOVE_UNPACK, upl, unpack_q0, unpack_n, dtab, unpack_buf, true, true, st);
         if (e != hipSuccess) return e;
-        return nts_launch_move(NTS_MOVE_PACK, ppl, pack_q0, pack_n, stab, pack_buf, true, st);
+        return nts_launch_move(NTS_MOVE_PACK, ppl, pack_q0, pack_n, stab, pack_buf, true, true, st);
     }
     NtsMoveJob a = {}, b = {};   // an absent side is a job of zero vectors
     if (has_a) nts_make_job(NTS_MOVE_PACK, ppl, pack_q0, pack_n, pack_buf, &a);
     if (has_b) nts_make_job(NTS_MOVE_UNPACK, upl, unpack_q0, unpack_n, unpack_buf, &b);
-    // A plan ranked by destination slot is packed and unpacked in that order: what lies in the
-    // staging buffers is no output of the pipeline, and the unpack half then writes upwards.
-    if (has_a && ppl->d_sslot_by_dst) a.slots = ppl->d_sslot_by_dst;
-    if (has_b && upl->d_dslot_by_dst) b.slots = upl->d_dslot_by_dst;
+    if (has_a) use_rank_order(NTS_MOVE_PACK, ppl, &a);
+    if (has_b) use_rank_order(NTS_MOVE_UNPACK, upl, &b);
     const int vec = has_a ? ppl->vec : upl->vec;
     const uint32_t wg_a = (a.n_vec + kThreads - 1) / kThreads, wg_b = (b.n_vec + kThreads - 1) / kThreads;
     const dim3 grid(wg_a + wg_b), block(kThreads);

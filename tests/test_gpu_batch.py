@@ -47,7 +47,10 @@ def test_batch_of_unrelated_pairs_equals_the_oracle_pair_by_pair(env, first):
             h = random_case_host(c, b.nts_route(c["H"], c["Ns"], c["rs"], c["Nd"], c["rd"]))
             src_d = [torch.from_numpy(a).cuda() for a in h["src_arr"]]
             dst_d = [torch.from_numpy(a).cuda() for a in h["dst_arr"]]
-            plans.append(b.nts_plan_create(ctx, **random_case_plan_args(b, c, h)))
+            args = random_case_plan_args(b, c, h)
+            if seed % 2:                                   # every other pair moves its tokens in destination order
+                args["flags"] |= b.NTS_ORDER_BY_DST
+            plans.append(b.nts_plan_create(ctx, **args))
             stabs.append([t.data_ptr() for t in src_d])
             dtabs.append([t.data_ptr() for t in dst_d])
             hosts.append(h)
@@ -165,7 +168,8 @@ def test_whole_tp_switch_as_one_batch_matches_the_oracle_cluster(env):
                 plans.append(b.nts_plan_create(ctx, L=L, D=D, elem_bytes=2, page_size=1, Hs=Hs, Hd=Hn,
                                                src_head_off=so, dst_head_off=do, w=w, S_src=S, S_dst=S,
                                                ctx_len=[len(sslot)], src_pages=sslot, dst_pages=dslot,
-                                               staging_bytes=2048, flags=b.NTS_VALIDATE_UNIQUE_DST))
+                                               staging_bytes=2048,
+                                               flags=b.NTS_VALIDATE_UNIQUE_DST | (b.NTS_ORDER_BY_DST if (s + d + step) % 2 else 0)))
                 stabs.append(b.layer_ptrs(dev[s].data_ptr(), L, S * Hs * D * 2))
                 dtabs.append(b.layer_ptrs(new_dev[d].data_ptr(), L, S * Hn * D * 2))
             assert len(plans) >= G
