@@ -1,6 +1,7 @@
 """Seeded random geometries: every case draws a model shape, page size, TP pair,
 request mix, pool sizes, row padding and staging size (every other case also asks
-for run detection), runs pack, the pipelined
+for run detection, every third for the destination ranking: pack and unpack must
+keep the caller's token order all the same), runs pack, the pipelined
 migration and the pool-to-pool kernel through the C ABI and compares whole
 outputs with the oracle, bit for bit."""
 import numpy as np
@@ -34,6 +35,8 @@ def test_random_geometry(env, seed):
     kw = random_case_plan_args(b, c, h)
     if seed % 2:
         kw["flags"] |= b.NTS_DETECT_RUNS
+    if seed % 3 == 0:                     # every third case moves its tokens in destination order where it may
+        kw["flags"] |= b.NTS_ORDER_BY_DST
     plan = b.nts_plan_create(ctx, **kw)
     try:
         info = b.nts_plan_info(plan)
