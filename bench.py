@@ -307,7 +307,17 @@ def linear_bench(args, torch, b):
     Launches are captured into a HIP graph that walks through more than 3 GiB of distinct
     weight copies, so no shard is served from a cache and launch gaps do not hide the kernels."""
     from workload.linear import LAYERS
+    from workload import device as wdev
     ctx = b.nts_init(0)
+    # measured ceilings beside the nominal peaks: the matrix cores alone on random operands (the clock
+    # they sustain is power-limited and data-dependent) and a read-only HBM stream
+    mfma_ceiling = wdev.mfma_ceiling_tflops()
+    read_ceiling = wdev.read_ceiling_gbs()
+    print(json.dumps({"linear_ceilings": {"mfma_bf16_TFLOPs_measured": mfma_ceiling, "mfma_bf16_TFLOPs_nominal": 2500.0,
+                                          "hbm_read_GBs_measured": read_ceiling, "hbm_GBs_nominal": HBM_PEAK_GBS,
+                                          "how": "workload/fill_gpu.hip probes: 4 x 4 v_mfma_f32_32x32x16_bf16 tiles per "
+                                                 "wavefront on pseudo-random registers, four wavefronts per CU; eight "
+                                                 "16-byte non-temporal loads per lane over 1 GiB"}}), flush=True)
     for layer in [f"{args.model}_{name}" for name in args.layers.split(",")]:
         n_out, n_in, split = LAYERS[layer]
         wbytes = n_out * n_in * 2
@@ -389,10 +399,12 @@ def linear_bench(args, torch, b):
                 # below ~312 flop per weight byte (2.5 PFLOP/s / 8 TB/s) the layer is bound by reading the shard
                 if M <= 256:
                     ach = (shard_bytes + M * k * 2 + M * nn * 2) / us / 1e3
-                    roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS}
+                    roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                            "read_ceiling": read_ceiling, "frac_of_read_ceiling": ach / read_ceiling}
                 else:
                     ach = 2.0 * M * nn * k / us / 1e6
-                    roof = {"bound": "mfma", "achieved": ach, "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0}
+                    roof = {"bound": "mfma", "achieved": ach, "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0,
+                            "mfma_ceiling": mfma_ceiling, "frac_of_mfma_ceiling": ach / mfma_ceiling}
                 print(json.dumps({"linear": layer, "split": split, "tp": tp, "rank": tp - 1, "M": M, "Nn": nn, "K": k,
                                   "shard_MiB": shard_bytes / 2**20, "us_per_call": us, "dtype": "bf16",
                                   "kernel": "tiled" if how.tiled else "decode" if how.tile_rows == 16 else "stream",

@@ -53,6 +53,17 @@ def test_device_fill_matches_host_fill(torch):
     assert wdev.count_mismatch(t, 1234, start_word=77) == 1
 
 
+def test_measurement_probes_run_and_report_plausible_ceilings(torch):
+    """The two probes bench.py --linear reports as measured ceilings (matrix cores alone on
+    random operands; a read-only HBM stream) launch, finish and land between a loose floor
+    and the chip's nominal peaks."""
+    from workload import device as wdev
+    t = wdev.mfma_ceiling_tflops(0.05)
+    g = wdev.read_ceiling_gbs(256 << 20)
+    assert 500.0 < t <= 2500.0 * 1.02, t
+    assert 2000.0 < g <= 8000.0 * 1.02, g
+
+
 @pytest.mark.parametrize("p", [1, 4, 16])
 def test_plan_flattening_matches_oracle(b, ctx, p):
     from gpu_util import make_plan, oracle_slots

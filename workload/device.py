@@ -37,6 +37,10 @@ def _clib():
         _lib.wl_fill_words.restype = ctypes.c_int
         _lib.wl_count_mismatch.argtypes = [vp, u64, u64, u64, vp, vp]
         _lib.wl_count_mismatch.restype = ctypes.c_int
+        _lib.wl_mfma_probe.argtypes = [vp, ctypes.c_uint32, ctypes.c_uint32, u64, vp]
+        _lib.wl_mfma_probe.restype = ctypes.c_int
+        _lib.wl_read_probe.argtypes = [vp, u64, vp, vp]
+        _lib.wl_read_probe.restype = ctypes.c_int
     return _lib
 
 
@@ -65,3 +69,58 @@ def count_mismatch(t, seed: int, start_word: int = 0) -> int:
     if rc:
         raise RuntimeError(f"wl_count_mismatch failed with HIP error {rc}")
     return int(cnt.item())
+
+
+def mfma_ceiling_tflops(seconds: float = 0.25) -> float:
+    """bf16 TFLOP/s the matrix cores sustain on pseudo-random operands with nothing else going on
+    (registers only; 1024 workgroups of four wavefronts, each a 128 x 128 accumulator tile), timed
+    over about ``seconds`` of back-to-back launches so that the clock settles where the power limit
+    puts it."""
+    import torch
+    wgs, iters = 1024, 4096
+    out = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    flops = wgs * 4 * iters * 16 * 32768.0
+
+    def launch():
+        rc = _clib().wl_mfma_probe(out.data_ptr(), wgs, iters, fill_key(99), st)
+        if rc:
+            raise RuntimeError(f"wl_mfma_probe failed with HIP error {rc}")
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    launch()
+    torch.cuda.synchronize()
+    e0.record(); launch(); e1.record(); torch.cuda.synchronize()
+    n = max(2, int(seconds / (e0.elapsed_time(e1) * 1e-3)))
+    for _ in range(n):                      # settle
+        launch()
+    e0.record()
+    for _ in range(n):
+        launch()
+    e1.record()
+    torch.cuda.synchronize()
+    return flops * n / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def read_ceiling_gbs(n_bytes: int = 1 << 30) -> float:
+    """GB/s of a read-only stream over ``n_bytes`` of HBM (eight 16-byte non-temporal loads per lane)."""
+    import torch
+    buf = torch.empty(2 * n_bytes, dtype=torch.uint8, device="cuda").fill_(5)     # two halves: no reuse from a cache
+    sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+
+    def launch(i):
+        rc = _clib().wl_read_probe(buf.data_ptr() + (i & 1) * n_bytes, n_bytes, sink.data_ptr(), st)
+        if rc:
+            raise RuntimeError(f"wl_read_probe failed with HIP error {rc}")
+
+    for i in range(4):
+        launch(i)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = 20
+    e0.record()
+    for i in range(n):
+        launch(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return n_bytes * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
