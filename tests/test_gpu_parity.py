@@ -162,6 +162,7 @@ def test_chunks_concatenate_to_the_stream(b, ctx, torch):
     (ModelShape(L=5, H=32, D=128, e=2), (1, 0, 1, 0), 16, 200),   # 8 KiB fragments: several column steps
     (ModelShape(L=2, H=12, D=128, e=2), (1, 0, 4, 3), 1, 333),    # 3 heads: 768 B, 48 of 64 lanes
     (ModelShape(L=1, H=8, D=128, e=4), (4, 1, 8, 2), 1, 1),       # a single token
+    (ModelShape(L=96, H=2, D=32, e=2), (1, 0, 2, 1), 1, 61),      # NTS_MAX_LAYERS: the whole by-value pointer table in use
 ])
 def test_other_geometries(b, ctx, torch, shape, tr, p, T):
     from gpu_util import device_pool, make_plan, slab_bytes, to_host
