@@ -76,6 +76,10 @@ def parse_args():
     ap.add_argument("--tune", action="store_true",
                     help="with --linear: let nts_shard_linear_tune pick each shape's configuration by timing the "
                          "candidates once, and report the default's time beside the tuned one")
+    ap.add_argument("--tune-replay", action="store_true",
+                    help="with --linear: time every candidate configuration (nts_shard_linear_candidates) by the same "
+                         "graph replay as the result itself and keep the fastest (nts_shard_linear_remember): what a "
+                         "caller with its own measurement loop gets")
     ap.add_argument("--library", action="store_true",
                     help="with --linear: also time torch.matmul (hipBLASLt) on the same shards, graph-replayed alike")
     ap.add_argument("--planner", action="store_true",
@@ -373,6 +377,18 @@ def linear_bench(args, torch, b):
                                                   hip_stream=torch.cuda.current_stream().cuda_stream, **kw)
                     torch.cuda.synchronize()
                     us = replay_us()
+                if args.tune_replay:
+                    default_us, default_how = us, how
+                    wsb = max(wsb, 32 * M * nn * 4)        # room for every candidate's K split
+                    ws = torch.empty(wsb + 16, dtype=torch.uint8, device="cuda")
+                    best = (us, how)
+                    for cand in b.nts_shard_linear_candidates(**kw)[1:]:
+                        b.nts_shard_linear_remember(ctx, cand, **kw)
+                        t = replay_us()
+                        if t < best[0]:
+                            best = (t, cand)
+                    b.nts_shard_linear_remember(ctx, best[1], **kw)
+                    us, how = best
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 lib_us = None
                 if args.library:

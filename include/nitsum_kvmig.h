@@ -391,6 +391,24 @@ int nts_shard_linear_tune(nts_ctx *ctx, const nts_linear_desc *d, const void *X,
                           size_t workspace_bytes, void *hip_stream, nts_linear_launch *picked);
 int nts_shard_linear_tuned(const nts_ctx *ctx, const nts_linear_desc *d, nts_linear_launch *out);
 
+/*
+ * The pieces nts_shard_linear_tune is made of, for callers that want to time the
+ * candidates their own way (inside their graph, on their real activations):
+ *   nts_shard_linear_candidates  host arithmetic: the configurations the tuner would
+ *       try for this descriptor, out[0] the default, at most max_out (16 at most);
+ *   nts_shard_linear_with        nts_shard_linear with exactly the configuration `how`
+ *       (workspace: k_splits * M * rows * 4 bytes when k_splits > 1; enqueues only);
+ *       NTS_EINVAL when the library has no such kernel instance for this problem;
+ *   nts_shard_linear_remember    makes `how` the context's choice for this shape, as
+ *       the tuner does with its winner; how == NULL forgets the shape again.
+ * Every configuration computes the same layer to the same parity bar.
+ */
+int nts_shard_linear_candidates(const nts_linear_desc *d, nts_linear_launch *out, int max_out, int *n_out);
+int nts_shard_linear_with(nts_ctx *ctx, const nts_linear_desc *d, const nts_linear_launch *how,
+                          const void *X, const void *W_full, void *Y, void *workspace,
+                          size_t workspace_bytes, void *hip_stream);
+int nts_shard_linear_remember(nts_ctx *ctx, const nts_linear_desc *d, const nts_linear_launch *how);
+
 /* ------------------------------------------------------------------------
  * Goodput-efficiency planner (paper Sec. 3.3.1; host only, no GPU needed).
  * For SLO tier k, thp[i] / thd[i] are the profiled maximum prefill / decode

@@ -48,6 +48,7 @@ EXPORTS = (
     "nts_batch_staging_bytes", "nts_run_migrate_static",
     "nts_shard_linear", "nts_shard_linear_workspace", "nts_shard_linear_launch",
     "nts_shard_linear_tune", "nts_shard_linear_tuned",
+    "nts_shard_linear_candidates", "nts_shard_linear_with", "nts_shard_linear_remember",
     "nts_balanced_block", "nts_goodput_efficiency", "nts_plan_cluster",
 )
 NTS_TP_LEVELS = 4
@@ -131,6 +132,10 @@ _lib.nts_shard_linear.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), _vp, _vp
 _lib.nts_shard_linear_tune.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), _vp, _vp, _i, _vp, _vp, ctypes.c_size_t, _vp,
                                        ctypes.POINTER(nts_linear_launch)]
 _lib.nts_shard_linear_tuned.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), ctypes.POINTER(nts_linear_launch)]
+_lib.nts_shard_linear_candidates.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(nts_linear_launch), _i, _pi]
+_lib.nts_shard_linear_with.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), ctypes.POINTER(nts_linear_launch), _vp, _vp,
+                                       _vp, _vp, ctypes.c_size_t, _vp]
+_lib.nts_shard_linear_remember.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), ctypes.POINTER(nts_linear_launch)]
 _d = ctypes.c_double
 _lib.nts_balanced_block.argtypes = [_d, _d, _i, _pi, _pi]
 _lib.nts_goodput_efficiency.argtypes = [_d, _i, _d, _i, _i, _i, _d, ctypes.POINTER(_d)]
@@ -358,6 +363,32 @@ def nts_shard_linear_tuned(ctx: int, *, M: int, n_out: int, n_in: int, tp: int, 
     if st != NTS_OK:
         raise NtsError(st, "nts_shard_linear_tuned")
     return out
+
+
+def nts_shard_linear_candidates(*, M: int, n_out: int, n_in: int, tp: int, rank: int, split: int,
+                                ldx: int = 0, ldw: int = 0, ldy: int = 0, dtype: int = 0, max_out: int = 16):
+    """The configurations the tuner would try (host arithmetic), the default first."""
+    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy, dtype)
+    out = (nts_linear_launch * max_out)()
+    n = ctypes.c_int(0)
+    st = _lib.nts_shard_linear_candidates(ctypes.byref(d), out, max_out, ctypes.byref(n))
+    if st != NTS_OK:
+        raise NtsError(st, "nts_shard_linear_candidates")
+    return [out[i] for i in range(n.value)]
+
+
+def nts_shard_linear_with(ctx: int, how: "nts_linear_launch", X: int, W_full: int, Y: int, *, M: int, n_out: int,
+                          n_in: int, tp: int, rank: int, split: int, ldx: int = 0, ldw: int = 0, ldy: int = 0,
+                          dtype: int = 0, workspace: int = 0, workspace_bytes: int = 0, hip_stream: int = 0) -> None:
+    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy, dtype)
+    _check(_lib.nts_shard_linear_with(ctx, ctypes.byref(d), ctypes.byref(how), X, W_full, Y, workspace, workspace_bytes,
+                                      hip_stream), ctx)
+
+
+def nts_shard_linear_remember(ctx: int, how: Optional["nts_linear_launch"], *, M: int, n_out: int, n_in: int, tp: int,
+                              rank: int, split: int, ldx: int = 0, ldw: int = 0, ldy: int = 0, dtype: int = 0) -> None:
+    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy, dtype)
+    _check(_lib.nts_shard_linear_remember(ctx, ctypes.byref(d), ctypes.byref(how) if how is not None else None), ctx)
 
 
 def nts_balanced_block(thp: float, thd: float, max_inst: int = 8) -> Tuple[int, int]:

@@ -815,6 +815,110 @@ static hipError_t launch_linear(const LinearGeom &g, int dtype, const void *X, c
                                    g.ldy, g.M, g.Nn, g.K, dtype == NTS_F16, st);
 }
 
+static int check_linear_operands(nts_ctx *ctx, const void *X, const void *W_full, const void *Y)
+{
+    if (!X || !W_full || !Y) return fail(ctx, NTS_EINVAL, "null operand");
+    if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W_full) | reinterpret_cast<uintptr_t>(Y)) % 16)
+        return fail(ctx, NTS_EINVAL, "operands must be 16-byte aligned");
+    return NTS_OK;
+}
+
+// Inverse of describe_launch: the configuration a public launch description names, for the problem in
+// `g`.  False when the library has no such kernel instance or the split does not fit the problem.
+static bool launch_to_geom(const nts_linear_launch *how, LinearGeom *g)
+{
+    if (!how) return false;
+    const int n_slabs = g->K / 64;
+    NtsStreamCfg c;
+    c.splits = how->k_splits;
+    if (c.splits < 1 || c.splits > 32) return false;
+    if (how->tiled) {
+        if (how->tile_rows != 256 || how->tile_cols != 256 || c.splits != 1) return false;
+        g->tiled = true;
+        g->cfg.splits = 1;
+        return true;
+    }
+    const int sps = (n_slabs + c.splits - 1) / c.splits;
+    if ((n_slabs + sps - 1) / sps != c.splits) return false;                 // would leave an empty split
+    c.nsets = how->slabs_ahead + 1;
+    if (how->tile_rows == 16) {                                              // decode kernel
+        if (g->M > 16 || how->tile_cols % 16) return false;
+        c.rt = how->tile_cols / 16;
+        c.ks = how->k_waves;
+        const bool inst = (c.ks == 2 && c.rt == 1) || (c.ks == 4 && c.rt == 1) || (c.ks == 4 && c.rt == 2);
+        if (!inst || c.nsets != (c.rt == 1 ? 8 : 6) || sps / c.ks < 1) return false;
+    } else {                                                                 // streaming kernel
+        if (how->tile_rows % 32 || how->tile_cols % 32 || how->k_waves != 1) return false;
+        c.mt = how->tile_rows / 32;
+        c.cw = how->tile_cols / 32;
+        c.rt = 1;
+        c.ks = 0;
+        static const int inst[][3] = {{1, 4, 4}, {2, 4, 4}, {3, 4, 4}, {4, 4, 4}, {6, 4, 3}, {8, 4, 3},
+                                      {1, 1, 8}, {2, 1, 4}, {4, 1, 4}, {2, 2, 4}, {4, 2, 4}};
+        bool ok = false;
+        for (const auto &v : inst) ok = ok || (v[0] == c.mt && v[1] == c.cw && v[2] == c.nsets);
+        if (!ok) return false;
+    }
+    g->tiled = false;
+    g->cfg = c;
+    return true;
+}
+
+int nts_shard_linear_candidates(const nts_linear_desc *d, nts_linear_launch *out, int max_out, int *n_out)
+{
+    LinearGeom g;
+    if (!out || !n_out || max_out < 1 || linear_geom(d, &g) != NTS_OK) return NTS_EINVAL;
+    NtsLinearCand cand[16];
+    const int n = nts_linear_candidates(g.M, g.Nn, g.K, 1.4, cand, max_out < 16 ? max_out : 16);
+    for (int i = 0; i < n; ++i) {
+        LinearGeom h = g;
+        h.tiled = cand[i].tiled;
+        h.cfg = cand[i].cfg;
+        describe_launch(h, &out[i]);
+    }
+    *n_out = n;
+    return NTS_OK;
+}
+
+int nts_shard_linear_with(nts_ctx *ctx, const nts_linear_desc *d, const nts_linear_launch *how, const void *X,
+                          const void *W_full, void *Y, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!ctx) return NTS_EINVAL;
+    LinearGeom g;
+    if (linear_geom(d, &g) != NTS_OK) return fail(ctx, NTS_EINVAL, "bad linear-layer descriptor");
+    if (!launch_to_geom(how, &g)) return fail(ctx, NTS_EINVAL, "no such kernel configuration for this problem");
+    const int rc = check_linear_operands(ctx, X, W_full, Y);
+    if (rc != NTS_OK) return rc;
+    const size_t need = linear_workspace_need(g);
+    if (need && (!workspace || reinterpret_cast<uintptr_t>(workspace) % 16 || workspace_bytes < need))
+        return fail(ctx, NTS_EINVAL, "workspace missing, misaligned or too small");
+    DeviceGuard guard(ctx->device);
+    NTS_HIP(ctx, launch_linear(g, d->dtype, X, W_full, Y, workspace, static_cast<hipStream_t>(hip_stream)));
+    return NTS_OK;
+}
+
+int nts_shard_linear_remember(nts_ctx *ctx, const nts_linear_desc *d, const nts_linear_launch *how)
+{
+    if (!ctx) return NTS_EINVAL;
+    LinearGeom g;
+    if (linear_geom(d, &g) != NTS_OK) return fail(ctx, NTS_EINVAL, "bad linear-layer descriptor");
+    const auto key = std::make_tuple(g.M, g.Nn, g.K, int(d->dtype));
+    if (!how) {                                       // forget: back to the default
+        ctx->tuned_linear.erase(key);
+        return NTS_OK;
+    }
+    if (!launch_to_geom(how, &g)) return fail(ctx, NTS_EINVAL, "no such kernel configuration for this problem");
+    nts_ctx::TunedLinear t;
+    t.tiled = g.tiled;
+    t.mt = g.cfg.mt; t.cw = g.cfg.cw; t.rt = g.cfg.rt; t.nsets = g.cfg.nsets; t.splits = g.cfg.splits; t.ks = g.cfg.ks;
+    try {
+        ctx->tuned_linear[key] = t;
+    } catch (...) {
+        return fail(ctx, NTS_ENOMEM, "host allocation failed");
+    }
+    return NTS_OK;
+}
+
 int nts_shard_linear_launch(const nts_linear_desc *d, nts_linear_launch *out)
 {
     LinearGeom g;
@@ -830,14 +934,6 @@ int nts_shard_linear_tuned(const nts_ctx *ctx, const nts_linear_desc *d, nts_lin
     if (ctx->tuned_linear.find(std::make_tuple(g.M, g.Nn, g.K, int(d->dtype))) == ctx->tuned_linear.end()) return NTS_ERANGE;
     apply_tuned(ctx, d->dtype, SIZE_MAX, true, &g);
     describe_launch(g, out);
-    return NTS_OK;
-}
-
-static int check_linear_operands(nts_ctx *ctx, const void *X, const void *W_full, const void *Y)
-{
-    if (!X || !W_full || !Y) return fail(ctx, NTS_EINVAL, "null operand");
-    if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W_full) | reinterpret_cast<uintptr_t>(Y)) % 16)
-        return fail(ctx, NTS_EINVAL, "operands must be 16-byte aligned");
     return NTS_OK;
 }
 

@@ -943,8 +943,9 @@ int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out
     auto same = [](const NtsLinearCand &a, const NtsLinearCand &b) {
         if (a.tiled != b.tiled) return false;
         if (a.tiled) return true;
-        return a.cfg.mt == b.cfg.mt && a.cfg.cw == b.cfg.cw && a.cfg.rt == b.cfg.rt && a.cfg.splits == b.cfg.splits &&
-               a.cfg.ks == b.cfg.ks && a.cfg.nsets == b.cfg.nsets;
+        if (a.cfg.ks != b.cfg.ks || a.cfg.rt != b.cfg.rt || a.cfg.splits != b.cfg.splits || a.cfg.nsets != b.cfg.nsets)
+            return false;
+        return a.cfg.ks > 0 || (a.cfg.mt == b.cfg.mt && a.cfg.cw == b.cfg.cw);   // the decode kernel has no tile fields
     };
     double best = 0.;
     for (const NtsLinearCand &c : all) {

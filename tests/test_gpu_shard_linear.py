@@ -347,3 +347,67 @@ def test_tuned_configuration_keeps_parity(env, M, n_out, n_in, tp, split):
             check(Yd, "default-sized workspace")
     finally:
         b.nts_free(ctx)
+
+
+@pytest.mark.parametrize("M,n_out,n_in,tp,split,dtype", [
+    (1, 4096, 14336, 1, "in", "bf16"), (16, 6144, 4096, 1, "out", "bf16"), (9, 1000, 12352, 1, "out", "f16"),
+    (64, 4096, 4096, 4, "in", "bf16"), (130, 4104, 6144, 1, "out", "f16"), (300, 2048, 2048, 1, "out", "bf16"),
+    (1024, 6144, 4096, 1, "out", "bf16"), (520, 2056, 512, 2, "in", "bf16")])
+def test_every_candidate_configuration_computes_the_layer(env, M, n_out, n_in, tp, split, dtype):
+    """nts_shard_linear_candidates lists what the tuner may pick for a shape; each of
+    them, run through nts_shard_linear_with, must give the layer's result: inside the
+    tight tolerance on random inputs and bit-exact on integer inputs.  The first
+    candidate is the default; a description the library has no kernel for is refused;
+    remembering one makes nts_shard_linear use it."""
+    torch, b, _ = env
+    ctx = b.nts_init(0)
+    try:
+        sp = b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN
+        k = n_in if split == "out" else n_in // tp
+        nn = n_out // tp if split == "out" else n_out
+        pad = 8 if nn % 8 == 0 else 8 - nn % 8
+        kw = dict(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=tp - 1, split=sp, ldy=nn + pad,
+                  dtype=b.NTS_BF16 if dtype == "bf16" else b.NTS_F16)
+        cands = b.nts_shard_linear_candidates(**kw)
+        fields = ("tiled", "tile_rows", "tile_cols", "k_splits", "slabs_ahead", "k_waves")
+        key = lambda c: tuple(getattr(c, f) for f in fields)
+        assert 1 <= len(cands) <= 16 and len({key(c) for c in cands}) == len(cands)
+        assert key(cands[0]) == key(b.nts_shard_linear_launch(**kw))
+        decode = osl.bf16_to_f64 if dtype == "bf16" else osl.f16_to_f64
+        st = torch.cuda.current_stream().cuda_stream
+        ws = torch.empty(32 * M * nn * 4 + 16, dtype=torch.uint8, device="cuda")
+        for exact in (False, True):
+            Xh, Wh = (linear_inputs_int if exact else linear_inputs)(70 + M, M, n_out, n_in, x_cols=k, dtype=dtype)
+            Xd = torch.from_numpy(Xh.view(np.int16)).cuda()
+            Wd = torch.from_numpy(Wh.view(np.int16)).cuda()
+            X64, W64 = decode(Xh), decode(Wh)
+            want, _ = osl.shard_linear(X64, W64, tp, tp - 1, split)
+            tight = osl.tight_tolerance(want, osl.product_norm(X64, W64, tp, tp - 1, split), k, dtype)
+            for c in cands:
+                Yd = torch.full((M, nn + pad), 12345, dtype=torch.int16, device="cuda")
+                b.nts_shard_linear_with(ctx, c, Xd.data_ptr(), Wd.data_ptr(), Yd.data_ptr(), workspace=ws.data_ptr(),
+                                        workspace_bytes=ws.numel() - 16, hip_stream=st, **kw)
+                torch.cuda.synchronize()
+                got = Yd.cpu().numpy().view(np.uint16)
+                assert np.all(got[:, nn:] == 12345), key(c)
+                if exact:
+                    assert np.array_equal(got[:, :nn], osl.round_to_bits(want, dtype)), key(c)
+                else:
+                    assert np.all(np.abs(decode(got[:, :nn]) - want) <= tight), key(c)
+        # a split that needs workspace is refused without it; a description with no kernel behind it is refused
+        split_c = [c for c in cands if c.k_splits > 1]
+        if split_c:
+            with pytest.raises(b.NtsError):
+                b.nts_shard_linear_with(ctx, split_c[0], Xd.data_ptr(), Wd.data_ptr(), Yd.data_ptr(), hip_stream=st, **kw)
+        bogus = type(cands[0])(tiled=0, tile_rows=160, tile_cols=128, k_splits=1, slabs_ahead=3, k_waves=1)
+        with pytest.raises(b.NtsError) as ei:
+            b.nts_shard_linear_with(ctx, bogus, Xd.data_ptr(), Wd.data_ptr(), Yd.data_ptr(), hip_stream=st, **kw)
+        assert ei.value.status == b.NTS_EINVAL
+        # remember / forget
+        last = cands[-1]
+        b.nts_shard_linear_remember(ctx, last, **kw)
+        assert key(b.nts_shard_linear_tuned(ctx, **kw)) == key(last)
+        b.nts_shard_linear_remember(ctx, None, **kw)
+        assert b.nts_shard_linear_tuned(ctx, **kw) is None
+    finally:
+        b.nts_free(ctx)
