@@ -70,9 +70,10 @@ int fill_tab(const nts_plan *pl, const void *const *ptrs, NtsLayerTab &tab)
 // Remember that `pl` has work on `st`: nts_plan_free orders that work before any reuse of the plan's block.
 void note_stream(nts_plan *pl, hipStream_t st)
 {
-    for (hipStream_t s : pl->used_streams)
-        if (s == st) return;
-    pl->used_streams.push_back(st);
+    for (int i = 0; i < pl->n_used_streams; ++i)
+        if (pl->used_streams[i] == st) return;
+    if (pl->n_used_streams < nts_plan::kMaxStreams) pl->used_streams[pl->n_used_streams++] = st;
+    else pl->more_streams = true;
 }
 
 bool overlaps(const char *a, int64_t na, const char *b, int64_t nb)
@@ -351,7 +352,7 @@ int nts_plan_free(nts_plan *pl)
             if (ctx->spare[slot].bytes >= pl->d_block_bytes) slot = -1;   // this one is the smallest
         }
         hipError_t e = hipSuccess;
-        if (slot >= 0 && pl->used_streams.size() <= 1) {
+        if (slot >= 0 && pl->n_used_streams <= 1) {
             nts_ctx::Spare &sp = ctx->spare[slot];
             if (sp.ptr) {                            // evict: the block must be idle before hipFree
                 if (sp.pending) e = hipEventSynchronize(sp.ev);
@@ -360,7 +361,7 @@ int nts_plan_free(nts_plan *pl)
                 sp.bytes = 0;
                 sp.pending = false;
             }
-            if (e == hipSuccess && !pl->used_streams.empty()) {
+            if (e == hipSuccess && pl->n_used_streams > 0) {
                 e = hipEventRecord(sp.ev, pl->used_streams[0]);
                 sp.pending = e == hipSuccess;
             }
@@ -373,7 +374,9 @@ int nts_plan_free(nts_plan *pl)
         }
         if (pl->d_block) {                           // not kept (or several streams): wait, then free
             (void)hipGetLastError();
-            for (hipStream_t s : pl->used_streams) (void)hipStreamSynchronize(s);
+            if (pl->more_streams) (void)hipDeviceSynchronize();
+            else
+                for (int i = 0; i < pl->n_used_streams; ++i) (void)hipStreamSynchronize(pl->used_streams[i]);
             e = hipFree(pl->d_block);
         }
         if (e != hipSuccess) rc = fail_hip(ctx, e, "nts_plan_free");

@@ -63,8 +63,13 @@ struct nts_plan {
     int64_t n_runs = 0;
     // host copies of the slot lists, fetched on first use by the per-fragment memcpy baseline
     std::vector<int32_t> h_sslot, h_dslot, h_run_start;
-    // streams this plan's run calls have launched on; their pending work reads d_block
-    std::vector<hipStream_t> used_streams;
+    // streams this plan's run calls have launched on; their pending work reads d_block.  A fixed
+    // array, so that a run call never allocates; with more streams than it holds, nts_plan_free
+    // waits for the whole device instead.
+    static constexpr int kMaxStreams = 8;
+    hipStream_t used_streams[kMaxStreams] = {};
+    int n_used_streams = 0;
+    bool more_streams = false;
 };
 
 // Base pointers of the 2L per-(layer, K|V) arrays of one pool; passed by value

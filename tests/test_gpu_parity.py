@@ -521,3 +521,38 @@ def test_migrate_can_be_captured_in_a_hip_graph(b, ctx, torch):
         del graph
     finally:
         b.nts_plan_free(plan)
+
+
+def test_one_plan_on_many_streams_then_freed(b, ctx, torch):
+    """A plan remembers the streams it has work on so that freeing it is ordered behind that
+    work; with more streams than its fixed record holds the free waits for the device.  Ten
+    streams in turn, the last run left unsynchronised before the free, a new plan right after."""
+    from gpu_util import device_pool, make_plan, slab_bytes, to_host
+    from workload import device as wdev
+    case = make_case("c1")[0]
+    sh = case.shape
+    _, _, dst_h = _expected_full(case, sh.L, sh.D)
+    src_d, dst_d = device_pool(case, "src"), device_pool(case, "dst")
+    sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+    dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
+    streams = [torch.cuda.Stream() for _ in range(10)]
+    plan = make_plan(b, ctx, case, staging_bytes=1 << 20)
+    info = b.nts_plan_info(plan)
+    staging = torch.empty(2 * info.chunk_bytes, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    try:
+        for i, s in enumerate(streams):
+            b.nts_run_migrate(plan, sp, dp, staging.data_ptr(), s.cuda_stream)
+            if i + 1 < len(streams):
+                s.synchronize()
+                assert to_host(dst_d).tobytes() == dst_h.tobytes()
+                wdev.fill_tensor(dst_d, case.seed_dst)
+                torch.cuda.synchronize()
+    finally:
+        b.nts_plan_free(plan)
+    other = make_plan(b, ctx, case, staging_bytes=1 << 20)   # may take over the freed plan's block
+    try:
+        torch.cuda.synchronize()
+        assert to_host(dst_d).tobytes() == dst_h.tobytes()
+    finally:
+        b.nts_plan_free(other)
