@@ -150,6 +150,16 @@ int nts_route(int H, int Ns, int rs, int Nd, int rd,
  * NTS_ENOMEM, NTS_EHIP.  A plan with zero tokens is legal; its run calls do nothing.
  */
 int nts_plan_create(nts_ctx *ctx, const nts_desc *d, nts_plan **out);
+
+/*
+ * Frees a plan (NULL is allowed).  Run calls of the plan that are still queued
+ * or running stay valid: the plan's device arrays are kept until that work has
+ * finished.  With work on one stream the call does not wait (the arrays are
+ * handed to the next plan of the context, which orders itself behind that work);
+ * with work on several streams it waits for them, beyond eight streams for the
+ * whole device.  NTS_EHIP if the runtime reports an error; the plan is gone
+ * either way.
+ */
 int nts_plan_free(nts_plan *plan);
 int nts_plan_info(const nts_plan *plan, nts_info *out);
 
