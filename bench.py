@@ -556,6 +556,20 @@ def main():
     t1 = time.perf_counter()
 
     ms_per_step = 1e3 * (t1 - t0) / args.steps
+    # In the timed loop the planning of step k+1 runs while the GPU still executes step k's
+    # launches (run calls only enqueue).  Beside it: one step at a time with the device idle before
+    # and after (no overlap between steps), and the planning part alone; medians of five.
+    alone, plan_alone = [], []
+    for _ in range(5):
+        torch.cuda.synchronize()
+        ta = time.perf_counter()
+        one_step()
+        torch.cuda.synchronize()
+        alone.append(1e3 * (time.perf_counter() - ta))
+        ta = time.perf_counter()
+        for p_ in [pr.plan(ctx, staging_bytes) for pr in pairs]:
+            b.nts_plan_free(p_)
+        plan_alone.append(1e3 * (time.perf_counter() - ta))
     F = sum(i.F for i in infos)
     X = sum(i.X for i in infos)
     T = sum(i.T for i in infos)
@@ -585,6 +599,11 @@ def main():
                    "payload_bytes": X, "staging_bytes_each": infos[0].chunk_bytes,
                    "stage_launches_per_step": launches, "pairs": n_pairs,
                    "pairs_run_as": "one batch (nts_run_migrate_batch)" if batch else "one call per pair"},
+        "ms_per_step_one_at_a_time": sorted(alone)[2],
+        "plan_ms_alone": sorted(plan_alone)[2],
+        "steps_overlap": "run calls only enqueue, so in the timed loop a step's route + plan runs while the previous "
+                         "step's launches execute; ms_per_step_one_at_a_time has the device idle before and after "
+                         "each step, plan_ms_alone is route + nts_plan_create + nts_plan_free by themselves",
         "tokens_per_s": T / (ms_per_step * 1e-3),
         "payload_GBps": X / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "kernel": "nts_stage_kernel<16> (pack chunk k || unpack chunk k-1)",
