@@ -182,22 +182,46 @@ __global__ __launch_bounds__(kThreads) void nts_direct_kernel(NtsMoveJob a, NtsL
                                                               NtsLayerTab btab)
 {
     typedef typename VecOf<BYTES>::type vec_t;
-    const uint32_t gv = blockIdx.x * kThreads + threadIdx.x;
-    if (gv >= a.n_vec) return;
-    uint32_t fl, v;
-    if (a.v_shift >= 0) {
-        fl = gv >> a.v_shift;
-        v = gv & (a.V - 1u);
+    const uint32_t gv0 = blockIdx.x * kThreads;       // first vector of this wavefront: wave-uniform
+    const char *src;
+    char *dst;
+    if (a.wave_in_frag) {
+        // the wavefront lies inside one fragment: fragment arithmetic, both slot loads and both
+        // layer pointer loads run on the scalar unit (as in move_vector)
+        if (gv0 >= a.n_vec) return;
+        uint32_t fl, v0;
+        if (a.v_shift >= 0) {
+            fl = gv0 >> a.v_shift;
+            v0 = gv0 & (a.V - 1u);
+        } else {
+            fl = fast_div(gv0, a.V_magic);
+            v0 = gv0 - fl * a.V;
+        }
+        const uint32_t t = a.j0 + fl;
+        const uint32_t ls = a.T_magic ? fast_div(t, a.T_magic) : t;
+        const uint32_t j = t - ls * a.T;
+        const int64_t ss = a.slots[j], ds = b.slots[j];
+        const uint64_t in_frag = uint64_t(v0 + threadIdx.x) * BYTES;
+        src = atab.p[a.lc0 + ls] + ss * a.stride + a.head_off + in_frag;
+        dst = btab.p[a.lc0 + ls] + ds * b.stride + b.head_off + in_frag;
     } else {
-        fl = fast_div(gv, a.V_magic);
-        v = gv - fl * a.V;
+        const uint32_t gv = gv0 + threadIdx.x;
+        if (gv >= a.n_vec) return;
+        uint32_t fl, v;
+        if (a.v_shift >= 0) {
+            fl = gv >> a.v_shift;
+            v = gv & (a.V - 1u);
+        } else {
+            fl = fast_div(gv, a.V_magic);
+            v = gv - fl * a.V;
+        }
+        const uint32_t t = a.j0 + fl;
+        const uint32_t ls = a.T_magic ? fast_div(t, a.T_magic) : t;
+        const uint32_t j = t - ls * a.T;
+        const int64_t ss = a.slots[j], ds = b.slots[j];
+        src = atab.p[a.lc0 + ls] + ss * a.stride + a.head_off + uint64_t(v) * BYTES;
+        dst = btab.p[a.lc0 + ls] + ds * b.stride + b.head_off + uint64_t(v) * BYTES;
     }
-    const uint32_t t = a.j0 + fl;
-    const uint32_t ls = a.T_magic ? fast_div(t, a.T_magic) : t;
-    const uint32_t j = t - ls * a.T;
-    const int64_t ss = a.slots[j], ds = b.slots[j];
-    const char *src = atab.p[a.lc0 + ls] + ss * a.stride + a.head_off + uint64_t(v) * BYTES;
-    char *dst = btab.p[a.lc0 + ls] + ds * b.stride + b.head_off + uint64_t(v) * BYTES;
     const vec_t x = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(src));
     store_stream(x, dst);
 }
