@@ -116,6 +116,37 @@ def test_config2_whole_outputs(env):
         del src_d, dst_d
 
 
+@pytest.mark.parametrize("staging_bytes", [(20 << 20) + 3 * 2048, (9 << 20) + 1024])
+def test_config2_chunks_that_end_inside_a_workgroup_group(env, staging_bytes):
+    """The stage kernel hands its workgroups out in aligned groups of 8192 (8 MiB of stream) and
+    leaves the ragged end of a job in plain order: chunks of 20 MiB + 3 fragments (two groups and a
+    tail) and of 9 MiB + 1 KiB (one group and a tail), with and without the destination ranking."""
+    from gpu_util import compare_every_layer, device_pool, make_plan, oracle_slots, slab_bytes
+    torch, b, wdev, ctx, staging = env
+    for case in make_case("c2"):
+        sh = case.shape
+        es, ed = oracle_slots(case)
+        src_d = device_pool(case, "src")
+        sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+        for flags in (b.NTS_VALIDATE_UNIQUE_DST, b.NTS_VALIDATE_UNIQUE_DST | b.NTS_ORDER_BY_DST):
+            print(f"  {case.name} staging {staging_bytes} flags {flags}", flush=True)
+            dst_d = device_pool(case, "dst")
+            dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
+            plan = make_plan(b, ctx, case, staging_bytes=staging_bytes, flags=flags)
+            try:
+                info = b.nts_plan_info(plan)
+                assert info.chunk_bytes // 1024 > 8192 and (info.chunk_bytes // 1024) % 8192 != 0
+                assert 2 * info.chunk_bytes <= staging.numel()
+                b.nts_run_migrate(plan, sp, dp, staging.data_ptr(), torch.cuda.current_stream().cuda_stream)
+                torch.cuda.synchronize()
+            finally:
+                b.nts_plan_free(plan)
+            check_properties(env, case, src_d, dst_d, info)
+            compare_every_layer(case, dst_d, es, ed)
+            del dst_d
+        del src_d
+
+
 @pytest.mark.parametrize("name", ["c3", "c3b", "c3c", "c3d"])
 def test_config3_headline_and_companions(env, name):
     from gpu_util import compare_every_layer, oracle_slots
