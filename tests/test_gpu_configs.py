@@ -147,6 +147,36 @@ def test_config2_chunks_that_end_inside_a_workgroup_group(env, staging_bytes):
         del src_d
 
 
+def test_config2_chunk_calls_at_size(env):
+    """Chunk-by-chunk pack -> unpack through two buffers (the calls a sender and a receiver would
+    use) at 1e6 fragments, with chunks that end inside a group of the kernels' workgroup mapping;
+    every byte of the destination pool against the oracle."""
+    from gpu_util import compare_every_layer, device_pool, make_plan, oracle_slots, slab_bytes
+    torch, b, wdev, ctx, staging = env
+    st = torch.cuda.current_stream().cuda_stream
+    for case in make_case("c2"):
+        sh = case.shape
+        es, ed = oracle_slots(case)
+        src_d, dst_d = device_pool(case, "src"), device_pool(case, "dst")
+        sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+        dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
+        plan = make_plan(b, ctx, case, staging_bytes=(18 << 20) + 5 * 1024)
+        try:
+            info = b.nts_plan_info(plan)
+            assert (info.chunk_bytes // 1024) % 8192 != 0 and 2 * info.chunk_bytes <= staging.numel()
+            print(f"  {case.name}: {info.n_chunks} chunks of {info.chunk_bytes} bytes", flush=True)
+            for k in range(info.n_chunks):
+                p_ = staging.data_ptr() + (k & 1) * info.chunk_bytes
+                b.nts_run_pack_chunk(plan, sp, k, p_, st)
+                b.nts_run_unpack_chunk(plan, p_, k, dp, st)
+            torch.cuda.synchronize()
+        finally:
+            b.nts_plan_free(plan)
+        check_properties(env, case, src_d, dst_d, info)
+        compare_every_layer(case, dst_d, es, ed)
+        del src_d, dst_d
+
+
 @pytest.mark.parametrize("name", ["c3", "c3b", "c3c", "c3d"])
 def test_config3_headline_and_companions(env, name):
     from gpu_util import compare_every_layer, oracle_slots

@@ -154,6 +154,33 @@ def test_chunks_concatenate_to_the_stream(b, ctx, torch):
         b.nts_plan_free(plan)
 
 
+def test_chunk_by_chunk_pack_then_unpack_equals_the_migration(b, ctx, torch):
+    """What a sender and a receiver do around their transport: chunk k packed into one of two
+    buffers, unpacked from it on the other side; ragged chunk size, last chunk short."""
+    from gpu_util import device_pool, make_plan, slab_bytes, to_host
+    for case in make_case("c1")[:3]:
+        sh = case.shape
+        _, _, dst_h = _expected_full(case, sh.L, sh.D)
+        src_d, dst_d = device_pool(case, "src"), device_pool(case, "dst")
+        sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+        dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
+        plan = make_plan(b, ctx, case, staging_bytes=200 * 1024 + 12)
+        try:
+            info = b.nts_plan_info(plan)
+            assert info.n_chunks > 3 and info.F % info.chunk_frags != 0
+            bufs = torch.full((2, info.chunk_bytes + 64), 0xA5, dtype=torch.uint8, device="cuda")
+            st = torch.cuda.current_stream().cuda_stream
+            for k in range(info.n_chunks):
+                p_ = bufs[k & 1].data_ptr()
+                b.nts_run_pack_chunk(plan, sp, k, p_, st)
+                b.nts_run_unpack_chunk(plan, p_, k, dp, st)
+            torch.cuda.synchronize()
+            assert to_host(dst_d).tobytes() == dst_h.tobytes()
+            assert (to_host(bufs)[:, info.chunk_bytes:] == 0xA5).all()      # nothing past a chunk
+        finally:
+            b.nts_plan_free(plan)
+
+
 @pytest.mark.parametrize("shape,tr,p,T", [
     (ModelShape(L=3, H=8, D=64, e=1), (1, 0, 2, 1), 1, 300),      # fp8 KV, 256 B fragments
     (ModelShape(L=2, H=6, D=40, e=2), (1, 0, 2, 0), 2, 157),      # 240 B fragments: 48 B-aligned -> 16 B vectors
