@@ -94,6 +94,7 @@ struct NtsMoveJob {
     uint32_t lc0, j0;      // q0 split into slab index and token index
     uint32_t n_vec;        // vectors (= lanes) of this job
     uint32_t wave_in_frag; // 1 when V is a multiple of 64: a wavefront never straddles fragments
+    uint32_t frags_in_wave; // 2 or 4 when V is 32 or 16: whole fragments per full wavefront; else 0
 };
 
 enum NtsMoveMode { NTS_MOVE_PACK = 0, NTS_MOVE_UNPACK = 1 };

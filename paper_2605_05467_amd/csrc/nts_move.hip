@@ -79,6 +79,31 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint64_t m)
     return uint32_t(__umul64hi(m, uint64_t(n)));
 }
 
+// A full wavefront that covers NF = 2 or 4 whole fragments (V = 64 / NF vectors each), first
+// vector gv0: if the fragments lie in one (layer, K|V) slab, the paged address of this lane's
+// vector from NF scalar slot loads and one or two selects; false if they straddle two slabs.
+template <int BYTES, int NF>
+__device__ __forceinline__ bool small_fragments(const NtsMoveJob &job, const NtsLayerTab &tab, uint32_t gv0,
+                                                uint32_t lane, char **paged)
+{
+    constexpr uint32_t V = kThreads / NF, kShift = NF == 2 ? 5 : 4;
+    const uint32_t t0 = job.j0 + (gv0 >> kShift);
+    const uint32_t ls = job.T_magic ? fast_div(t0, job.T_magic) : t0;
+    const uint32_t j = t0 - ls * job.T;
+    if (j + NF > job.T) return false;
+    int64_t slot;
+    if (NF == 2) {
+        const int32_t s0 = job.slots[j], s1 = job.slots[j + 1];
+        slot = lane < 32u ? s0 : s1;
+    } else {
+        const int32_t s0 = job.slots[j], s1 = job.slots[j + 1], s2 = job.slots[j + 2], s3 = job.slots[j + 3];
+        const int32_t lo = (lane & 16u) ? s1 : s0, hi = (lane & 16u) ? s3 : s2;
+        slot = (lane & 32u) ? hi : lo;
+    }
+    *paged = tab.p[job.lc0 + ls] + slot * job.stride + job.head_off + uint64_t(lane & (V - 1u)) * BYTES;
+    return true;
+}
+
 // wg: index of the (single-wavefront) workgroup inside the job; lane: threadIdx.x
 // LIN_NT: access the stream side with non-temporal instructions too (the paged side always is)
 template <int BYTES, bool PACK, bool LIN_NT>
@@ -109,20 +134,32 @@ __device__ __forceinline__ void move_vector(const NtsMoveJob &job, const NtsLaye
     } else {
         gv = gv0 + lane;
         if (gv >= job.n_vec) return;
-        uint32_t fl, v;                               // fragment (launch-local) and vector inside it
-        if (job.v_shift >= 0) {
-            fl = gv >> job.v_shift;
-            v = gv & (job.V - 1u);
-        } else {
-            fl = fast_div(gv, job.V_magic);
-            v = gv - fl * job.V;
+        bool done = false;
+        // V = 32 or 16: a full wavefront covers two or four whole fragments.  When they lie in one
+        // (layer, K|V) slab the scalar unit fetches their slots and the one layer pointer, and
+        // each lane takes the slot of its own fragment.  Through the pipeline: 512 B fragments
+        // 6.09 -> 6.6 TB/s, 256 B fragments 5.92 -> 6.4 TB/s.  (Two blocks with constant shifts:
+        // one block with the fragment count as a variable measured 1 % slower.)
+        if (job.frags_in_wave == 2 && gv0 + kThreads <= job.n_vec)
+            done = small_fragments<BYTES, 2>(job, tab, gv0, lane, &paged);
+        if (job.frags_in_wave == 4 && gv0 + kThreads <= job.n_vec)
+            done = small_fragments<BYTES, 4>(job, tab, gv0, lane, &paged);
+        if (!done) {
+            uint32_t fl, v;                           // fragment (launch-local) and vector inside it
+            if (job.v_shift >= 0) {
+                fl = gv >> job.v_shift;
+                v = gv & (job.V - 1u);
+            } else {
+                fl = fast_div(gv, job.V_magic);
+                v = gv - fl * job.V;
+            }
+            const uint32_t t = job.j0 + fl;
+            // slabs crossed since the launch's first one (T == 1 has no 64-bit reciprocal)
+            const uint32_t ls = job.T_magic ? fast_div(t, job.T_magic) : t;
+            const uint32_t j = t - ls * job.T;
+            const int64_t slot = job.slots[j];
+            paged = tab.p[job.lc0 + ls] + slot * job.stride + job.head_off + uint64_t(v) * BYTES;
         }
-        const uint32_t t = job.j0 + fl;
-        // slabs crossed since the launch's first one (T == 1 has no 64-bit reciprocal)
-        const uint32_t ls = job.T_magic ? fast_div(t, job.T_magic) : t;
-        const uint32_t j = t - ls * job.T;
-        const int64_t slot = job.slots[j];
-        paged = tab.p[job.lc0 + ls] + slot * job.stride + job.head_off + uint64_t(v) * BYTES;
     }
     char *lin = job.linear + uint64_t(gv) * BYTES;
     if (PACK) {
@@ -281,6 +318,7 @@ void nts_make_job(NtsMoveMode mode, const nts_plan *pl, int64_t q0, int64_t n_fr
     job->j0 = uint32_t(q0 % pl->T);
     job->n_vec = uint32_t(n_frag * V);
     job->wave_in_frag = (V % kThreads) == 0 ? 1 : 0;
+    job->frags_in_wave = (V == 32 || V == 16) ? kThreads / V : 0;
 }
 
 // A plan ranked by destination slot is packed and unpacked in that order inside the pipeline:
