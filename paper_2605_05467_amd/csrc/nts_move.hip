@@ -10,9 +10,9 @@
 // share one.  Vector index -> (fragment, offset) and fragment -> (slab, token)
 // are exact divisions by launch constants, done with a precomputed 64-bit
 // reciprocal (Lemire's method) or a shift.  Measured on MI355X this
-// one-vector-per-lane shape (4 KiB per 256-thread workgroup, hundreds of
-// thousands of workgroups) sustains more HBM bandwidth than variants that
-// keep several loads in flight per lane or that run a persistent grid.
+// one-vector-per-lane shape (1 KiB per single-wavefront workgroup, millions of
+// workgroups) sustains more HBM bandwidth than variants that keep several
+// loads in flight per lane or that run a persistent grid.
 //
 // nts_stage_kernel is the double buffer of Sec. 3.2.2 as one launch: runs of
 // its workgroups alternate between packing chunk k into one staging buffer
