@@ -226,6 +226,42 @@ def test_config4_skewed_four_destinations(env):
     assert total_F == 2621440
 
 
+@pytest.mark.parametrize("ranked", [False, True])
+def test_whole_stream_pack_and_unpack_beyond_one_launch(env, ranked):
+    """nts_run_pack and nts_run_unpack on a 33 GiB stream (config 5's recipe at 270,336 tokens): more
+    than 2^31 lanes, so each call takes two launches; the stream keeps the caller's token order
+    whether or not the plan is ranked.  Every byte of the destination pool against the oracle."""
+    from gpu_util import compare_every_layer, device_pool, make_plan, oracle_slots, slab_bytes
+    torch, b, wdev, ctx, _ = env
+    case = make_case("c5", tokens=270336)[0]
+    sh = case.shape
+    free, total = torch.cuda.mem_get_info()
+    need = case.pool_bytes("src") + case.pool_bytes("dst") + case.T * sh.L * 2 * sh.H * sh.D * sh.e + (1 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of free HBM, {free >> 30} GiB available")
+    es, ed = oracle_slots(case)
+    src_d, dst_d = device_pool(case, "src"), device_pool(case, "dst")
+    sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(case, "src"))
+    dp = b.layer_ptrs(dst_d.data_ptr(), sh.L, slab_bytes(case, "dst"))
+    flags = b.NTS_VALIDATE_UNIQUE_DST | (b.NTS_ORDER_BY_DST if ranked else 0)
+    plan = make_plan(b, ctx, case, staging_bytes=STAGING, flags=flags)
+    try:
+        info = b.nts_plan_info(plan)
+        assert info.X > 32 << 30                       # 16-byte lanes: more than 2^31 of them
+        stream = torch.empty(info.X, dtype=torch.uint8, device="cuda")
+        st = torch.cuda.current_stream().cuda_stream
+        b.nts_run_pack(plan, sp, stream.data_ptr(), st)
+        b.nts_run_unpack(plan, stream.data_ptr(), dp, st)
+        torch.cuda.synchronize()
+    finally:
+        b.nts_plan_free(plan)
+    del stream
+    check_properties(env, case, src_d, dst_d, info)
+    compare_every_layer(case, dst_d, es, ed, label=f"33 GiB stream, ranked={ranked}")
+    del src_d, dst_d
+    torch.cuda.empty_cache()
+
+
 def test_config5_roofline_size(env):
     """Two 92 GiB pools, 88 GiB payload: every byte of the destination pool
     against the oracle, layer by layer, for the double-buffered pipeline and for
