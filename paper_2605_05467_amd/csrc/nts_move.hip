@@ -45,32 +45,34 @@ template <> struct VecOf<4> { typedef uint32_t type; };
 // Ordinary (cache-allocating) store that is written through at agent scope: the line goes to the
 // memory side at once instead of staying dirty in this XCD's L2 until the end-of-kernel release
 // flushes it.  Used for the staging buffers, which the next launch reads from any XCD.
+// The compiler does not know that the statement is a store: the wait states a wide store needs
+// before its data registers may be overwritten are spelled out (s_nop) instead of left to it.
 __device__ __forceinline__ void store_through(const VecOf<16>::type &x, void *p)
 {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(x) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(x) : "memory");
 }
 __device__ __forceinline__ void store_through(const VecOf<8>::type &x, void *p)
 {
-    asm volatile("global_store_dwordx2 %0, %1, off sc1" ::"v"(p), "v"(x) : "memory");
+    asm volatile("global_store_dwordx2 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(x) : "memory");
 }
 __device__ __forceinline__ void store_through(const VecOf<4>::type &x, void *p)
 {
-    asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(x) : "memory");
+    asm volatile("global_store_dword %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(x) : "memory");
 }
 
 // Non-temporal store (the line is not kept in any cache: every pool byte is written once) that
 // is written through at agent scope as well, for the same reason as above.
 __device__ __forceinline__ void store_stream(const VecOf<16>::type &x, void *p)
 {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" ::"v"(p), "v"(x) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(x) : "memory");
 }
 __device__ __forceinline__ void store_stream(const VecOf<8>::type &x, void *p)
 {
-    asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" ::"v"(p), "v"(x) : "memory");
+    asm volatile("global_store_dwordx2 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(x) : "memory");
 }
 __device__ __forceinline__ void store_stream(const VecOf<4>::type &x, void *p)
 {
-    asm volatile("global_store_dword %0, %1, off sc1 nt" ::"v"(p), "v"(x) : "memory");
+    asm volatile("global_store_dword %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(x) : "memory");
 }
 
 // n / d for n < 2^32, given m = floor((2^64 - 1) / d) + 1 (exact for every 32-bit n)
