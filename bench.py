@@ -382,9 +382,11 @@ def linear_bench(args, torch, b):
                     wsb = max(wsb, 32 * M * nn * 4)        # room for every candidate's K split
                     ws = torch.empty(wsb + 16, dtype=torch.uint8, device="cuda")
                     best = (us, how)
+                    cand_us = [(how, us)]
                     for cand in b.nts_shard_linear_candidates(**kw)[1:]:
                         b.nts_shard_linear_remember(ctx, cand, **kw)
                         t = replay_us()
+                        cand_us.append((cand, t))
                         if t < best[0]:
                             best = (t, cand)
                     b.nts_shard_linear_remember(ctx, best[1], **kw)
@@ -430,6 +432,9 @@ def linear_bench(args, torch, b):
                                       "default_kernel": "tiled" if default_how.tiled else "decode" if default_how.tile_rows == 16 else "stream",
                                       "default_tile": "%dx%d" % (default_how.tile_rows, default_how.tile_cols),
                                       "default_k_splits": default_how.k_splits} if default_us else {}),
+                                  **({"candidates_us": [["tiled" if c_.tiled else "decode" if c_.tile_rows == 16 else "stream",
+                                                         "%dx%d" % (c_.tile_rows, c_.tile_cols), c_.k_splits, c_.k_waves, t_]
+                                                        for c_, t_ in cand_us]} if args.tune_replay else {}),
                                   **({"library_us_per_call": lib_us, "vs_library": us / lib_us} if lib_us else {})}),
                       flush=True)
         del W

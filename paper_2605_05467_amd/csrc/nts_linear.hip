@@ -753,7 +753,7 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
     // The decode kernel against the best of the above.  Its estimate: a wavefront alone streams
     // about 10 GB/s of weights, a compute unit at most 26, less 0.4 per batch row (every
     // wavefront fetches the batch rows of its own K range); the chip at most 6.1 TB/s; a launch 2.5, every round of workgroups 1, short
-    // K ranges pay for their pipeline fill, and wide batches 0.08 per row.
+    // K ranges pay for their pipeline fill, and wide batches 0.05 per row.
     const double bytes = double(Nn) * K * 2.;
     double best_dec = 0.;
     int dec_ks = 0, dec_rb = 0, dec_splits = 0;
@@ -766,7 +766,7 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
                 if (spw < 4) continue;
                 if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) continue;
                 const int64_t wgs = int64_t((Nn + 16 * rb - 1) / (16 * rb)) * splits;
-                if (wgs > 384) continue;        // measured: with more than 1.5 workgroups per compute unit the
+                if (wgs > 512) continue;        // measured: with more than two workgroups per compute unit the
                                                 // streaming kernel's larger blocks do better than this estimate
                 const int per_cu = 12 / ks;                                 // workgroups a compute unit holds
                 const int64_t rounds = (wgs + 256 * per_cu - 1) / (256 * per_cu);
@@ -777,7 +777,7 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
                 if (wg_cu > 1 && rate > 22.) rate = 22.;    // measured: two small workgroups stream less than one of twice the rows
                 double stream_us = bytes / double(wgs) * double(wg_cu) / (rate * 1e3);
                 if (stream_us < hbm_us) stream_us = hbm_us;
-                double t = 2.5 + 1.0 * double(rounds) + stream_us + 0.08 * M + (spw < 16 ? 0.25 * (16 - spw) : 0.);
+                double t = 2.5 + 1.0 * double(rounds) + stream_us + 0.05 * M + (spw < 16 ? 0.08 * (16 - spw) : 0.);
                 if (splits > 1) t += 2.5 + out_elems * splits * 8. / 4.0e6;
                 if (dec_ks == 0 || t < best_dec) {
                     best_dec = t;

@@ -32,15 +32,20 @@ CASES = [
     (777, 7000, 256, 256, 128, False, 1),
     (200, 4104, 8320, 256, 128, True, 1),
     (520, 19000, 256, 256, 256, False, 1),
-    (1, 184, 1600, 16, 16, False, 2),
-    (3, 904, 11904, 16, 16, True, 2),
-    (7, 2104, 3392, 16, 16, False, 2),
+    (3, 104, 1600, 16, 16, False, 2),
+    (1, 184, 1600, 16, 16, False, 4),
+    (3, 944, 8192, 16, 16, True, 2),
+    (3, 904, 11904, 16, 16, True, 4),
+    (3, 584, 2048, 16, 16, False, 2),
+    (7, 2104, 3392, 16, 16, False, 4),
     (1, 904, 12352, 16, 16, True, 4),
     (17, 208, 2048, 32, 32, True, 1),
     (1, 4984, 3392, 16, 32, False, 4),
     (1, 1744, 16384, 16, 32, True, 4),
-    (5, 1264, 3392, 32, 32, True, 1),
-    (3, 1384, 7424, 32, 32, True, 1),
+    (1, 344, 3392, 32, 32, True, 1),
+    (5, 1264, 3392, 16, 16, False, 4),
+    (1, 224, 7424, 32, 32, True, 1),
+    (3, 1384, 7424, 16, 16, True, 4),
 ]
 
 # every (rows, cols, k_waves) the library instantiates
