@@ -766,8 +766,7 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
                 if (spw < 4) continue;
                 if (splits > 1 && out_elems * splits * 4 > double(int64_t(512) << 20)) continue;
                 const int64_t wgs = int64_t((Nn + 16 * rb - 1) / (16 * rb)) * splits;
-                if (wgs > 512) continue;        // measured: with more than two workgroups per compute unit the
-                                                // streaming kernel's larger blocks do better than this estimate
+                if (wgs > 4096) continue;
                 const int per_cu = 12 / ks;                                 // workgroups a compute unit holds
                 const int64_t rounds = (wgs + 256 * per_cu - 1) / (256 * per_cu);
                 const int64_t wg_cu = (wgs + 255) / 256;                    // workgroups of the busiest compute unit
@@ -789,7 +788,7 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K)
     // the lone-consumer variant's table entry was measured with weight blocks shared through the L2
     // by four batch tiles; with the single tile of a decode batch it runs about 12 % slower
     const double stream_t = c.mt == 1 && c.cw == 1 ? 1.12 * best_t : best_t;
-    if (dec_ks > 0 && best_dec < 0.95 * stream_t) {
+    if (dec_ks > 0 && best_dec < stream_t) {           // no margin: measured, the decode kernel wins more ties than it loses
         c.ks = dec_ks;
         c.rt = dec_rb;                                  // row blocks of 16 per wavefront
         c.splits = dec_splits;

@@ -42,7 +42,8 @@ CASES = [
     (17, 208, 2048, 32, 32, True, 1),
     (1, 4984, 3392, 16, 32, False, 4),
     (1, 1744, 16384, 16, 32, True, 4),
-    (1, 344, 3392, 32, 32, True, 1),
+    (1, 104, 4096, 32, 32, True, 1),
+    (1, 344, 3392, 16, 16, False, 4),
     (5, 1264, 3392, 16, 16, False, 4),
     (1, 224, 7424, 32, 32, True, 1),
     (3, 1384, 7424, 16, 16, True, 4),
