@@ -161,6 +161,38 @@ def draw_case(seed):
                 staging=staging, seed=seed)
 
 
+def draw_mid_case(seed):
+    """Like draw_case at a few thousand tokens and fragments of 256 B to 2 KiB: sizes at which a
+    launch has thousands of workgroups, wavefronts cover several small fragments, token counts are
+    odd (a wavefront may straddle two slabs) and chunks can exceed the kernels' workgroup groups."""
+    rng = SplitMix64(77000 + seed)
+    u = lambda lo, hi: int(rng.integers(lo, hi, 1)[0])
+    e = (1, 2, 2)[u(0, 2)]
+    D = (64, 128)[u(0, 1)]
+    L = u(2, 4)
+    tps = (1, 2, 4, 8)
+    Ns, Nd = tps[u(0, 3)], tps[u(0, 3)]
+    H = max(Ns, Nd) * (1, 2, 4, 8)[u(0, 3)]
+    rs = u(0, Ns - 1)
+    cands = [rd for rd in range(Nd) if orc.route(H, Ns, rs, Nd, rd)[2] > 0]
+    rd = cands[u(0, len(cands) - 1)]
+    p = (1, 1, 4, 16)[u(0, 3)]
+    n_req = u(3, 9)
+    ctx_len = rng.integers(300, 1500, n_req).astype(np.int32)
+    ctx_len[0] |= 1
+    ctx_len[-1] += 1 - int(ctx_len.sum()) % 2          # an odd total
+    n_pg = int(((ctx_len.astype(np.int64) + p - 1) // p).sum())
+    pool_pages_s = n_pg + u(1, 400)
+    pool_pages_d = n_pg + u(0, 400)
+    src_pages = rng.permutation(pool_pages_s)[:n_pg].astype(np.int32)
+    dst_pages = rng.permutation(pool_pages_d)[:n_pg].astype(np.int32)
+    pad_s, pad_d = (0, 16)[u(0, 1)], (0, 32)[u(0, 1)]
+    staging = (0, (9 << 20) + 4 * u(1, 5000), (3 << 20) + 4 * u(1, 5000), 1 << 20)[u(0, 3)]
+    return dict(e=e, D=D, L=L, H=H, Ns=Ns, rs=rs, Nd=Nd, rd=rd, p=p, ctx_len=ctx_len, src_pages=src_pages,
+                dst_pages=dst_pages, S_src=pool_pages_s * p, S_dst=pool_pages_d * p, pad_s=pad_s, pad_d=pad_d,
+                staging=staging, seed=seed)
+
+
 def random_case_host(c, routed):
     """Host side of a drawn case: 2L separately allocated, row-padded arrays per
     pool, the oracle's slot lists, stream and expected destination.  ``routed``

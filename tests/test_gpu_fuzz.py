@@ -25,8 +25,19 @@ def env():
 
 @pytest.mark.parametrize("seed", range(N_CASES))
 def test_random_geometry(env, seed):
+    run_drawn_case(env, draw_case(seed), seed)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_geometry_at_a_few_thousand_tokens(env, seed):
+    """Drawn geometries at sizes where a launch has thousands of workgroups: fragments of 256 B to
+    2 KiB (several per wavefront), odd token counts, chunks of 1 to 64 MiB."""
+    from gpu_util import draw_mid_case
+    run_drawn_case(env, draw_mid_case(seed), seed)
+
+
+def run_drawn_case(env, c, seed):
     torch, b, ctx = env
-    c = draw_case(seed)
     h = random_case_host(c, b.nts_route(c["H"], c["Ns"], c["rs"], c["Nd"], c["rd"]))
     L, st_d, row_d, S_d = h["L"], h["st_d"], h["row_d"], h["S_d"]
     src_arr, dst_arr, sslot, dslot, stream_h, want = (h[k] for k in ("src_arr", "dst_arr", "sslot", "dslot",
