@@ -395,7 +395,9 @@ def linear_bench(args, torch, b):
                 lib_us = None
                 if args.library:
                     # the same shard through torch.matmul (hipBLASLt), replayed from a graph in the same way
-                    Wv = W[:, (tp - 1) * nn:tp * nn, :] if split == "out" else W[:, :, (tp - 1) * k:tp * k]
+                    # (the shard as the library's own view of the full matrix: offset, rows, columns, row stride)
+                    v_off, v_rows, v_cols, v_rs = b.nts_shard_linear_view(**kw)
+                    Wv = [torch.as_strided(W[i].reshape(-1), (v_rows, v_cols), (v_rs, 1), v_off) for i in range(copies)]
                     torch.matmul(X, Wv[0].t(), out=Y)
                     torch.cuda.synchronize()
                     lgraph = torch.cuda.CUDAGraph()

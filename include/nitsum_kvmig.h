@@ -362,6 +362,20 @@ typedef struct nts_linear_launch {
 } nts_linear_launch;
 
 int nts_shard_linear_launch(const nts_linear_desc *d, nts_linear_launch *out);
+
+/*
+ * The shard of a descriptor as a view into the full weight matrix (host
+ * arithmetic only).  A GPU keeps the whole matrix and every TP level works on
+ * its part of it in place (Sec. 3.2.1), so a shard is nothing but an element
+ * offset, a row count, a column count and the full matrix's row stride:
+ *   shard[i][k] = W_full[*elem_offset + i * *row_stride + k],  i < *rows, k < *cols
+ * (rows = output features of the shard, cols = its reduction length).  This is
+ * what nts_shard_linear computes with; a caller can hand the same view to a GEMM
+ * library, which on this GPU is the faster route for prefill batches of a
+ * thousand rows and more.  Errors: NTS_EINVAL as for nts_shard_linear_workspace.
+ */
+int nts_shard_linear_view(const nts_linear_desc *d, int64_t *elem_offset, int64_t *rows, int64_t *cols,
+                          int64_t *row_stride);
 int nts_shard_linear(nts_ctx *ctx, const nts_linear_desc *d, const void *X, const void *W_full,
                      void *Y, void *workspace, size_t workspace_bytes, void *hip_stream);
 

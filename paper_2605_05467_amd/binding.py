@@ -46,7 +46,7 @@ EXPORTS = (
     "nts_run_pack", "nts_run_pack_chunk", "nts_run_unpack", "nts_run_unpack_chunk",
     "nts_run_migrate", "nts_run_migrate_batch", "nts_run_migrate_direct", "nts_run_memcpy_baseline",
     "nts_batch_staging_bytes", "nts_run_migrate_static",
-    "nts_shard_linear", "nts_shard_linear_workspace", "nts_shard_linear_launch",
+    "nts_shard_linear", "nts_shard_linear_workspace", "nts_shard_linear_launch", "nts_shard_linear_view",
     "nts_shard_linear_tune", "nts_shard_linear_tuned",
     "nts_shard_linear_candidates", "nts_shard_linear_with", "nts_shard_linear_remember",
     "nts_balanced_block", "nts_goodput_efficiency", "nts_plan_cluster",
@@ -128,6 +128,7 @@ _lib.nts_batch_staging_bytes.argtypes = [_i, _vp, ctypes.POINTER(_i64)]
 _lib.nts_run_memcpy_baseline.argtypes = [_vp, _vp, _vp, _i, _vp, ctypes.POINTER(_i64)]
 _lib.nts_shard_linear_workspace.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(ctypes.c_size_t)]
 _lib.nts_shard_linear_launch.argtypes = [ctypes.POINTER(nts_linear_desc), ctypes.POINTER(nts_linear_launch)]
+_lib.nts_shard_linear_view.argtypes = [ctypes.POINTER(nts_linear_desc)] + [ctypes.POINTER(ctypes.c_int64)] * 4
 _lib.nts_shard_linear.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.nts_shard_linear_tune.argtypes = [_vp, ctypes.POINTER(nts_linear_desc), _vp, _vp, _i, _vp, _vp, ctypes.c_size_t, _vp,
                                        ctypes.POINTER(nts_linear_launch)]
@@ -331,6 +332,17 @@ def nts_shard_linear_launch(*, M: int, n_out: int, n_in: int, tp: int, rank: int
     if st != NTS_OK:
         raise NtsError(st, "nts_shard_linear_launch")
     return out
+
+
+def nts_shard_linear_view(*, M: int, n_out: int, n_in: int, tp: int, rank: int, split: int,
+                          ldx: int = 0, ldw: int = 0, ldy: int = 0, dtype: int = 0):
+    """(elem_offset, rows, cols, row_stride) of the shard inside the full weight matrix."""
+    d = _linear_desc(M, n_out, n_in, tp, rank, split, ldx, ldw, ldy, dtype)
+    v = [ctypes.c_int64(0) for _ in range(4)]
+    st = _lib.nts_shard_linear_view(ctypes.byref(d), *[ctypes.byref(x) for x in v])
+    if st != NTS_OK:
+        raise NtsError(st, "nts_shard_linear_view")
+    return tuple(x.value for x in v)
 
 
 def nts_shard_linear(ctx: int, X: int, W_full: int, Y: int, *, M: int, n_out: int, n_in: int, tp: int,

@@ -930,6 +930,18 @@ int nts_shard_linear_launch(const nts_linear_desc *d, nts_linear_launch *out)
     return NTS_OK;
 }
 
+int nts_shard_linear_view(const nts_linear_desc *d, int64_t *elem_offset, int64_t *rows, int64_t *cols,
+                          int64_t *row_stride)
+{
+    LinearGeom g;
+    if (!elem_offset || !rows || !cols || !row_stride || linear_geom(d, &g) != NTS_OK) return NTS_EINVAL;
+    *elem_offset = g.a_off;
+    *rows = g.Nn;
+    *cols = g.K;
+    *row_stride = g.lda;
+    return NTS_OK;
+}
+
 int nts_shard_linear_tuned(const nts_ctx *ctx, const nts_linear_desc *d, nts_linear_launch *out)
 {
     LinearGeom g;

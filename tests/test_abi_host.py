@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from oracle import kvmig as orc
@@ -114,3 +115,28 @@ def test_linear_launch_query_reaches_every_kernel_variant(b):
     assert seen == VARIANTS
     with pytest.raises(b.NtsError):
         b.nts_shard_linear_launch(M=0, n_out=64, n_in=64, tp=1, rank=0, split=b.NTS_SPLIT_OUT)
+
+
+def test_linear_shard_view_is_the_oracles_slice(b):
+    """nts_shard_linear_view names the shard as offset / rows / cols / row stride inside the
+    full matrix; read through that view, a matrix of distinct values must give exactly the
+    slice the oracle takes (rows r*n/N.. for an output split, columns for an input split)."""
+    from oracle import shard_linear as osl
+    for n_out, n_in, ldw in ((64, 128, 0), (256, 192, 200), (128, 512, 640)):
+        stride = ldw or n_in
+        flat = np.arange(n_out * stride, dtype=np.int64)
+        W = flat.reshape(n_out, stride)[:, :n_in]
+        for tp in (1, 2, 4, 8):
+            if n_out % (64 * tp) or n_in % (64 * tp):
+                continue
+            for rank in range(tp):
+                for sp, name in ((b.NTS_SPLIT_OUT, "out"), (b.NTS_SPLIT_IN, "in")):
+                    off, rows, cols, rs = b.nts_shard_linear_view(M=4, n_out=n_out, n_in=n_in, tp=tp, rank=rank,
+                                                                  split=sp, ldw=ldw)
+                    X = np.zeros((1, n_in if name == "out" else n_in // tp))
+                    want = osl._shard(X, W, tp, rank, name)
+                    assert (rows, cols) == want.shape and rs == stride
+                    got = flat[off + np.arange(rows)[:, None] * rs + np.arange(cols)[None, :]]
+                    assert np.array_equal(got, want), (n_out, n_in, ldw, tp, rank, name)
+    with pytest.raises(b.NtsError):
+        b.nts_shard_linear_view(M=4, n_out=64, n_in=64, tp=3, rank=0, split=b.NTS_SPLIT_OUT)

@@ -411,3 +411,28 @@ def test_every_candidate_configuration_computes_the_layer(env, M, n_out, n_in, t
         assert b.nts_shard_linear_tuned(ctx, **kw) is None
     finally:
         b.nts_free(ctx)
+
+
+@pytest.mark.parametrize("split", ["out", "in"])
+def test_shard_view_feeds_a_gemm_library(env, split):
+    """The view nts_shard_linear_view names is the shard itself: a library GEMM on that view of the
+    full, row-padded weight matrix gives the layer's result (integer inputs, so both are exact and
+    must agree bit for bit with the once-rounded oracle)."""
+    torch, b, ctx = env
+    M, n_out, n_in, tp, rank, pad = 48, 512, 768, 4, 2, 8
+    k = n_in if split == "out" else n_in // tp
+    nn = n_out // tp if split == "out" else n_out
+    Xh, Wh = linear_inputs_int(5, M, n_out, n_in, x_cols=k, dtype="bf16")
+    ldw = n_in + pad
+    Wp = np.zeros((n_out, ldw), np.uint16); Wp[:, :n_in] = Wh
+    Xd = torch.from_numpy(Xh.view(np.int16)).cuda().view(torch.bfloat16)
+    Wd = torch.from_numpy(Wp.view(np.int16)).cuda().view(torch.bfloat16)
+    sp = b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN
+    off, rows, cols, rs = b.nts_shard_linear_view(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=rank, split=sp, ldw=ldw)
+    assert (rows, cols, rs) == (nn, k, ldw)
+    view = torch.as_strided(Wd.reshape(-1), (rows, cols), (rs, 1), off)
+    Y = torch.matmul(Xd, view.t())
+    torch.cuda.synchronize()
+    want, _ = osl.shard_linear(osl.bf16_to_f64(Xh), osl.bf16_to_f64(Wh), tp, rank, split)
+    got = Y.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, osl.round_to_bits(want, "bf16"))
