@@ -397,7 +397,8 @@ def linear_bench(args, torch, b):
                     # the same shard through torch.matmul (hipBLASLt), replayed from a graph in the same way
                     # (the shard as the library's own view of the full matrix: offset, rows, columns, row stride)
                     v_off, v_rows, v_cols, v_rs = b.nts_shard_linear_view(**kw)
-                    Wv = [torch.as_strided(W[i].reshape(-1), (v_rows, v_cols), (v_rs, 1), v_off) for i in range(copies)]
+                    # (as_strided takes the offset from the start of the storage, so each copy's own offset is added)
+                    Wv = [torch.as_strided(W, (v_rows, v_cols), (v_rs, 1), W[i].storage_offset() + v_off) for i in range(copies)]
                     torch.matmul(X, Wv[0].t(), out=Y)
                     torch.cuda.synchronize()
                     lgraph = torch.cuda.CUDAGraph()

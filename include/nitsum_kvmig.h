@@ -351,8 +351,8 @@ int nts_shard_linear_workspace(const nts_linear_desc *d, size_t *bytes);
  * that must reach every kernel variant.  Errors: NTS_EINVAL as above.
  */
 typedef struct nts_linear_launch {
-    int32_t tiled;       /* 1: 256 x 256 matrix-core tiles; 0: weight-streaming kernel, or, with
-                            tile_rows == 16, the decode kernel */
+    int32_t tiled;       /* 1: matrix-core tiles of 256 batch rows by tile_cols (256 or 128) outputs;
+                            0: weight-streaming kernel, or, with tile_rows == 16, the decode kernel */
     int32_t tile_rows;   /* batch rows per workgroup */
     int32_t tile_cols;   /* output columns (weight rows) per workgroup */
     int32_t k_splits;    /* parts the reduction is cut into; > 1 uses the workspace */

@@ -728,7 +728,7 @@ namespace {
 struct LinearGeom {
     int M, Nn, K;
     int64_t ldx, lda, ldy, a_off;   // a_off: element offset of the shard inside W
-    bool tiled;                      // 256 x 256 tiled kernel, else the weight-streaming kernel
+    int tiled;                       // tile width of the tiled kernel (256 or 128), 0: the streaming / decode kernels
     NtsStreamCfg cfg;                // streaming kernel: tile, prefetch depth, K splits
 };
 
@@ -759,7 +759,7 @@ int linear_geom(const nts_linear_desc *d, LinearGeom *g)
     // the tiled kernel addresses the 256 rows of a tile with 32-bit byte offsets from the tile's first row
     const int64_t lim = int64_t(1) << 23;
     if (g->ldx >= lim || g->lda >= lim || g->ldy >= lim) return NTS_EINVAL;
-    g->tiled = nts_linear_use_tiled(g->M, g->Nn);
+    g->tiled = nts_linear_use_tiled(g->M, g->Nn, g->K);
     g->cfg = nts_linear_stream_config(g->M, g->Nn, g->K);
     if (g->tiled) g->cfg.splits = 1;
     return NTS_OK;
@@ -780,7 +780,7 @@ static void describe_launch(const LinearGeom &g, nts_linear_launch *out)
     out->tiled = g.tiled ? 1 : 0;
     const bool decode = !g.tiled && g.cfg.ks > 0;
     out->tile_rows = g.tiled ? 256 : decode ? 16 : 32 * g.cfg.mt;
-    out->tile_cols = g.tiled ? 256 : decode ? 16 * g.cfg.rt : 32 * g.cfg.cw * g.cfg.rt;
+    out->tile_cols = g.tiled ? g.tiled : decode ? 16 * g.cfg.rt : 32 * g.cfg.cw * g.cfg.rt;
     out->k_splits = g.cfg.splits;
     out->slabs_ahead = g.tiled ? 2 : g.cfg.nsets - 1;
     out->k_waves = decode ? g.cfg.ks : 1;
@@ -815,7 +815,7 @@ static hipError_t launch_linear(const LinearGeom &g, int dtype, const void *X, c
                                         g.ldy, static_cast<float *>(workspace), g.cfg, g.M, g.Nn, g.K,
                                         dtype == NTS_F16, st);
     return nts_launch_linear_tiled(static_cast<const uint16_t *>(X), g.ldx, A, g.lda, static_cast<uint16_t *>(Y),
-                                   g.ldy, g.M, g.Nn, g.K, dtype == NTS_F16, st);
+                                   g.ldy, g.M, g.Nn, g.K, g.tiled, dtype == NTS_F16, st);
 }
 
 static int check_linear_operands(nts_ctx *ctx, const void *X, const void *W_full, const void *Y)
@@ -836,8 +836,9 @@ static bool launch_to_geom(const nts_linear_launch *how, LinearGeom *g)
     c.splits = how->k_splits;
     if (c.splits < 1 || c.splits > 32) return false;
     if (how->tiled) {
-        if (how->tile_rows != 256 || how->tile_cols != 256 || c.splits != 1) return false;
-        g->tiled = true;
+        if (how->tile_rows != 256 || (how->tile_cols != 256 && how->tile_cols != 128) || c.splits != 1) return false;
+        if (g->M < 256) return false;                    // as in the default choice: a whole batch tile at least
+        g->tiled = how->tile_cols;
         g->cfg.splits = 1;
         return true;
     }
@@ -862,7 +863,7 @@ static bool launch_to_geom(const nts_linear_launch *how, LinearGeom *g)
         for (const auto &v : inst) ok = ok || (v[0] == c.mt && v[1] == c.cw && v[2] == c.nsets);
         if (!ok) return false;
     }
-    g->tiled = false;
+    g->tiled = 0;
     g->cfg = c;
     return true;
 }

@@ -36,7 +36,7 @@ struct nts_ctx {
     std::string err;
     // configurations nts_shard_linear_tune found fastest, by (M, shard rows, reduction length, format)
     struct TunedLinear {
-        bool tiled;
+        int tiled;      // tile width of the tiled kernel (256 or 128), 0: streaming / decode kernel
         int mt, cw, rt, nsets, splits, ks;
     };
     std::map<std::tuple<int, int, int, int>, TunedLinear> tuned_linear;
@@ -149,10 +149,10 @@ struct NtsStreamCfg {
     int ks = 0;       // > 0: the decode kernel (16 weight rows per workgroup, ks wavefronts sharing K) instead
 };
 NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K);
-bool nts_linear_use_tiled(int M, int Nn);
+int nts_linear_use_tiled(int M, int Nn, int K);   // tile width of the tiled kernel, 0: not tiled
 // one way of running a problem: the tiled kernel, or the streaming / decode kernel with `cfg`
 struct NtsLinearCand {
-    bool tiled = false;
+    int tiled = 0;          // tile width of the tiled kernel (256 or 128), 0: streaming / decode kernel
     NtsStreamCfg cfg;
     double est_us = 0.;
 };
@@ -161,4 +161,5 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
                                     int64_t ldy, float *part, const NtsStreamCfg &c, int M, int Nn, int K,
                                     bool f16, hipStream_t st);
 hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
-                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, bool f16, hipStream_t st);
+                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, int tile_cols, bool f16,
+                                   hipStream_t st);

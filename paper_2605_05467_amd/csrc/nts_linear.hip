@@ -423,39 +423,43 @@ __global__ __launch_bounds__(64 * KS) void nts_linear_decode_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Large batches (M > 64, prefill): bound by the matrix cores.  A 256-thread
-// workgroup computes a 256 x 256 tile of Y; each of its four wavefronts owns a
-// 128 x 128 quadrant as 4 x 4 tiles of v_mfma_f32_32x32x16_bf16 (256 fp32
-// accumulators per lane, one wavefront per SIMD).  X and weight rows are both
-// contiguous along k, so both operands are staged the same way: 64-wide k
-// slabs go global -> registers -> LDS (row pitch 144 B, which spreads the 32
-// rows a ds_read_b128 touches over all banks).  LDS holds two slabs: while the
-// MFMAs of slab s read one buffer, slab s+1 is written into the other and the
-// global loads of slab s+2 are in flight; one barrier per slab.
-constexpr int kTileM = 256, kTileN = 256, kTileK = 64;
+// Large batches (prefill): bound by the matrix cores.  A 256-thread workgroup computes a
+// 256 x 64*NB tile of Y (NB = 4: 256 x 256; NB = 2: 256 x 128); each of its four wavefronts
+// owns a 128 x 32*NB part as 4 x NB tiles of v_mfma_f32_32x32x16 (64*NB fp32 accumulators per
+// lane, one wavefront per SIMD).  X and weight rows are both contiguous along k, so both
+// operands are staged the same way: 64-wide k slabs go global -> registers -> LDS (row pitch
+// 144 B, which spreads the 32 rows a ds_read_b128 touches over all banks).  LDS holds two
+// slabs: while the MFMAs of slab s read one buffer, slab s+1 is written into the other and the
+// global loads of slab s+2 are in flight; one barrier per slab.  The narrower tile reads 1.5 x
+// the LDS bytes per MFMA and reaches 0.87 of the wide tile's rate per compute unit; it is for
+// outputs whose 256 x 256 tiling leaves the last round of workgroups half empty or fills too
+// few compute units (measured: 6144 outputs at M = 4096, 384 wide tiles in 1.5 rounds, 210 us;
+// 768 narrow tiles in 3 rounds, 178 us).
+constexpr int kTileM = 256, kTileK = 64;                // tile height and slab depth; the width is 64 * NB
 constexpr int kSupM = 4, kSupN = 8;                     // tiles per XCD-resident block
 constexpr int kPitch = kTileK * 2 + 16;                 // bytes per LDS row
-constexpr int kTileLds = (kTileM + kTileN) * kPitch;    // 73728 B per buffer, two buffers of dynamic LDS
 
-template <class E>
+template <class E, int NB>
 __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
     uint16_t *__restrict__ Y, int64_t ldy, int M, int Nn, int K)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr int kTN = 64 * NB;                        // tile width: two wavefronts of NB 32-wide tiles
+    constexpr int kLdsN = (kTileM + kTN) * kPitch;      // bytes per LDS buffer
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv >> 1, wn = wv & 1;                // quadrant of this wavefront
     // Workgroup -> tile.  Consecutive workgroup ids go to the 8 XCDs in turn and each XCD has
     // its own L2, so the 32 workgroups that run together on one XCD are given a 4 x 8 block of
     // tiles: every X slab is then fetched into that L2 once for 8 tiles and every weight slab
     // once for 4, instead of each workgroup streaming a weight tile of its own.
-    const int tiles_m = (M + kTileM - 1) / kTileM, tiles_n = (Nn + kTileN - 1) / kTileN;
+    const int tiles_m = (M + kTileM - 1) / kTileM, tiles_n = (Nn + kTN - 1) / kTN;
     const int sup_n = (tiles_n + kSupN - 1) / kSupN;
     const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
     const int sup = (seq / (kSupM * kSupN)) * 8 + xcd, in_sup = seq % (kSupM * kSupN);
     const int tm = (sup / sup_n) * kSupM + in_sup / kSupN, tn = (sup % sup_n) * kSupN + in_sup % kSupN;
     if (tm >= tiles_m || tn >= tiles_n) return;         // whole workgroup leaves before any barrier
-    const int m0 = tm * kTileM, n0 = tn * kTileN;
+    const int m0 = tm * kTileM, n0 = tn * kTN;
 
     // staging map: 256 rows x 8 vectors of 16 B per operand and slab; thread t takes
     // vector (t & 7) of rows (t >> 3) + 32 * q, q = 0..7: eight lanes read one 128 B line.
@@ -463,22 +467,27 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     // 32-bit byte offset per lane that never changes (row inside the tile times the row
     // stride), so the slab loop spends no vector instructions on addresses.
     const int sv = tid & 7, sr = tid >> 3;
-    uint32_t xo[8], ao[8];
+    constexpr int NA = 2 * NB;                          // 32-row passes of the weight operand
+    uint32_t xo[8], ao[NA];
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
         const int r = sr + 32 * q;
         xo[q] = uint32_t(min(m0 + r, M - 1) - m0) * uint32_t(ldx * 2) + uint32_t(sv * 16);
+    }
+#pragma unroll
+    for (int q = 0; q < NA; ++q) {
+        const int r = sr + 32 * q;
         ao[q] = uint32_t(min(n0 + r, Nn - 1) - n0) * uint32_t(lda * 2) + uint32_t(sv * 16);
     }
     const char *xt = reinterpret_cast<const char *>(X) + int64_t(m0) * ldx * 2;
     const char *at = reinterpret_cast<const char *>(A) + int64_t(n0) * lda * 2;
 #define NTS_GLOAD(base, o) (*reinterpret_cast<const u32x4 *>((base) + (o)))
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][NB];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
@@ -488,105 +497,106 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 
     // prologue: slab 0 into LDS buffer 0, slab 1 into registers; both slabs' loads are issued
     // before the first wait, so the tile starts after one memory latency, not two
-    u32x4 xr[8], ar[8];
+    u32x4 xr[8], ar[NA];
     {
-        u32x4 x0[8], a0[8];
+        u32x4 x0[8], a0[NA];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            x0[q] = NTS_GLOAD(xt, xo[q]);
-            a0[q] = NTS_GLOAD(at, ao[q]);
-        }
+        for (int q = 0; q < 8; ++q) x0[q] = NTS_GLOAD(xt, xo[q]);
+#pragma unroll
+        for (int q = 0; q < NA; ++q) a0[q] = NTS_GLOAD(at, ao[q]);
         const int64_t off = int64_t(min(1, n_slabs - 1)) * (kTileK * 2);
         const char *xg = xt + off, *ag = at + off;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            xr[q] = NTS_GLOAD(xg, xo[q]);
-            ar[q] = NTS_GLOAD(ag, ao[q]);
-        }
+        for (int q = 0; q < 8; ++q) xr[q] = NTS_GLOAD(xg, xo[q]);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            *reinterpret_cast<u32x4 *>(lds + st_off + 32 * q * kPitch) = x0[q];
-            *reinterpret_cast<u32x4 *>(lds + kTileM * kPitch + st_off + 32 * q * kPitch) = a0[q];
-        }
+        for (int q = 0; q < NA; ++q) ar[q] = NTS_GLOAD(ag, ao[q]);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) *reinterpret_cast<u32x4 *>(lds + st_off + 32 * q * kPitch) = x0[q];
+#pragma unroll
+        for (int q = 0; q < NA; ++q) *reinterpret_cast<u32x4 *>(lds + kTileM * kPitch + st_off + 32 * q * kPitch) = a0[q];
     }
     nts_lds_barrier();
 
-    // Two fragment sets: while the 16 MFMAs of k step kk run on one set, the eight fragments of
+    // Two fragment sets: while the 4*NB MFMAs of k step kk run on one set, the 4+NB fragments of
     // step kk+1 are read from LDS into the other, one read every STRIDE MFMAs and in the order
-    // the next step consumes them (A0 B0 B1 B2 B3 A1 A2 A3).  A wavefront issues in order and
-    // can have only 15 LDS operations outstanding (4-bit counter), so everything that goes
-    // through LDS is spread between the MFMAs instead of issued in bursts: the 16 stores of
+    // the next step consumes them (X0, the weight fragments, X1 X2 X3).  A wavefront issues in
+    // order and can have only 15 LDS operations outstanding (4-bit counter), so everything that
+    // goes through LDS is spread between the MFMAs instead of issued in bursts: the stores of
     // slab s+1 (in registers since the previous slab) and, right behind each store, the global
-    // load of slab s+2 into the same register, one pair per three MFMAs over the first three k
+    // load of slab s+2 into the same register, one pair per PAIR MFMAs over the first three k
     // steps.  sched_barrier pins this order; left alone the compiler serialises read - wait -
-    // MFMA.  Over a slab the LDS is about three quarters busy, evenly.
+    // MFMA.  With NB = 4 the LDS is about three quarters busy over a slab, evenly.
+    // One barrier per slab, before the last k step: by then every wavefront has read all of
+    // slab s (so slab s+2 may overwrite its buffer from the next iteration on) and has written
+    // its part of slab s+1 (so the first fragments of slab s+1 can be read during the last k
+    // step).  The reads of the last k step are issued back to back in the step before it, so
+    // the barrier's wait for LDS is short.  Nothing in the loop is conditional: past the end
+    // the loads repeat the last slab and the spare buffer takes the copy.  Two slabs per trip,
+    // so each slab's LDS buffer is a constant and fragment reads and stores carry their whole
+    // address in the instruction's offset field from a few per-lane bases.
+    constexpr int NF = 4 + NB;                          // fragments per k step
+    constexpr int NM = 4 * NB;                          // MFMAs per k step
+    constexpr int NS = 8 + NA;                          // staged vectors per thread and slab
+    constexpr int PAIR = (3 * NM) / NS;                 // MFMA slots per store/load pair (first three k steps)
 #define NTS_READ_FRAG(base, kk, r, XF, AF)                                                             \
     {                                                                                                  \
-        if ((r) == 0 || (r) >= 5) {                                                                    \
-            const int a_ = (r) == 0 ? 0 : (r) - 4;                                                     \
+        if ((r) == 0 || (r) > NB) {                                                                    \
+            const int a_ = (r) == 0 ? 0 : (r) - NB;                                                    \
             XF[a_] = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(                      \
                 (base) + (wm * 128 + a_ * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));              \
         } else {                                                                                       \
             const int b_ = (r) - 1;                                                                    \
             AF[b_] = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(                      \
-                (base) + (kTileM + wn * 128 + b_ * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));     \
+                (base) + (kTileM + wn * 32 * NB + b_ * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2)); \
         }                                                                                              \
     }
+    // staged vector i of a slab: X and weight vectors alternate while there are weight vectors left
 #define NTS_STORE_ONE(i)                                                                               \
     {                                                                                                  \
-        if ((i) & 1) *reinterpret_cast<u32x4 *>(nx + kTileM * kPitch + st_off + 32 * ((i) >> 1) * kPitch) = ar[(i) >> 1]; \
-        else *reinterpret_cast<u32x4 *>(nx + st_off + 32 * ((i) >> 1) * kPitch) = xr[(i) >> 1];         \
+        if ((i) < 2 * NA && ((i) & 1)) *reinterpret_cast<u32x4 *>(nx + kTileM * kPitch + st_off + 32 * ((i) >> 1) * kPitch) = ar[(i) >> 1]; \
+        else { const int q_ = (i) < 2 * NA ? (i) >> 1 : (i) - NA;                                      \
+               *reinterpret_cast<u32x4 *>(nx + st_off + 32 * q_ * kPitch) = xr[q_]; }                  \
     }
 #define NTS_LOAD_ONE(i)                                                                                \
     {                                                                                                  \
-        if ((i) & 1) ar[(i) >> 1] = NTS_GLOAD(ag, ao[(i) >> 1]);                                       \
-        else xr[(i) >> 1] = NTS_GLOAD(xg, xo[(i) >> 1]);                                               \
+        if ((i) < 2 * NA && ((i) & 1)) ar[(i) >> 1] = NTS_GLOAD(ag, ao[(i) >> 1]);                     \
+        else { const int q_ = (i) < 2 * NA ? (i) >> 1 : (i) - NA; xr[q_] = NTS_GLOAD(xg, xo[q_]); }    \
     }
-    // the 16 MFMAs of one k step on (XF, AF); G0 = slot number of the first one within the slab;
-    // fragment r of step NKK at NBASE goes into (NXF, NAF) after MFMA r * STRIDE
 #define NTS_KSTEP(XF, AF, G0, NBASE, NKK, NXF, NAF, STRIDE)                                            \
     {                                                                                                  \
         _Pragma("unroll") for (int a = 0; a < 4; ++a)                                                  \
-            _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                            \
-                const int i = a * 4 + b, g = (G0) + i;       /* constants after unrolling */           \
+            _Pragma("unroll") for (int b = 0; b < NB; ++b) {                                           \
+                const int i = a * NB + b, g = (G0) + i;      /* constants after unrolling */           \
                 acc[a][b] = E::mfma32(AF[b], XF[a], acc[a][b]);                                       \
-                if (i % (STRIDE) == 0 && i / (STRIDE) < 8) NTS_READ_FRAG(NBASE, NKK, i / (STRIDE), NXF, NAF) \
-                if (g % 3 == 0 && g / 3 < 16) NTS_STORE_ONE(g / 3)                                     \
-                if (g % 3 == 1 && g / 3 < 16) NTS_LOAD_ONE(g / 3)                                      \
+                if (i % (STRIDE) == 0 && i / (STRIDE) < NF) NTS_READ_FRAG(NBASE, NKK, i / (STRIDE), NXF, NAF) \
+                if (g % PAIR == 0 && g / PAIR < NS) NTS_STORE_ONE(g / PAIR)                            \
+                if (g % PAIR == 1 && g / PAIR < NS) NTS_LOAD_ONE(g / PAIR)                             \
                 __builtin_amdgcn_sched_barrier(0);                                                     \
             }                                                                                          \
     }
-
-    // One barrier per slab, before the last k step: by then every wavefront has read all of
-    // slab s (so slab s+2 may overwrite its buffer from the next iteration on) and has written
-    // its part of slab s+1 (so the first fragments of slab s+1 can be read during the last k
-    // step).  The reads of the last k step are issued in the first half of the step before it,
-    // so the barrier's wait for LDS is short.  Nothing in the loop is conditional: past the end
-    // the loads repeat the last slab and the spare buffer takes the copy.
     typedef typename E::vec8 vec8;
-    vec8 xf0[4], af0[4], xf1[4], af1[4];
+    vec8 xf0[4], af0[NB], xf1[4], af1[NB];
 #pragma unroll
-    for (int r = 0; r < 8; ++r) NTS_READ_FRAG(lds, 0, r, xf0, af0)
-    // Two slabs per trip, so each slab's LDS buffer is a constant: fragment reads and stores then
-    // carry their whole address in the instruction's offset field from a few per-lane bases.
+    for (int r = 0; r < NF; ++r) NTS_READ_FRAG(lds, 0, r, xf0, af0)
+    constexpr int S2 = NM / NF >= 2 ? 2 : 1;            // fragment reads every other MFMA where there is room
 #define NTS_SLAB(XS, NX, S)                                                                            \
     {                                                                                                  \
         const unsigned char *xs = (XS);                                                                \
         unsigned char *nx = (NX);                                                                      \
         const int64_t off = int64_t(min((S) + 2, n_slabs - 1)) * (kTileK * 2);                         \
         const char *xg = xt + off, *ag = at + off;                                                     \
-        NTS_KSTEP(xf0, af0, 0, xs, 1, xf1, af1, 2)                                                     \
-        NTS_KSTEP(xf1, af1, 16, xs, 2, xf0, af0, 2)                                                    \
-        NTS_KSTEP(xf0, af0, 32, xs, 3, xf1, af1, 1)                                                    \
+        NTS_KSTEP(xf0, af0, 0, xs, 1, xf1, af1, S2)                                                    \
+        NTS_KSTEP(xf1, af1, NM, xs, 2, xf0, af0, S2)                                                   \
+        NTS_KSTEP(xf0, af0, 2 * NM, xs, 3, xf1, af1, 1)                                                \
         nts_lds_barrier();                                                                             \
-        NTS_KSTEP(xf1, af1, 48, nx, 0, xf0, af0, 2)                                                    \
+        NTS_KSTEP(xf1, af1, 3 * NM, nx, 0, xf0, af0, S2)                                               \
     }
     int s = 0;
     for (; s + 2 <= n_slabs; s += 2) {
-        NTS_SLAB(lds, lds + kTileLds, s)
-        NTS_SLAB(lds + kTileLds, lds, s + 1)
+        NTS_SLAB(lds, lds + kLdsN, s)
+        NTS_SLAB(lds + kLdsN, lds, s + 1)
     }
-    if (s < n_slabs) NTS_SLAB(lds, lds + kTileLds, s)
+    if (s < n_slabs) NTS_SLAB(lds, lds + kLdsN, s)
 #undef NTS_SLAB
 #undef NTS_GLOAD
 #undef NTS_READ_FRAG
@@ -596,19 +606,20 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     // Epilogue.  The weight fragment is the first MFMA operand, so D[i][j] has i = weight row,
     // j = batch row: lane (fr, fg) holds, of batch row fr of tile a, the output columns
     // (v/4)*8 + fg*4 + v%4 of tile b, four neighbours per group of v.  Stored from there a row
-    // would get 16 bytes per instruction; instead each wavefront rounds a 32 x 128 strip to 16
+    // would get 16 bytes per instruction; instead each wavefront rounds a 32 x 32*NB strip to 16
     // bits two values per instruction, puts it into its own piece of LDS 8 bytes per lane (row
-    // pitch 264 B: the 32 rows of a store fall into different banks) and writes whole 256-byte
+    // pitch 64*NB + 8 bytes: the 32 rows of a store fall into different banks) and writes whole
     // row segments, 16 bytes per lane.
     nts_lds_barrier();                                  // every wavefront is done with the tile buffers
     {
-        constexpr int kOutPitch = 128 * 2 + 8;          // bytes per strip row in LDS
+        constexpr int kOutPitch = 64 * NB + 8;          // bytes per strip row in LDS
+        constexpr int kLanesRow = 4 * NB, kRowsIns = 64 / kLanesRow;
         unsigned char *strip = lds + wv * 32 * kOutPitch;
-        const int orow = lane >> 4, ocol = (lane & 15) * 8;
+        const int orow = lane / kLanesRow, ocol = (lane % kLanesRow) * 8;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
+            for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const u32x2 pk = {E::round2(acc[a][b][4 * g], acc[a][b][4 * g + 1]),
@@ -617,12 +628,12 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
                 }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the strip is complete (LDS works in order)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int r = j * 4 + orow;
+            for (int j = 0; j < 32 / kRowsIns; ++j) {
+                const int r = j * kRowsIns + orow;
                 const u32x2 lo = *reinterpret_cast<const u32x2 *>(strip + r * kOutPitch + ocol * 2);
                 const u32x2 hi = *reinterpret_cast<const u32x2 *>(strip + r * kOutPitch + ocol * 2 + 8);
                 const u32x4 val = {lo[0], lo[1], hi[0], hi[1]};
-                const int m = m0 + wm * 128 + a * 32 + r, n = n0 + wn * 128 + ocol;
+                const int m = m0 + wm * 128 + a * 32 + r, n = n0 + wn * 32 * NB + ocol;
                 if (m < M) {
                     uint16_t *dst = Y + int64_t(m) * ldy + n;
                     if (n + 8 <= Nn) {
@@ -634,7 +645,7 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
                     }
                 }
             }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // strip read before it is overwritten
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
     }
 }
@@ -838,20 +849,36 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
     return hipGetLastError();
 }
 
-// The tiled kernel pays off once its 256 x 256 tiles occupy most of the chip (measured
-// break-even near 150 tiles); below that the streaming kernel (several batch tiles per weight
-// block, K splits) is faster.
-bool nts_linear_use_tiled(int M, int Nn)
+// Estimated time of the tiled kernel with tiles `cols` wide: rounds of 256 workgroups, each
+// round a fixed cost plus its slabs (measured per slab: 1.57 us for 256 x 256, 0.91 us for
+// 256 x 128).
+static double tiled_estimate_us(int M, int Nn, int K, int cols)
 {
-    const int64_t tiles = int64_t((M + kTileM - 1) / kTileM) * ((Nn + kTileN - 1) / kTileN);
-    return M > 256 && tiles >= 160;
+    const int64_t tiles = int64_t((M + kTileM - 1) / kTileM) * ((Nn + cols - 1) / cols);
+    const double per_round = cols == 256 ? 11. + 1.57 * (K / kTileK) : 8. + 0.91 * (K / kTileK);
+    return 2.5 + double((tiles + 255) / 256) * per_round;
+}
+
+// Tile width of the tiled kernel for a problem, 0 for the streaming kernel.  The tiled kernel
+// pays off once its tiles occupy most of the chip (measured break-even near 150 tiles of
+// 256 x 256, 160 of 256 x 128); below that the streaming kernel (several batch tiles per
+// weight block, K splits) is faster.  Between the two widths the round estimate decides: the
+// narrow tile does 13 % less per compute unit but wastes less of a ragged last round.
+int nts_linear_use_tiled(int M, int Nn, int K)
+{
+    if (M < 256) return 0;
+    const int64_t tm = (M + kTileM - 1) / kTileM;
+    const int64_t t256 = tm * ((Nn + 255) / 256), t128 = tm * ((Nn + 127) / 128);
+    const bool ok256 = M > 256 && t256 >= 160, ok128 = t128 >= 160;
+    if (ok256 && ok128) return tiled_estimate_us(M, Nn, K, 128) < 0.97 * tiled_estimate_us(M, Nn, K, 256) ? 128 : 256;
+    return ok256 ? 256 : ok128 ? 128 : 0;
 }
 
 // Every configuration that may be fastest for a problem, for nts_shard_linear_tune to time: the
 // streaming kernel's variants with each K split that is valid for them, the decode kernel's
 // (row blocks, wavefronts per K range, K split) combinations for M <= 16, and the tiled kernel
-// for M > 256.  Each gets the same estimate nts_linear_stream_config uses (the tiled kernel:
-// 11 us per round of tiles plus 1.57 us per slab); the list is cut to those within `slack` of
+// in both tile widths for M >= 256.  Each gets the same estimate nts_linear_stream_config uses
+// (the tiled kernel: tiled_estimate_us); the list is cut to those within `slack` of
 // the smallest estimate, sorted by estimate, at most `max_out`.  The configuration
 // nts_shard_linear uses by default is always first.
 int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out, int max_out)
@@ -863,7 +890,7 @@ int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out
     const double out_elems = double(M) * Nn;
     const double hbm_us = double(Nn) * K * 2. / 6.1e6;
     NtsLinearCand def;
-    def.tiled = nts_linear_use_tiled(M, Nn);
+    def.tiled = nts_linear_use_tiled(M, Nn, K);
     def.cfg = nts_linear_stream_config(M, Nn, K);
     if (def.tiled) def.cfg.splits = 1;
     def.est_us = 0.;
@@ -884,7 +911,7 @@ int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out
                        0.7 * double(rounds - seq_rounds);
             if (splits > 1) t += 2.5 + out_elems * splits * 8. / 4.0e6;
             NtsLinearCand c;
-            c.tiled = false;
+            c.tiled = 0;
             c.cfg.mt = v.mt;
             c.cfg.cw = v.cw;
             c.cfg.rt = 1;
@@ -916,10 +943,10 @@ int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out
                     if (wg_cu > 1 && rate > 22.) rate = 22.;
                     double stream_us = bytes / double(wgs) * double(wg_cu) / (rate * 1e3);
                     if (stream_us < hbm_us) stream_us = hbm_us;
-                    double t = 2.5 + 1.0 * double(rounds) + stream_us + 0.08 * M + (spw < 16 ? 0.25 * (16 - spw) : 0.);
+                    double t = 2.5 + 1.0 * double(rounds) + stream_us + 0.05 * M + (spw < 16 ? 0.08 * (16 - spw) : 0.);
                     if (splits > 1) t += 2.5 + out_elems * splits * 8. / 4.0e6;
                     NtsLinearCand c;
-                    c.tiled = false;
+                    c.tiled = 0;
                     c.cfg.mt = 1;
                     c.cfg.cw = 4;
                     c.cfg.ks = ks;
@@ -930,15 +957,15 @@ int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out
                     all.push_back(c);
                 }
     }
-    if (M > 256) {
-        const int64_t tiles = int64_t((M + kTileM - 1) / kTileM) * ((Nn + kTileN - 1) / kTileN);
-        NtsLinearCand c;
-        c.tiled = true;
-        c.cfg = def.cfg;
-        c.cfg.splits = 1;
-        c.est_us = 2.5 + double((tiles + 255) / 256) * (11. + 1.57 * n_slabs);
-        all.push_back(c);
-    }
+    if (M >= 256)
+        for (int cols = 256; cols >= 128; cols -= 128) {
+            NtsLinearCand c;
+            c.tiled = cols;
+            c.cfg = def.cfg;
+            c.cfg.splits = 1;
+            c.est_us = tiled_estimate_us(M, Nn, K, cols);
+            all.push_back(c);
+        }
     auto same = [](const NtsLinearCand &a, const NtsLinearCand &b) {
         if (a.tiled != b.tiled) return false;
         if (a.tiled) return true;
@@ -962,20 +989,28 @@ int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out
     return n;
 }
 
-hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
-                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, bool f16, hipStream_t st)
+template <class E, int NB>
+static hipError_t launch_tiled_one(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda, uint16_t *Y,
+                                   int64_t ldy, int M, int Nn, int K, hipStream_t st)
 {
-    static std::atomic<uint64_t> configured[2] = {{0}, {0}};
-    const hipError_t ea = allow_dynamic_lds(
-        configured[f16 ? 1 : 0],
-        f16 ? reinterpret_cast<const void *>(nts_linear_tiled_kernel<F16>)
-            : reinterpret_cast<const void *>(nts_linear_tiled_kernel<Bf16>),
-        2 * kTileLds);
+    constexpr int cols = 64 * NB, lds_bytes = 2 * (kTileM + cols) * kPitch;
+    static std::atomic<uint64_t> configured{0};
+    const hipError_t ea = allow_dynamic_lds(configured, reinterpret_cast<const void *>(nts_linear_tiled_kernel<E, NB>), lds_bytes);
     if (ea != hipSuccess) return ea;
-    const int tiles_m = (M + kTileM - 1) / kTileM, tiles_n = (Nn + kTileN - 1) / kTileN;
+    const int tiles_m = (M + kTileM - 1) / kTileM, tiles_n = (Nn + cols - 1) / cols;
     const int sups = ((tiles_m + kSupM - 1) / kSupM) * ((tiles_n + kSupN - 1) / kSupN);
     const dim3 grid(unsigned((sups + 7) / 8) * 8u * kSupM * kSupN), block(256);
-    if (f16) hipLaunchKernelGGL(nts_linear_tiled_kernel<F16>, grid, block, 2 * kTileLds, st, X, ldx, A, lda, Y, ldy, M, Nn, K);
-    else hipLaunchKernelGGL(nts_linear_tiled_kernel<Bf16>, grid, block, 2 * kTileLds, st, X, ldx, A, lda, Y, ldy, M, Nn, K);
+    hipLaunchKernelGGL((nts_linear_tiled_kernel<E, NB>), grid, block, lds_bytes, st, X, ldx, A, lda, Y, ldy, M, Nn, K);
     return hipGetLastError();
+}
+
+hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
+                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, int tile_cols, bool f16,
+                                   hipStream_t st)
+{
+    if (tile_cols == 128)
+        return f16 ? launch_tiled_one<F16, 2>(X, ldx, A, lda, Y, ldy, M, Nn, K, st)
+                   : launch_tiled_one<Bf16, 2>(X, ldx, A, lda, Y, ldy, M, Nn, K, st);
+    return f16 ? launch_tiled_one<F16, 4>(X, ldx, A, lda, Y, ldy, M, Nn, K, st)
+               : launch_tiled_one<Bf16, 4>(X, ldx, A, lda, Y, ldy, M, Nn, K, st);
 }

@@ -102,16 +102,16 @@ def test_linear_launch_query_reaches_every_kernel_variant(b):
     variant, and the query must agree with the workspace size."""
     from linear_cases import CASES, VARIANTS
     seen = set()
-    for M, Nn, K, rows, cols, is_split, k_waves in CASES:
+    for M, Nn, K, rows, cols, is_split, k_waves, tiled in CASES:
         for sp, n_out, n_in in ((b.NTS_SPLIT_OUT, 2 * Nn, K), (b.NTS_SPLIT_IN, Nn, 2 * K)):
             kw = dict(M=M, n_out=n_out, n_in=n_in, tp=2, rank=1, split=sp)
             l = b.nts_shard_linear_launch(**kw)
             assert (l.tile_rows, l.tile_cols, l.k_splits > 1, l.k_waves) == (rows, cols, is_split, k_waves), (M, Nn, K)
-            assert l.tiled == int((rows, cols) == (256, 256))
+            assert l.tiled == int(tiled), (M, Nn, K)
             ws = b.nts_shard_linear_workspace(**kw)
             assert ws == (l.k_splits * M * Nn * 4 if l.k_splits > 1 else 0)
             assert 1 <= l.slabs_ahead <= 7
-            seen.add((l.tile_rows, l.tile_cols, l.k_waves))
+            seen.add((l.tile_rows, l.tile_cols, l.k_waves, bool(l.tiled)))
     assert seen == VARIANTS
     with pytest.raises(b.NtsError):
         b.nts_shard_linear_launch(M=0, n_out=64, n_in=64, tp=1, rank=0, split=b.NTS_SPLIT_OUT)

@@ -118,7 +118,7 @@ def test_large_batches_tile_edges(env, M, split):
     run_case(env, M, 1024, 2048, 4, 3, split, seed=M + 200)
 
 
-@pytest.mark.parametrize("case", CASES, ids=lambda c: "M%d_N%d_K%d_tile%dx%d%s_kw%d" % (c[:5] + ("_split" if c[5] else "", c[6])))
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "M%d_N%d_K%d_%s%dx%d%s_kw%d" % (c[:3] + ("tiled" if c[7] else "tile",) + c[3:5] + ("_split" if c[5] else "", c[6])))
 @pytest.mark.parametrize("split", ["out", "in"])
 def test_every_kernel_variant(env, case, split):
     """One shard shape per instantiated kernel variant (tile height x workgroup
@@ -127,13 +127,13 @@ def test_every_kernel_variant(env, case, split):
     TP level 2 from a full matrix twice the shard, as rank 1; the variant each
     shape reaches is pinned by the CPU suite."""
     torch, b, ctx = env
-    M, Nn, K, rows, cols, is_split, k_waves = case
+    M, Nn, K, rows, cols, is_split, k_waves, tiled = case
     n_out, n_in = (2 * Nn, K) if split == "out" else (Nn, 2 * K)
     sp = b.NTS_SPLIT_OUT if split == "out" else b.NTS_SPLIT_IN
     pad = 8 if M % 2 else 0
     l = b.nts_shard_linear_launch(M=M, n_out=n_out, n_in=n_in, tp=2, rank=1, split=sp, ldx=K + pad,
                                   ldw=n_in + pad, ldy=Nn + pad)
-    assert (l.tile_rows, l.tile_cols, l.k_splits > 1, l.k_waves) == (rows, cols, is_split, k_waves)
+    assert (l.tile_rows, l.tile_cols, l.k_splits > 1, l.k_waves, bool(l.tiled)) == (rows, cols, is_split, k_waves, tiled)
     run_case(env, M, n_out, n_in, 2, 1, split, seed=M + Nn, pad=pad,
              dtype="f16" if (M + Nn // 8) % 3 == 0 else "bf16")
     # and bit-exact on integer inputs, in both element formats
