@@ -729,6 +729,7 @@ struct LinearGeom {
     int M, Nn, K;
     int64_t ldx, lda, ldy, a_off;   // a_off: element offset of the shard inside W
     int tiled;                       // tile width of the tiled kernel (256 or 128), 0: the streaming / decode kernels
+    int tiled_rows;                  // its tile height (256 or 128)
     NtsStreamCfg cfg;                // streaming kernel: tile, prefetch depth, K splits
 };
 
@@ -759,7 +760,7 @@ int linear_geom(const nts_linear_desc *d, LinearGeom *g)
     // the tiled kernel addresses the 256 rows of a tile with 32-bit byte offsets from the tile's first row
     const int64_t lim = int64_t(1) << 23;
     if (g->ldx >= lim || g->lda >= lim || g->ldy >= lim) return NTS_EINVAL;
-    g->tiled = nts_linear_use_tiled(g->M, g->Nn, g->K);
+    g->tiled = nts_linear_use_tiled(g->M, g->Nn, g->K, &g->tiled_rows);
     g->cfg = nts_linear_stream_config(g->M, g->Nn, g->K);
     if (g->tiled) g->cfg.splits = 1;
     return NTS_OK;
@@ -779,7 +780,7 @@ static void describe_launch(const LinearGeom &g, nts_linear_launch *out)
     *out = nts_linear_launch{};
     out->tiled = g.tiled ? 1 : 0;
     const bool decode = !g.tiled && g.cfg.ks > 0;
-    out->tile_rows = g.tiled ? 256 : decode ? 16 : 32 * g.cfg.mt;
+    out->tile_rows = g.tiled ? g.tiled_rows : decode ? 16 : 32 * g.cfg.mt;
     out->tile_cols = g.tiled ? g.tiled : decode ? 16 * g.cfg.rt : 32 * g.cfg.cw * g.cfg.rt;
     out->k_splits = g.cfg.splits;
     out->slabs_ahead = g.tiled ? 2 : g.cfg.nsets - 1;
@@ -800,6 +801,7 @@ static void apply_tuned(const nts_ctx *ctx, int dtype, size_t workspace_bytes, b
     const nts_ctx::TunedLinear &t = it->second;
     LinearGeom h = *g;
     h.tiled = t.tiled;
+    h.tiled_rows = t.tiled_rows;
     h.cfg.mt = t.mt; h.cfg.cw = t.cw; h.cfg.rt = t.rt; h.cfg.nsets = t.nsets; h.cfg.splits = t.splits; h.cfg.ks = t.ks;
     const size_t need = linear_workspace_need(h);
     if (need && (!have_workspace || workspace_bytes < need)) return;
@@ -815,7 +817,7 @@ static hipError_t launch_linear(const LinearGeom &g, int dtype, const void *X, c
                                         g.ldy, static_cast<float *>(workspace), g.cfg, g.M, g.Nn, g.K,
                                         dtype == NTS_F16, st);
     return nts_launch_linear_tiled(static_cast<const uint16_t *>(X), g.ldx, A, g.lda, static_cast<uint16_t *>(Y),
-                                   g.ldy, g.M, g.Nn, g.K, g.tiled, dtype == NTS_F16, st);
+                                   g.ldy, g.M, g.Nn, g.K, g.tiled_rows, g.tiled, dtype == NTS_F16, st);
 }
 
 static int check_linear_operands(nts_ctx *ctx, const void *X, const void *W_full, const void *Y)
@@ -836,9 +838,12 @@ static bool launch_to_geom(const nts_linear_launch *how, LinearGeom *g)
     c.splits = how->k_splits;
     if (c.splits < 1 || c.splits > 32) return false;
     if (how->tiled) {
-        if (how->tile_rows != 256 || (how->tile_cols != 256 && how->tile_cols != 128) || c.splits != 1) return false;
-        if (g->M < 256) return false;                    // as in the default choice: a whole batch tile at least
+        const bool known = (how->tile_rows == 256 && (how->tile_cols == 256 || how->tile_cols == 128)) ||
+                           (how->tile_rows == 128 && how->tile_cols == 128);
+        if (!known || c.splits != 1) return false;
+        if (g->M < how->tile_rows) return false;         // as in the default choice: a whole batch tile at least
         g->tiled = how->tile_cols;
+        g->tiled_rows = how->tile_rows;
         g->cfg.splits = 1;
         return true;
     }
@@ -877,6 +882,7 @@ int nts_shard_linear_candidates(const nts_linear_desc *d, nts_linear_launch *out
     for (int i = 0; i < n; ++i) {
         LinearGeom h = g;
         h.tiled = cand[i].tiled;
+        h.tiled_rows = cand[i].tiled_rows;
         h.cfg = cand[i].cfg;
         describe_launch(h, &out[i]);
     }
@@ -914,6 +920,7 @@ int nts_shard_linear_remember(nts_ctx *ctx, const nts_linear_desc *d, const nts_
     if (!launch_to_geom(how, &g)) return fail(ctx, NTS_EINVAL, "no such kernel configuration for this problem");
     nts_ctx::TunedLinear t;
     t.tiled = g.tiled;
+    t.tiled_rows = g.tiled_rows;
     t.mt = g.cfg.mt; t.cw = g.cfg.cw; t.rt = g.cfg.rt; t.nsets = g.cfg.nsets; t.splits = g.cfg.splits; t.ks = g.cfg.ks;
     try {
         ctx->tuned_linear[key] = t;
@@ -1008,6 +1015,7 @@ int nts_shard_linear_tune(nts_ctx *ctx, const nts_linear_desc *d, const void *X,
     for (int i = 0; i < n && e == hipSuccess; ++i) {
         LinearGeom h = g;
         h.tiled = cand[i].tiled;
+        h.tiled_rows = cand[i].tiled_rows;
         h.cfg = cand[i].cfg;
         const size_t need = linear_workspace_need(h);
         if (need && (!ws_ok || workspace_bytes < need)) continue;       // does not fit the caller's workspace
@@ -1045,12 +1053,14 @@ int nts_shard_linear_tune(nts_ctx *ctx, const nts_linear_desc *d, const void *X,
     {
         LinearGeom h = g;
         h.tiled = cand[best].tiled;
+        h.tiled_rows = cand[best].tiled_rows;
         h.cfg = cand[best].cfg;
         NTS_HIP(ctx, launch_linear(h, d->dtype, X, W_list[0], Y, workspace, st));
         if (picked) describe_launch(h, picked);
     }
     nts_ctx::TunedLinear t;
     t.tiled = cand[best].tiled;
+    t.tiled_rows = cand[best].tiled_rows;
     t.mt = cand[best].cfg.mt; t.cw = cand[best].cfg.cw; t.rt = cand[best].cfg.rt; t.nsets = cand[best].cfg.nsets;
     t.splits = cand[best].cfg.splits; t.ks = cand[best].cfg.ks;
     try {

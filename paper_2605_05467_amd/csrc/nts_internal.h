@@ -37,6 +37,7 @@ struct nts_ctx {
     // configurations nts_shard_linear_tune found fastest, by (M, shard rows, reduction length, format)
     struct TunedLinear {
         int tiled;      // tile width of the tiled kernel (256 or 128), 0: streaming / decode kernel
+        int tiled_rows; // its tile height (256 or 128)
         int mt, cw, rt, nsets, splits, ks;
     };
     std::map<std::tuple<int, int, int, int>, TunedLinear> tuned_linear;
@@ -149,10 +150,11 @@ struct NtsStreamCfg {
     int ks = 0;       // > 0: the decode kernel (16 weight rows per workgroup, ks wavefronts sharing K) instead
 };
 NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K);
-int nts_linear_use_tiled(int M, int Nn, int K);   // tile width of the tiled kernel, 0: not tiled
+int nts_linear_use_tiled(int M, int Nn, int K, int *rows);   // tile width (and height) of the tiled kernel, 0: not tiled
 // one way of running a problem: the tiled kernel, or the streaming / decode kernel with `cfg`
 struct NtsLinearCand {
     int tiled = 0;          // tile width of the tiled kernel (256 or 128), 0: streaming / decode kernel
+    int tiled_rows = 256;   // its tile height (256 or 128)
     NtsStreamCfg cfg;
     double est_us = 0.;
 };
@@ -161,5 +163,5 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
                                     int64_t ldy, float *part, const NtsStreamCfg &c, int M, int Nn, int K,
                                     bool f16, hipStream_t st);
 hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
-                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, int tile_cols, bool f16,
-                                   hipStream_t st);
+                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, int tile_rows, int tile_cols,
+                                   bool f16, hipStream_t st);

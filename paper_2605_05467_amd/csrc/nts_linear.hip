@@ -424,53 +424,57 @@ __global__ __launch_bounds__(64 * KS) void nts_linear_decode_kernel(
 
 // ---------------------------------------------------------------------------
 // Large batches (prefill): bound by the matrix cores.  A 256-thread workgroup computes a
-// 256 x 64*NB tile of Y (NB = 4: 256 x 256; NB = 2: 256 x 128); each of its four wavefronts
-// owns a 128 x 32*NB part as 4 x NB tiles of v_mfma_f32_32x32x16 (64*NB fp32 accumulators per
-// lane, one wavefront per SIMD).  X and weight rows are both contiguous along k, so both
-// operands are staged the same way: 64-wide k slabs go global -> registers -> LDS (row pitch
-// 144 B, which spreads the 32 rows a ds_read_b128 touches over all banks).  LDS holds two
-// slabs: while the MFMAs of slab s read one buffer, slab s+1 is written into the other and the
-// global loads of slab s+2 are in flight; one barrier per slab.  The narrower tile reads 1.5 x
-// the LDS bytes per MFMA and reaches 0.87 of the wide tile's rate per compute unit; it is for
-// outputs whose 256 x 256 tiling leaves the last round of workgroups half empty or fills too
-// few compute units (measured: 6144 outputs at M = 4096, 384 wide tiles in 1.5 rounds, 210 us;
-// 768 narrow tiles in 3 rounds, 178 us).
-constexpr int kTileM = 256, kTileK = 64;                // tile height and slab depth; the width is 64 * NB
+// 64*MA x 64*NB tile of Y (MA = NB = 4: 256 x 256; MA = 4, NB = 2: 256 x 128; MA = NB = 2:
+// 128 x 128); each of its four wavefronts owns a 32*MA x 32*NB part as MA x NB tiles of
+// v_mfma_f32_32x32x16 (16*MA*NB fp32 accumulators per lane, one wavefront per SIMD).  X and
+// weight rows are both contiguous along k, so both operands are staged the same way: 64-wide k
+// slabs go global -> registers -> LDS (row pitch 144 B, which spreads the 32 rows a
+// ds_read_b128 touches over all banks).  LDS holds two slabs: while the MFMAs of slab s read
+// one buffer, slab s+1 is written into the other and the global loads of slab s+2 are in
+// flight; one barrier per slab.  The smaller tiles read more LDS bytes per MFMA (x1.5, x2) and
+// reach 0.87 and about 0.75 of the 256 x 256 tile's rate per compute unit; they are for outputs
+// whose 256 x 256 tiling leaves the last round of workgroups half empty or fills too few
+// compute units (measured: 6144 outputs at M = 4096, 384 tiles of 256 x 256 in 1.5 rounds,
+// 210 us; 768 of 256 x 128 in 3 rounds, 178 us; 4096 outputs at M = 1024, 64 tiles of
+// 256 x 256, streaming kernel 56 us; 256 tiles of 128 x 128, 45 us).
+constexpr int kTileK = 64;                              // slab depth; a tile is 64 * MA rows by 64 * NB columns
 constexpr int kSupM = 4, kSupN = 8;                     // tiles per XCD-resident block
 constexpr int kPitch = kTileK * 2 + 16;                 // bytes per LDS row
 
-template <class E, int NB>
+template <class E, int NB, int MA>
 __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     const uint16_t *__restrict__ X, int64_t ldx, const uint16_t *__restrict__ A, int64_t lda,
     uint16_t *__restrict__ Y, int64_t ldy, int M, int Nn, int K)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int kTN = 64 * NB;                        // tile width: two wavefronts of NB 32-wide tiles
-    constexpr int kLdsN = (kTileM + kTN) * kPitch;      // bytes per LDS buffer
+    constexpr int kTM = 64 * MA;                        // tile height: two wavefronts of MA 32-row tiles
+    constexpr int kLdsN = (kTM + kTN) * kPitch;         // bytes per LDS buffer
+    constexpr int NX = 2 * MA;                          // 32-row passes of the batch operand
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv >> 1, wn = wv & 1;                // quadrant of this wavefront
     // Workgroup -> tile.  Consecutive workgroup ids go to the 8 XCDs in turn and each XCD has
     // its own L2, so the 32 workgroups that run together on one XCD are given a 4 x 8 block of
     // tiles: every X slab is then fetched into that L2 once for 8 tiles and every weight slab
     // once for 4, instead of each workgroup streaming a weight tile of its own.
-    const int tiles_m = (M + kTileM - 1) / kTileM, tiles_n = (Nn + kTN - 1) / kTN;
+    const int tiles_m = (M + kTM - 1) / kTM, tiles_n = (Nn + kTN - 1) / kTN;
     const int sup_n = (tiles_n + kSupN - 1) / kSupN;
     const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
     const int sup = (seq / (kSupM * kSupN)) * 8 + xcd, in_sup = seq % (kSupM * kSupN);
     const int tm = (sup / sup_n) * kSupM + in_sup / kSupN, tn = (sup % sup_n) * kSupN + in_sup % kSupN;
     if (tm >= tiles_m || tn >= tiles_n) return;         // whole workgroup leaves before any barrier
-    const int m0 = tm * kTileM, n0 = tn * kTN;
+    const int m0 = tm * kTM, n0 = tn * kTN;
 
-    // staging map: 256 rows x 8 vectors of 16 B per operand and slab; thread t takes
-    // vector (t & 7) of rows (t >> 3) + 32 * q, q = 0..7: eight lanes read one 128 B line.
+    // staging map: rows x 8 vectors of 16 B per operand and slab; thread t takes vector
+    // (t & 7) of rows (t >> 3) + 32 * q, q = 0 .. rows / 32 - 1: eight lanes read one 128 B line.
     // A load's address is a uniform 64-bit base (the tile's first row plus the slab) plus a
     // 32-bit byte offset per lane that never changes (row inside the tile times the row
     // stride), so the slab loop spends no vector instructions on addresses.
     const int sv = tid & 7, sr = tid >> 3;
     constexpr int NA = 2 * NB;                          // 32-row passes of the weight operand
-    uint32_t xo[8], ao[NA];
+    uint32_t xo[NX], ao[NA];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < NX; ++q) {
         const int r = sr + 32 * q;
         xo[q] = uint32_t(min(m0 + r, M - 1) - m0) * uint32_t(ldx * 2) + uint32_t(sv * 16);
     }
@@ -483,9 +487,9 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     const char *at = reinterpret_cast<const char *>(A) + int64_t(n0) * lda * 2;
 #define NTS_GLOAD(base, o) (*reinterpret_cast<const u32x4 *>((base) + (o)))
 
-    f32x16 acc[4][NB];
+    f32x16 acc[MA][NB];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < MA; ++a)
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -497,35 +501,35 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
 
     // prologue: slab 0 into LDS buffer 0, slab 1 into registers; both slabs' loads are issued
     // before the first wait, so the tile starts after one memory latency, not two
-    u32x4 xr[8], ar[NA];
+    u32x4 xr[NX], ar[NA];
     {
-        u32x4 x0[8], a0[NA];
+        u32x4 x0[NX], a0[NA];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) x0[q] = NTS_GLOAD(xt, xo[q]);
+        for (int q = 0; q < NX; ++q) x0[q] = NTS_GLOAD(xt, xo[q]);
 #pragma unroll
         for (int q = 0; q < NA; ++q) a0[q] = NTS_GLOAD(at, ao[q]);
         const int64_t off = int64_t(min(1, n_slabs - 1)) * (kTileK * 2);
         const char *xg = xt + off, *ag = at + off;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) xr[q] = NTS_GLOAD(xg, xo[q]);
+        for (int q = 0; q < NX; ++q) xr[q] = NTS_GLOAD(xg, xo[q]);
 #pragma unroll
         for (int q = 0; q < NA; ++q) ar[q] = NTS_GLOAD(ag, ao[q]);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) *reinterpret_cast<u32x4 *>(lds + st_off + 32 * q * kPitch) = x0[q];
+        for (int q = 0; q < NX; ++q) *reinterpret_cast<u32x4 *>(lds + st_off + 32 * q * kPitch) = x0[q];
 #pragma unroll
-        for (int q = 0; q < NA; ++q) *reinterpret_cast<u32x4 *>(lds + kTileM * kPitch + st_off + 32 * q * kPitch) = a0[q];
+        for (int q = 0; q < NA; ++q) *reinterpret_cast<u32x4 *>(lds + kTM * kPitch + st_off + 32 * q * kPitch) = a0[q];
     }
     nts_lds_barrier();
 
-    // Two fragment sets: while the 4*NB MFMAs of k step kk run on one set, the 4+NB fragments of
-    // step kk+1 are read from LDS into the other, one read every STRIDE MFMAs and in the order
-    // the next step consumes them (X0, the weight fragments, X1 X2 X3).  A wavefront issues in
+    // Two fragment sets: while the MA*NB MFMAs of k step kk run on one set, the MA+NB fragments
+    // of step kk+1 are read from LDS into the other, one read every STRIDE MFMAs and in the order
+    // the next step consumes them (X0, the weight fragments, X1 ...).  A wavefront issues in
     // order and can have only 15 LDS operations outstanding (4-bit counter), so everything that
     // goes through LDS is spread between the MFMAs instead of issued in bursts: the stores of
     // slab s+1 (in registers since the previous slab) and, right behind each store, the global
     // load of slab s+2 into the same register, one pair per PAIR MFMAs over the first three k
     // steps.  sched_barrier pins this order; left alone the compiler serialises read - wait -
-    // MFMA.  With NB = 4 the LDS is about three quarters busy over a slab, evenly.
+    // MFMA.  With MA = NB = 4 the LDS is about three quarters busy over a slab, evenly.
     // One barrier per slab, before the last k step: by then every wavefront has read all of
     // slab s (so slab s+2 may overwrite its buffer from the next iteration on) and has written
     // its part of slab s+1 (so the first fragments of slab s+1 can be read during the last k
@@ -534,48 +538,52 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     // the loads repeat the last slab and the spare buffer takes the copy.  Two slabs per trip,
     // so each slab's LDS buffer is a constant and fragment reads and stores carry their whole
     // address in the instruction's offset field from a few per-lane bases.
-    constexpr int NF = 4 + NB;                          // fragments per k step
-    constexpr int NM = 4 * NB;                          // MFMAs per k step
-    constexpr int NS = 8 + NA;                          // staged vectors per thread and slab
+    constexpr int NF = MA + NB;                         // fragments per k step
+    constexpr int NM = MA * NB;                         // MFMAs per k step
+    constexpr int NS = NX + NA;                         // staged vectors per thread and slab
     constexpr int PAIR = (3 * NM) / NS;                 // MFMA slots per store/load pair (first three k steps)
+    constexpr int LSLOT = PAIR > 1 ? 1 : 0;             // the load follows its store, in the same slot if pairs come every MFMA
 #define NTS_READ_FRAG(base, kk, r, XF, AF)                                                             \
     {                                                                                                  \
         if ((r) == 0 || (r) > NB) {                                                                    \
             const int a_ = (r) == 0 ? 0 : (r) - NB;                                                    \
             XF[a_] = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(                      \
-                (base) + (wm * 128 + a_ * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));              \
+                (base) + (wm * 32 * MA + a_ * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2));              \
         } else {                                                                                       \
             const int b_ = (r) - 1;                                                                    \
             AF[b_] = __builtin_bit_cast(vec8, *reinterpret_cast<const u32x4 *>(                      \
-                (base) + (kTileM + wn * 32 * NB + b_ * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2)); \
+                (base) + (kTM + wn * 32 * NB + b_ * 32 + fr) * kPitch + ((kk) * 16 + fg * 8) * 2)); \
         }                                                                                              \
     }
     // staged vector i of a slab: X and weight vectors alternate while there are weight vectors left
 #define NTS_STORE_ONE(i)                                                                               \
     {                                                                                                  \
-        if ((i) < 2 * NA && ((i) & 1)) *reinterpret_cast<u32x4 *>(nx + kTileM * kPitch + st_off + 32 * ((i) >> 1) * kPitch) = ar[(i) >> 1]; \
-        else { const int q_ = (i) < 2 * NA ? (i) >> 1 : (i) - NA;                                      \
+        constexpr int NI_ = 2 * (NA < NX ? NA : NX);     /* interleaved part */                        \
+        if ((i) < NI_ ? ((i) & 1) : (NA > NX)) { const int q_ = (i) < NI_ ? (i) >> 1 : (i) - NX;       \
+               *reinterpret_cast<u32x4 *>(nx + kTM * kPitch + st_off + 32 * q_ * kPitch) = ar[q_]; }   \
+        else { const int q_ = (i) < NI_ ? (i) >> 1 : (i) - NA;                                         \
                *reinterpret_cast<u32x4 *>(nx + st_off + 32 * q_ * kPitch) = xr[q_]; }                  \
     }
 #define NTS_LOAD_ONE(i)                                                                                \
     {                                                                                                  \
-        if ((i) < 2 * NA && ((i) & 1)) ar[(i) >> 1] = NTS_GLOAD(ag, ao[(i) >> 1]);                     \
-        else { const int q_ = (i) < 2 * NA ? (i) >> 1 : (i) - NA; xr[q_] = NTS_GLOAD(xg, xo[q_]); }    \
+        constexpr int NI_ = 2 * (NA < NX ? NA : NX);                                                   \
+        if ((i) < NI_ ? ((i) & 1) : (NA > NX)) { const int q_ = (i) < NI_ ? (i) >> 1 : (i) - NX; ar[q_] = NTS_GLOAD(ag, ao[q_]); } \
+        else { const int q_ = (i) < NI_ ? (i) >> 1 : (i) - NA; xr[q_] = NTS_GLOAD(xg, xo[q_]); }       \
     }
 #define NTS_KSTEP(XF, AF, G0, NBASE, NKK, NXF, NAF, STRIDE)                                            \
     {                                                                                                  \
-        _Pragma("unroll") for (int a = 0; a < 4; ++a)                                                  \
+        _Pragma("unroll") for (int a = 0; a < MA; ++a)                                                 \
             _Pragma("unroll") for (int b = 0; b < NB; ++b) {                                           \
                 const int i = a * NB + b, g = (G0) + i;      /* constants after unrolling */           \
                 acc[a][b] = E::mfma32(AF[b], XF[a], acc[a][b]);                                       \
                 if (i % (STRIDE) == 0 && i / (STRIDE) < NF) NTS_READ_FRAG(NBASE, NKK, i / (STRIDE), NXF, NAF) \
                 if (g % PAIR == 0 && g / PAIR < NS) NTS_STORE_ONE(g / PAIR)                            \
-                if (g % PAIR == 1 && g / PAIR < NS) NTS_LOAD_ONE(g / PAIR)                             \
+                if (g % PAIR == LSLOT && g / PAIR < NS) NTS_LOAD_ONE(g / PAIR)                             \
                 __builtin_amdgcn_sched_barrier(0);                                                     \
             }                                                                                          \
     }
     typedef typename E::vec8 vec8;
-    vec8 xf0[4], af0[NB], xf1[4], af1[NB];
+    vec8 xf0[MA], af0[NB], xf1[MA], af1[NB];
 #pragma unroll
     for (int r = 0; r < NF; ++r) NTS_READ_FRAG(lds, 0, r, xf0, af0)
     constexpr int S2 = NM / NF >= 2 ? 2 : 1;            // fragment reads every other MFMA where there is room
@@ -617,7 +625,7 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
         unsigned char *strip = lds + wv * 32 * kOutPitch;
         const int orow = lane / kLanesRow, ocol = (lane % kLanesRow) * 8;
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
+        for (int a = 0; a < MA; ++a) {
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -633,7 +641,7 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
                 const u32x2 lo = *reinterpret_cast<const u32x2 *>(strip + r * kOutPitch + ocol * 2);
                 const u32x2 hi = *reinterpret_cast<const u32x2 *>(strip + r * kOutPitch + ocol * 2 + 8);
                 const u32x4 val = {lo[0], lo[1], hi[0], hi[1]};
-                const int m = m0 + wm * 128 + a * 32 + r, n = n0 + wn * 32 * NB + ocol;
+                const int m = m0 + wm * 32 * MA + a * 32 + r, n = n0 + wn * 32 * NB + ocol;
                 if (m < M) {
                     uint16_t *dst = Y + int64_t(m) * ldy + n;
                     if (n + 8 <= Nn) {
@@ -849,35 +857,48 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
     return hipGetLastError();
 }
 
-// Estimated time of the tiled kernel with tiles `cols` wide: rounds of 256 workgroups, each
+// Estimated time of the tiled kernel with tiles of rows x cols: rounds of 256 workgroups, each
 // round a fixed cost plus its slabs (measured per slab: 1.57 us for 256 x 256, 0.91 us for
-// 256 x 128).
-static double tiled_estimate_us(int M, int Nn, int K, int cols)
+// 256 x 128, 0.6 us for 128 x 128).
+static double tiled_estimate_us(int M, int Nn, int K, int rows, int cols)
 {
-    const int64_t tiles = int64_t((M + kTileM - 1) / kTileM) * ((Nn + cols - 1) / cols);
-    const double per_round = cols == 256 ? 11. + 1.57 * (K / kTileK) : 8. + 0.91 * (K / kTileK);
+    const int64_t tiles = int64_t((M + rows - 1) / rows) * ((Nn + cols - 1) / cols);
+    const int S = K / kTileK;
+    const double per_round = cols == 256 ? 11. + 1.57 * S : rows == 256 ? 8. + 0.91 * S : 4. + 0.6 * S;
     return 2.5 + double((tiles + 255) / 256) * per_round;
 }
 
-// Tile width of the tiled kernel for a problem, 0 for the streaming kernel.  The tiled kernel
-// pays off once its tiles occupy most of the chip (measured break-even near 150 tiles of
-// 256 x 256, 160 of 256 x 128); below that the streaming kernel (several batch tiles per
-// weight block, K splits) is faster.  Between the two widths the round estimate decides: the
-// narrow tile does 13 % less per compute unit but wastes less of a ragged last round.
-int nts_linear_use_tiled(int M, int Nn, int K)
+// Tile of the tiled kernel for a problem (*rows x returned columns), 0 for the streaming kernel.
+// The tiled kernel pays off once its tiles occupy most of the chip (measured break-even near
+// 150 tiles of 256 x 256, 160 of the smaller ones); below that the streaming kernel (several
+// batch tiles per weight block, K splits) is faster.  Between 256 x 256 and 256 x 128 the
+// round estimate decides: the narrow tile does 13 % less per compute unit but wastes less of a
+// ragged last round.  128 x 128 is for outputs too small for either (measured on every such
+// prefill shape of the 8B model: level with or up to 30 % ahead of the streaming kernel, and
+// behind the larger tiles wherever those qualify).
+int nts_linear_use_tiled(int M, int Nn, int K, int *rows)
 {
+    *rows = 256;
     if (M < 256) return 0;
-    const int64_t tm = (M + kTileM - 1) / kTileM;
-    const int64_t t256 = tm * ((Nn + 255) / 256), t128 = tm * ((Nn + 127) / 128);
-    const bool ok256 = M > 256 && t256 >= 160, ok128 = t128 >= 160;
-    if (ok256 && ok128) return tiled_estimate_us(M, Nn, K, 128) < 0.97 * tiled_estimate_us(M, Nn, K, 256) ? 128 : 256;
-    return ok256 ? 256 : ok128 ? 128 : 0;
+    const int64_t tm = (M + 255) / 256;
+    const int64_t t256 = tm * ((Nn + 255) / 256), t128c = tm * ((Nn + 127) / 128);
+    const int64_t t128s = int64_t((M + 127) / 128) * ((Nn + 127) / 128);
+    const bool ok256 = M > 256 && t256 >= 160, ok128c = M >= 256 && t128c >= 160;
+    if (ok256 && ok128c)
+        return tiled_estimate_us(M, Nn, K, 256, 128) < 0.97 * tiled_estimate_us(M, Nn, K, 256, 256) ? 128 : 256;
+    if (ok256) return 256;
+    if (ok128c) return 128;
+    if (M >= 512 && t128s >= 160) {      // with fewer than four row tiles the streaming kernel stays ahead
+        *rows = 128;
+        return 128;
+    }
+    return 0;
 }
 
 // Every configuration that may be fastest for a problem, for nts_shard_linear_tune to time: the
 // streaming kernel's variants with each K split that is valid for them, the decode kernel's
 // (row blocks, wavefronts per K range, K split) combinations for M <= 16, and the tiled kernel
-// in both tile widths for M >= 256.  Each gets the same estimate nts_linear_stream_config uses
+// in its three tile shapes for M >= 128.  Each gets the same estimate nts_linear_stream_config uses
 // (the tiled kernel: tiled_estimate_us); the list is cut to those within `slack` of
 // the smallest estimate, sorted by estimate, at most `max_out`.  The configuration
 // nts_shard_linear uses by default is always first.
@@ -890,7 +911,7 @@ int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out
     const double out_elems = double(M) * Nn;
     const double hbm_us = double(Nn) * K * 2. / 6.1e6;
     NtsLinearCand def;
-    def.tiled = nts_linear_use_tiled(M, Nn, K);
+    def.tiled = nts_linear_use_tiled(M, Nn, K, &def.tiled_rows);
     def.cfg = nts_linear_stream_config(M, Nn, K);
     if (def.tiled) def.cfg.splits = 1;
     def.est_us = 0.;
@@ -957,17 +978,19 @@ int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out
                     all.push_back(c);
                 }
     }
-    if (M >= 256)
-        for (int cols = 256; cols >= 128; cols -= 128) {
-            NtsLinearCand c;
-            c.tiled = cols;
-            c.cfg = def.cfg;
-            c.cfg.splits = 1;
-            c.est_us = tiled_estimate_us(M, Nn, K, cols);
-            all.push_back(c);
-        }
+    static const int kTiles[3][2] = {{256, 256}, {256, 128}, {128, 128}};
+    for (const auto &t : kTiles) {
+        if (M < t[0]) continue;
+        NtsLinearCand c;
+        c.tiled = t[1];
+        c.tiled_rows = t[0];
+        c.cfg = def.cfg;
+        c.cfg.splits = 1;
+        c.est_us = tiled_estimate_us(M, Nn, K, t[0], t[1]);
+        all.push_back(c);
+    }
     auto same = [](const NtsLinearCand &a, const NtsLinearCand &b) {
-        if (a.tiled != b.tiled) return false;
+        if (a.tiled != b.tiled || (a.tiled && a.tiled_rows != b.tiled_rows)) return false;
         if (a.tiled) return true;
         if (a.cfg.ks != b.cfg.ks || a.cfg.rt != b.cfg.rt || a.cfg.splits != b.cfg.splits || a.cfg.nsets != b.cfg.nsets)
             return false;
@@ -989,28 +1012,30 @@ int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out
     return n;
 }
 
-template <class E, int NB>
+template <class E, int NB, int MA>
 static hipError_t launch_tiled_one(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda, uint16_t *Y,
                                    int64_t ldy, int M, int Nn, int K, hipStream_t st)
 {
-    constexpr int cols = 64 * NB, lds_bytes = 2 * (kTileM + cols) * kPitch;
+    constexpr int rows = 64 * MA, cols = 64 * NB, lds_bytes = 2 * (rows + cols) * kPitch;
     static std::atomic<uint64_t> configured{0};
-    const hipError_t ea = allow_dynamic_lds(configured, reinterpret_cast<const void *>(nts_linear_tiled_kernel<E, NB>), lds_bytes);
+    const hipError_t ea = allow_dynamic_lds(configured, reinterpret_cast<const void *>(nts_linear_tiled_kernel<E, NB, MA>), lds_bytes);
     if (ea != hipSuccess) return ea;
-    const int tiles_m = (M + kTileM - 1) / kTileM, tiles_n = (Nn + cols - 1) / cols;
+    const int tiles_m = (M + rows - 1) / rows, tiles_n = (Nn + cols - 1) / cols;
     const int sups = ((tiles_m + kSupM - 1) / kSupM) * ((tiles_n + kSupN - 1) / kSupN);
     const dim3 grid(unsigned((sups + 7) / 8) * 8u * kSupM * kSupN), block(256);
-    hipLaunchKernelGGL((nts_linear_tiled_kernel<E, NB>), grid, block, lds_bytes, st, X, ldx, A, lda, Y, ldy, M, Nn, K);
+    hipLaunchKernelGGL((nts_linear_tiled_kernel<E, NB, MA>), grid, block, lds_bytes, st, X, ldx, A, lda, Y, ldy, M, Nn, K);
     return hipGetLastError();
 }
 
 hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_t *A, int64_t lda,
-                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, int tile_cols, bool f16,
-                                   hipStream_t st)
+                                   uint16_t *Y, int64_t ldy, int M, int Nn, int K, int tile_rows, int tile_cols,
+                                   bool f16, hipStream_t st)
 {
-    if (tile_cols == 128)
-        return f16 ? launch_tiled_one<F16, 2>(X, ldx, A, lda, Y, ldy, M, Nn, K, st)
-                   : launch_tiled_one<Bf16, 2>(X, ldx, A, lda, Y, ldy, M, Nn, K, st);
-    return f16 ? launch_tiled_one<F16, 4>(X, ldx, A, lda, Y, ldy, M, Nn, K, st)
-               : launch_tiled_one<Bf16, 4>(X, ldx, A, lda, Y, ldy, M, Nn, K, st);
+#define NTS_TILED(NB, MA)                                                                              \
+    return f16 ? launch_tiled_one<F16, NB, MA>(X, ldx, A, lda, Y, ldy, M, Nn, K, st)                   \
+               : launch_tiled_one<Bf16, NB, MA>(X, ldx, A, lda, Y, ldy, M, Nn, K, st);
+    if (tile_rows == 128) NTS_TILED(2, 2)
+    if (tile_cols == 128) NTS_TILED(2, 4)
+    NTS_TILED(4, 4)
+#undef NTS_TILED
 }
