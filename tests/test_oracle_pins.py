@@ -254,14 +254,14 @@ def test_stream_bytes_match_paper_size_identity():
 @pytest.mark.parametrize("tr", [(1, 0, 2, 1), (2, 1, 4, 2), (4, 3, 8, 7), (8, 2, 4, 1), (4, 1, 2, 0), (2, 1, 1, 0), (1, 0, 1, 0)])
 def test_migrate_equals_direct_and_closed_form_of_fill(tr):
     Ns, rs, Nd, rd = tr
-    H, L, D, S, T = 8, 2, 8, 64, 40
+    H, L, D, S, Sd, T = 8, 2, 8, 64, 52, 40         # the two pools differ in size
     so, do, w = orc.route(H, Ns, rs, Nd, rd)
     Hs, Hd = H // Ns, H // Nd
     rng = SplitMix64(300 + Ns * 10 + Nd)
     src = fill_pool_u16(11, L * 2 * S * Hs * D).reshape(L, 2, S, Hs, D)
-    dst0 = fill_pool_u16(12, L * 2 * S * Hd * D).reshape(L, 2, S, Hd, D)
+    dst0 = fill_pool_u16(12, L * 2 * Sd * Hd * D).reshape(L, 2, Sd, Hd, D)
     sslot = rng.permutation(S)[:T].astype(np.int32)
-    dslot = rng.permutation(S)[:T].astype(np.int32)
+    dslot = rng.permutation(Sd)[:T].astype(np.int32)
     a, b = dst0.copy(), dst0.copy()
     orc.migrate(src, a, sslot, dslot, so, do, w)
     orc.migrate_direct(src, b, sslot, dslot, so, do, w)
@@ -272,12 +272,49 @@ def test_migrate_equals_direct_and_closed_form_of_fill(tr):
         word = int(fill_words(11, lin // 4, 1)[0])
         assert int(a[l, c, dslot[j], do + h, x]) == (word >> (16 * (lin % 4))) & 0xFFFF
     # and an untouched element still equals the destination's own fill
-    free = sorted(set(range(S)) - set(dslot.tolist()))[0]
-    lin = (((0 * S + free) * Hd + 0) * D + 3)
+    free = sorted(set(range(Sd)) - set(dslot.tolist()))[0]
+    lin = (((0 * Sd + free) * Hd + 0) * D + 3)
     assert int(a[0, 0, free, 0, 3]) == (int(fill_words(12, lin // 4, 1)[0]) >> (16 * (lin % 4))) & 0xFFFF
 
 
-@pytest.mark.parametrize("tr", [(2, 1, 4, 2), (4, 1, 2, 0), (2, 1, 4, 3), (1, 0, 1, 0)])
+def test_argument_checks_accept_the_last_valid_value_and_reject_the_next():
+    """The C loops index without checks, so the Python side's range checks are
+    what keeps a bad argument from reading or writing outside a pool: each check
+    is tried at its last valid value and one beyond."""
+    L, S, H, D = 1, 6, 4, 2
+    src = np.arange(L * 2 * S * H * D, dtype=np.uint16).reshape(L, 2, S, H, D)
+    last, beyond = np.array([S - 1], np.int32), np.array([S], np.int32)
+    assert np.array_equal(orc.pack(src, last, 1, 3)[0, 0, 0], src[0, 0, S - 1, 1:4])       # head slice ends at H
+    for bad in [dict(sslot=beyond, src_head_off=0, w=1), dict(sslot=np.array([-1], np.int32), src_head_off=0, w=1),
+                dict(sslot=np.array([0, S], np.int32), src_head_off=0, w=1),              # one bad slot among good ones
+                dict(sslot=np.array([2, -1], np.int32), src_head_off=0, w=1),
+                dict(sslot=last, src_head_off=2, w=3), dict(sslot=last, src_head_off=-1, w=1),
+                dict(sslot=last, src_head_off=0, w=0)]:
+        with pytest.raises(ValueError):
+            orc.pack(src, **bad)
+    stream = orc.pack(src, last, 1, 3)
+    dst = np.zeros((L, 2, S, H, D), np.uint16)
+    orc.unpack(stream, dst, last, 1)                                                        # ends at H: fine
+    assert np.array_equal(dst[0, 0, S - 1, 1:4], src[0, 0, S - 1, 1:4]) and not dst[0, 0, S - 1, 0].any()
+    for slots, off in [(last, 2), (last, -1), (beyond, 0)]:
+        with pytest.raises(ValueError):
+            orc.unpack(stream, np.zeros_like(dst), slots, off)
+    # the direct form checks each side by itself: a slice that fits one pool but not the other is refused
+    narrow = np.zeros((L, 2, S, 2, D), np.uint16)
+    orc.migrate_direct(src, narrow, last, last, 2, 0, 2)                                    # both end at their pool's H
+    assert np.array_equal(narrow[0, 0, S - 1], src[0, 0, S - 1, 2:4])
+    for so, do, w in [(1, 0, 3), (2, 1, 2), (3, 0, 2), (0, 0, 0), (-1, 0, 1), (0, -1, 1)]:
+        with pytest.raises(ValueError):
+            orc.migrate_direct(src, np.zeros_like(narrow), last, last, so, do, w)
+    with pytest.raises(ValueError):
+        orc.migrate_direct(src, np.zeros_like(narrow), beyond, last, 2, 0, 2)
+    with pytest.raises(ValueError):
+        orc.head_interval(8, 0, 0)
+    # ranks whose head ranges only touch exchange nothing, and "nothing" is always (0, 0, 0)
+    assert orc.route(8, 2, 0, 4, 2) == (0, 0, 0) and orc.route(8, 4, 3, 2, 0) == (0, 0, 0)
+
+
+@pytest.mark.parametrize("tr", [(2, 1, 4, 2), (4, 1, 2, 0), (2, 1, 4, 3), (1, 0, 1, 0), (4, 0, 2, 0), (8, 5, 2, 1)])
 def test_migrated_element_source_against_dictionary_model(tr):
     """``migrated_element_source`` names, for one destination (slot, local head),
     the source (slot, local head) it must hold afterwards.  Expected side: a

@@ -27,6 +27,8 @@ def test_balanced_block_is_the_rate_ratio_when_it_is_integral():
     assert op.balanced_block(4.0, 6.0) == (3, 2)
     assert op.balanced_block(5.0, 5.0) == (1, 1)
     assert op.balanced_block(1.0, 8.0) == (8, 1)
+    # the instance limit binds: 8:1 is out of reach with four instances a side, 4:1 is the closest
+    assert op.balanced_block(1.0, 8.0, 4) == (4, 1) and op.balanced_block(8.0, 1.0, 4) == (1, 4)
     # and when balanced, Eq. 1 without the rps cap equals 1 / (TPi/THP + TPj/THD)
     for thp, tpi, thd, tpj in [(6.0, 2, 3.0, 1), (4.0, 4, 6.0, 2), (5.0, 1, 5.0, 8)]:
         P, D = op.balanced_block(thp, thd)
@@ -55,6 +57,24 @@ def test_greedy_hand_worked_run():
     assert [(a.tier, a.tp_prefill, a.tp_decode, a.P, a.D, a.gpus, a.served) for a in allocs] == \
         [(0, 2, 2, 1, 1, 4, 10.0), (1, 1, 1, 1, 1, 2, 2.0)]
     assert left == 2
+
+
+def test_weighted_greedy_hand_worked_order():
+    """Sec. 3.3.1's weight, GE times the tier's rate over what it is already served, by hand.
+    Only TP1 is feasible and every block is one prefill plus one decode instance (2 GPUs).
+    Tier A: 100 req/s wanted, 10 per block, GE 5.  Tier B: 12 wanted, 4 per block, GE 2.
+    Fresh tiers go first, best GE first: A, then B.  From then on A scores 5 * 100 / served_A and
+    B scores 2 * 12 / served_B: with B at 4 served (score 6) A wins at 10, 20, ... 80 served
+    (50, 25, 16.7, 12.5, 10, 8.3, 7.1, 6.25) and loses at 90 (5.56 < 6): B gets its second block
+    (score drops to 3), A its tenth (done), B its third (done)."""
+    tiers = [op.Tier(100.0, [10, 0, 0, 0], [10, 0, 0, 0]), op.Tier(12.0, [4, 0, 0, 0], [4, 0, 0, 0])]
+    allocs, left = op.plan(26, tiers)
+    assert [a.tier for a in allocs] == [0, 1] + [0] * 8 + [1, 0, 1] and left == 0
+    assert all(a.gpus == 2 and (a.P, a.D) == (1, 1) for a in allocs)
+    assert [a.served for a in allocs if a.tier == 1] == [4.0, 4.0, 4.0]
+    # two blocks fewer: B's second block still comes before A's tenth
+    allocs, left = op.plan(22, tiers)
+    assert [a.tier for a in allocs] == [0, 1] + [0] * 8 + [1] and left == 0
 
 
 def test_weighting_keeps_a_low_efficiency_tier_from_starving():
@@ -108,3 +128,7 @@ def test_single_tier_single_config_matches_brute_force():
         allocs, left = op.plan(G, [t])
         best = min(37.0, 6.0 * (G // 4))
         assert sum(a.served for a in allocs) == pytest.approx(best)
+        # levels with no throughput are never used: every block is the 4-GPU one, serves something,
+        # and the GPUs that do not make up a block (or are not needed) stay free
+        assert all(a.gpus == 4 and a.served > 0 for a in allocs) and left == G - 4 * len(allocs)
+        assert len(allocs) == min(G // 4, 7)

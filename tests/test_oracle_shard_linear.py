@@ -78,6 +78,20 @@ def test_tolerance_covers_fp32_accumulation_in_any_order():
     assert tol < 0.02 * bound                                   # and it is not vacuous
 
 
+def test_tolerance_hand_value_and_what_it_rejects():
+    """The worst-case bound on a case small enough for mental arithmetic: y = 1, sum |x w| = 2, k = 256,
+    bfloat16 output.  fp32 accumulation: 256 * 2^-23 * 2 = 2^-14; rounding: 2^-8 of (1 + 2^-14);
+    together 2^-8 + 2^-14 + 2^-22.  At a short reduction it is therefore tight enough that an error of
+    two output ulps (2 * 2^-7 for y = 1) fails, while half an ulp passes."""
+    tol = float(osl.tolerance(np.array(1.0), np.array(2.0), 256))
+    assert tol == 2.0 ** -8 + 2.0 ** -14 + 2.0 ** -22
+    assert 0.5 * 2.0 ** -7 <= tol < 2 * 2.0 ** -7
+    # float16 keeps three more bits: the rounding term shrinks by 8, the accumulation term stays
+    assert float(osl.tolerance(np.array(1.0), np.array(2.0), 256, out_bits=11)) == 2.0 ** -11 + 2.0 ** -14 + 2.0 ** -25
+    with pytest.raises(ValueError):
+        osl.shard_bounds(16, 0, 0)
+
+
 def test_round_to_bits_hand_values_and_ties_to_even():
     """bfloat16 keeps 8 significant bits: integers in [256, 512) are 2 apart, so
     257 and 259 are exact ties; float16 keeps 11: integers in [2048, 4096)."""
