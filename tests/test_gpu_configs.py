@@ -226,6 +226,34 @@ def test_config4_skewed_four_destinations(env):
     assert total_F == 2621440
 
 
+def test_config4_as_one_batch_call(env):
+    """Configuration 4 the way bench.py runs a workload of several pairs: all four plans made first, then one
+    nts_run_migrate_batch through the two staging buffers; every byte of the four destination pools against
+    the oracle."""
+    from gpu_util import compare_every_layer, device_pool, make_plan, oracle_slots, slab_bytes
+    torch, b, wdev, ctx, staging = env
+    cases = make_case("c4")
+    sh = cases[0].shape
+    src_d = device_pool(cases[0], "src")
+    sp = b.layer_ptrs(src_d.data_ptr(), sh.L, slab_bytes(cases[0], "src"))
+    dsts = [device_pool(c, "dst") for c in cases]
+    dps = [b.layer_ptrs(d.data_ptr(), sh.L, slab_bytes(c, "dst")) for c, d in zip(cases, dsts)]
+    plans = [make_plan(b, ctx, c, staging_bytes=STAGING, flags=b.NTS_VALIDATE_UNIQUE_DST | b.NTS_ORDER_BY_DST)
+             for c in cases]
+    try:
+        b.nts_run_migrate_batch(plans, [sp] * len(cases), dps, staging.data_ptr(),
+                                torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+    finally:
+        for p in plans:
+            b.nts_plan_free(p)
+    assert wdev.count_mismatch(src_d, cases[0].seed_src) == 0, "source pool changed"
+    for c, d in zip(cases, dsts):
+        es, ed = oracle_slots(c)
+        compare_every_layer(c, d, es, ed, label=f"c4 batch, destination rank {c.rd}")
+    del src_d, dsts
+
+
 @pytest.mark.parametrize("ranked", [False, True])
 def test_whole_stream_pack_and_unpack_beyond_one_launch(env, ranked):
     """nts_run_pack and nts_run_unpack on a 33 GiB stream (config 5's recipe at 270,336 tokens): more
