@@ -6,6 +6,7 @@
 // requires a clean exit (any sanitizer report aborts with a non-zero status).
 #include <inttypes.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <iostream>
@@ -14,6 +15,14 @@
 #include <vector>
 
 #include "nts_host.h"
+
+// a double from the next token; strtod, because stream extraction does not read "nan"
+static double next_double(std::istringstream &in)
+{
+    std::string tok;
+    in >> tok;
+    return strtod(tok.c_str(), nullptr);
+}
 
 int main()
 {
@@ -27,7 +36,12 @@ int main()
             in >> H >> Ns >> rs >> Nd >> rd;
             const int rc = nts_host_route(H, Ns, rs, Nd, rd, &so, &dof, &w);
             printf("route %d %d %d %d\n", rc, so, dof, w);
-        } else if (cmd == "geom") {
+        } else if (cmd == "route_null") {                   // one of the three result pointers missing
+            int which, a = 0, b = 0, c = 0;
+            in >> which;
+            printf("route_null %d\n", nts_host_route(8, 2, 0, 4, 1, which == 0 ? nullptr : &a, which == 1 ? nullptr : &b,
+                                                     which == 2 ? nullptr : &c));
+        } else if (cmd == "geom" || cmd == "geom_nosrc" || cmd == "geom_nodst") {
             nts_desc d;
             memset(&d, 0, sizeof d);
             int64_t staging;
@@ -41,6 +55,8 @@ int main()
             int32_t one_page = 0;
             d.ctx_len = len.data();
             d.src_pages = d.dst_pages = &one_page;          // only their being non-null matters here
+            if (cmd == "geom_nosrc") d.src_pages = nullptr;
+            if (cmd == "geom_nodst") d.dst_pages = nullptr;
             NtsGeometry g;
             const char *why = "";
             const int rc = nts_host_plan_geometry(&d, &g, &why);
@@ -88,15 +104,19 @@ int main()
             for (auto &x : cb) in >> x;
             printf("staging %" PRId64 "\n", nts_host_batch_staging_bytes(cb.data(), n));
         } else if (cmd == "block") {
-            double thp, thd;
+            const double thp = next_double(in), thd = next_double(in);
             int m, P = 0, D = 0;
-            in >> thp >> thd >> m;
+            in >> m;
             const int rc = nts_balanced_block(thp, thd, m, &P, &D);
             printf("block %d %d %d\n", rc, P, D);
         } else if (cmd == "ge") {
-            double thp, thd, rps, ge = 0;
+            double ge = 0;
             int tpi, tpj, P, D;
-            in >> thp >> tpi >> thd >> tpj >> P >> D >> rps;
+            const double thp = next_double(in);
+            in >> tpi;
+            const double thd = next_double(in);
+            in >> tpj >> P >> D;
+            const double rps = next_double(in);
             const int rc = nts_goodput_efficiency(thp, tpi, thd, tpj, P, D, rps, &ge);
             printf("ge %d %.17g\n", rc, ge);
         } else if (cmd == "plan") {
@@ -104,9 +124,9 @@ int main()
             in >> n_gpus >> n_tiers >> max_inst >> max_out;
             std::vector<nts_tier> tiers(size_t(n_tiers > 0 ? n_tiers : 0));
             for (auto &t : tiers) {
-                in >> t.rps;
-                for (double &v : t.thp) in >> v;
-                for (double &v : t.thd) in >> v;
+                t.rps = next_double(in);
+                for (double &v : t.thp) v = next_double(in);
+                for (double &v : t.thd) v = next_double(in);
             }
             std::vector<nts_alloc> out(size_t(max_out > 0 ? max_out : 0));
             int n = 0, left = 0;

@@ -52,6 +52,9 @@ def test_route_everywhere(run):
     for c, o in zip(bad[:5], out[len(cases):]):
         assert int(o[1]) == -1, c
     assert int(out[-2][1]) == 0 and int(out[-1][1]) == -1
+    # a single head, and a result pointer missing
+    assert [int(x) for x in run(["route 1 1 0 1 0"])[0][1:]] == [0, 0, 0, 1]
+    assert [int(o[1]) for o in run(["route_null %d" % k for k in range(3)])] == [-1, -1, -1]
 
 
 def _geom_line(L, D, e, p, Hs, Hd, so, do, w, S_src, S_dst, sst, dst, staging, lens):
@@ -115,7 +118,15 @@ def test_plan_geometry_rejections(run):
     bad = [dict(L=0), dict(L=97), dict(D=0), dict(D=(1 << 20) + 1), dict(e=3), dict(p=0), dict(Hs=0), dict(Hd=70000),
            dict(w=0), dict(w=5), dict(so=1), dict(do=-1), dict(so=2 ** 31 - 1), dict(S_src=0), dict(S_dst=2 ** 31),
            dict(p=2, S_src=63), dict(sst=500), dict(dst=(1 << 30) + 4), dict(D=1, e=1, w=3), dict(lens=[3, -1]),
-           dict(lens=[2 ** 31 - 1, 1])]
+           dict(lens=[2 ** 31 - 1, 1]),
+           # each side by itself: a bad value on one side with a good one on the other
+           dict(so=-1), dict(do=1), dict(Hs=8, so=5), dict(Hd=8, do=5), dict(Hs=70000), dict(Hd=0),
+           dict(S_dst=0), dict(S_src=2 ** 31), dict(p=2, S_dst=63), dict(dst=500), dict(sst=(1 << 30) + 4)]
+    # ... and the last value each of those checks lets through
+    good = [dict(L=1), dict(L=96), dict(D=1, e=4), dict(D=1 << 20, sst=1 << 30, dst=1 << 30, Hs=64, Hd=64),
+            dict(Hs=8, so=4), dict(Hd=8, do=4), dict(Hs=65536, Hd=65536, D=2), dict(S_src=1, S_dst=1),
+            dict(S_src=2 ** 31 - 1, S_dst=2 ** 31 - 1), dict(sst=1 << 30), dict(dst=1 << 30), dict(lens=[2 ** 31 - 1]),
+            dict(lens=[]), dict(lens=[0, 0])]
     lines = []
     for o in bad:
         c = dict(ok, **o)
@@ -126,6 +137,15 @@ def test_plan_geometry_rejections(run):
     for o, b in zip(out[:-1], bad):
         assert int(o[1]) == -1, (b, o)
     assert int(out[-1][1]) == 0
+    keys = ("L", "D", "e", "p", "Hs", "Hd", "so", "do", "w", "S_src", "S_dst", "sst", "dst", "staging", "lens")
+    for o, g in zip(run([_geom_line(*[dict(ok, **g)[k] for k in keys]) for g in good]), good):
+        assert int(o[1]) == 0, (g, o)
+    # a page table may be missing only when there is no token to look up
+    line = _geom_line(*[ok[k] for k in keys])
+    empty = _geom_line(*[dict(ok, lens=[0, 0])[k] for k in keys])
+    out = run([line.replace("geom", v, 1) for v in ("geom_nosrc", "geom_nodst")] +
+              [empty.replace("geom", v, 1) for v in ("geom_nosrc", "geom_nodst")])
+    assert [int(o[1]) for o in out] == [-1, -1, 0, 0]
 
 
 def test_alias_sweep_against_brute_force(run):
@@ -180,6 +200,22 @@ def test_planner_matches_the_oracle(run):
                 "%r %s %s" % (float(t[0]), " ".join(repr(float(x)) for x in t[1]), " ".join(repr(float(x)) for x in t[2]))
                 for t in tiers)))
             want.append(op.plan(G, [op.Tier(*t) for t in tiers]))
+    from planner_cases import INSTANCES, INVALID_TIERS
+    fmt = lambda tiers: " ".join(
+        "%r %s %s" % (float(t[0]), " ".join(repr(float(x)) for x in t[1]), " ".join(repr(float(x)) for x in t[2])) for t in tiers)
+    for G, tiers in INSTANCES:
+        lines.append("plan %d %d 8 4096 %s" % (G, len(tiers), fmt(tiers)))
+        want.append(op.plan(G, [op.Tier(*t) for t in tiers]))
+    bad = run(["plan 8 %d 8 64 %s" % (len(t), fmt(t)) for t in INVALID_TIERS] +
+              ["block 0.0 1.0 8", "block 1.0 0.0 8", "block -1.0 1.0 8", "block nan 1.0 8", "block 1.0 1.0 0",
+               "ge 0.0 1 1.0 1 1 1 1.0", "ge 1.0 1 0.0 1 1 1 1.0", "ge 1.0 0 1.0 1 1 1 1.0", "ge 1.0 1 1.0 0 1 1 1.0",
+               "ge 1.0 1 1.0 1 0 1 1.0", "ge 1.0 1 1.0 1 1 0 1.0", "ge 1.0 1 1.0 1 1 1 -1.0", "plan 8 1 0 64 5.0 1 1 1 1 1 1 1 1",
+               "plan -1 1 8 64 5.0 1 1 1 1 1 1 1 1"])
+    assert all(int(o[1]) == -1 for o in bad), bad
+    assert run(["ge 1.0 1 1.0 1 1 1 0.0"])[0][1:] == ["0", "0"]
+    from planner_cases import WEIGHTED
+    exact = run(["plan 26 2 8 %d %s" % (m, fmt(WEIGHTED)) for m in (13, 12)])    # room for exactly the 13 steps, and one short
+    assert exact[0][1:4] == ["0", "13", "0"] and exact[1][1:3] == ["-2", "13"]
     tiers = synthetic_tiers(2024, 4, rps_scale=400.0)
     lines.append("plan 128 4 8 2 %s" % " ".join(
         "%r %s %s" % (float(t[0]), " ".join(repr(float(x)) for x in t[1]), " ".join(repr(float(x)) for x in t[2])) for t in tiers))

@@ -51,6 +51,34 @@ def test_random_instances_match_oracle(b, seed):
         assert [a.served_rps for a in got] == [a.served for a in want]
 
 
+def test_instances_that_tell_the_weighting_apart(b):
+    from planner_cases import INSTANCES, INVALID_TIERS, WEIGHTED, WEIGHTED_ORDER_26
+    got, left = b.nts_plan_cluster(26, WEIGHTED)
+    assert [a.tier for a in got] == WEIGHTED_ORDER_26 and left == 0          # the order worked out by hand
+    assert len(b.nts_plan_cluster(26, WEIGHTED, max_out=13)[0]) == 13        # room for exactly the steps taken
+    with pytest.raises(b.NtsError):
+        b.nts_plan_cluster(26, WEIGHTED, max_out=12)
+    for G, tiers in INSTANCES:
+        got, left = b.nts_plan_cluster(G, tiers)
+        want, wleft = op.plan(G, [op.Tier(*t) for t in tiers])
+        assert left == wleft
+        assert [as_tuple(a) + (a.served_rps,) for a in got] == \
+            [(a.tier, a.tp_prefill, a.tp_decode, a.P, a.D, a.gpus, a.served) for a in want]
+    for tiers in INVALID_TIERS:
+        with pytest.raises(b.NtsError):
+            b.nts_plan_cluster(8, tiers)
+    for args in [(1.0, 0.0), (-1.0, 1.0), (float("nan"), 1.0), (1.0, float("nan"))]:
+        with pytest.raises(b.NtsError):
+            b.nts_balanced_block(*args)
+    with pytest.raises(b.NtsError):
+        b.nts_balanced_block(1.0, 1.0, 0)
+    for args in [(0.0, 1, 1.0, 1, 1, 1, 1.0), (1.0, 1, 0.0, 1, 1, 1, 1.0), (1.0, 1, 1.0, 0, 1, 1, 1.0),
+                 (1.0, 1, 1.0, 1, 0, 1, 1.0), (1.0, 1, 1.0, 1, 1, 0, 1.0), (1.0, 1, 1.0, 1, 1, 1, -1.0)]:
+        with pytest.raises(b.NtsError):
+            b.nts_goodput_efficiency(*args)
+    assert b.nts_goodput_efficiency(1.0, 1, 1.0, 1, 1, 1, 0.0) == 0.0       # a tier that asks for nothing is legal
+
+
 def test_paper_scale_instance_and_errors(b):
     """128 GPUs and four request groups (the size of the paper's planning-time figure)."""
     tiers = synthetic_tiers(2024, 4, rps_scale=400.0)
