@@ -177,9 +177,10 @@ __device__ __forceinline__ void move_vector(const NtsMoveJob &job, const NtsLaye
 
 // Which piece of its job a workgroup takes when the stream side is a staging buffer.
 // Consecutive workgroup ids go to the 8 XCDs in turn; taken as they come, every XCD would touch
-// every eighth KiB of the staging buffers and of the stream.  Inside aligned groups of 8 << kXcdSpanLog2 pieces the low bits are rotated so that
-// the workgroups one XCD receives cover 2^kXcdSpanLog2 consecutive pieces (1 MiB): a bijection of
-// each group, the ragged end of a job keeps the identity.  Measured on the stage kernel (ms per
+// every eighth KiB of the staging buffers and of the stream.  Inside aligned groups of
+// 8 << kXcdSpanLog2 pieces the low bits are rotated so that the workgroups one XCD receives
+// cover 2^kXcdSpanLog2 consecutive pieces (1 MiB): a bijection of each group, the ragged end of
+// a job keeps the identity.  Measured on the stage kernel (ms per
 // migration, 5 GiB / 88 GiB): none 3.19 / 55.5, 16 KiB per XCD 3.16 / 54.8, 128 KiB 3.15 / 54.6,
 // 1 MiB 3.15 / 54.3, 8 MiB 3.18 / 55.0 (runs of 256; with runs of 64: 3.09-3.13 / 53.7-54.0);
 // spans of 2-8 KiB lose 3 %.  The chunk calls gain 2 % (6.26 -> 6.40 TB/s through two 64 MiB
@@ -207,7 +208,7 @@ __global__ __launch_bounds__(kThreads) void nts_move_kernel(NtsMoveJob job, NtsL
 // (job b), while both jobs have a full run left; what remains of a, then of b, follows.
 // Runs of 64 to 256 single-wavefront workgroups measured 10 % faster than alternating
 // workgroup by workgroup or in runs of 16 (fewer read/write turnarounds in HBM) and 7 % faster
-// than runs of 8192; with the per-XCD mapping below 64 is level with or just ahead of 256.
+// than runs of 8192; with the per-XCD mapping above, 64 is level with or just ahead of 256.
 constexpr uint32_t kStageRunLog2 = 6, kStageRun = 1u << kStageRunLog2;
 
 template <int BYTES>
