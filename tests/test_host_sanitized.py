@@ -213,6 +213,14 @@ def test_planner_matches_the_oracle(run):
                "plan -1 1 8 64 5.0 1 1 1 1 1 1 1 1"])
     assert all(int(o[1]) == -1 for o in bad), bad
     assert run(["ge 1.0 1 1.0 1 1 1 0.0"])[0][1:] == ["0", "0"]
+    # legal corner cases: no tier at all, a tier that asks for nothing, one instance per side, no room asked for
+    # in the output array when no step is taken
+    one = "5.0 1 1 1 1 1 1 1 1"
+    corner = run(["plan 8 0 8 4", "plan 8 1 8 4 0.0 1 1 1 1 1 1 1 1", "plan 8 1 1 64 " + one, "plan 0 1 8 0 " + one,
+                  "plan 1 1 8 0 " + one])
+    assert corner[0][1:4] == ["0", "0", "8"] and corner[1][1:4] == ["0", "0", "8"]
+    assert corner[2][1:3] == ["0", "4"] and corner[2][3] == "0"           # four blocks of 1 + 1 GPUs serve 4 of the 5 req/s
+    assert corner[3][1:4] == ["0", "0", "0"] and corner[4][1:4] == ["0", "0", "1"]
     from planner_cases import WEIGHTED
     exact = run(["plan 26 2 8 %d %s" % (m, fmt(WEIGHTED)) for m in (13, 12)])    # room for exactly the 13 steps, and one short
     assert exact[0][1:4] == ["0", "13", "0"] and exact[1][1:3] == ["-2", "13"]
