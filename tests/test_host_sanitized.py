@@ -146,6 +146,8 @@ def test_plan_geometry_rejections(run):
     out = run([line.replace("geom", v, 1) for v in ("geom_nosrc", "geom_nodst")] +
               [empty.replace("geom", v, 1) for v in ("geom_nosrc", "geom_nodst")])
     assert [int(o[1]) for o in out] == [-1, -1, 0, 0]
+    single = _geom_line(*[dict(ok, lens=[0, 1])[k] for k in keys])              # one token is enough to need them
+    assert [int(o[1]) for o in run([single.replace("geom", v, 1) for v in ("geom_nosrc", "geom_nodst", "geom")])] == [-1, -1, 0]
 
 
 def test_alias_sweep_against_brute_force(run):
@@ -166,6 +168,12 @@ def test_alias_sweep_against_brute_force(run):
     top = 2 ** 64 - 1
     cases.append(([(top - 100, top, 0), (top - 300, top - 100, 1)], 4096, 64))
     lines.append("alias 2 %d %d 0 %d %d 1 4096 64" % (top - 100, top, top - 300, top - 100))
+    # ranges that only touch: a pool ending where the staging area or a pool of the other side begins
+    for rs, stg, sb in [([(1000, 2000, 0)], 2000, 100), ([(1000, 2000, 1)], 900, 100), ([(1000, 2000, 0)], 1999, 2),
+                        ([(1000, 2000, 0)], 999, 2), ([(1000, 2000, 0), (2000, 3000, 1)], 5000, 16),
+                        ([(2000, 3000, 0), (1000, 2000, 1)], 5000, 16), ([(1000, 2001, 0), (2000, 3000, 1)], 5000, 16)]:
+        cases.append((rs, stg, sb))
+        lines.append("alias %d %s %d %d" % (len(rs), " ".join("%d %d %d" % r for r in rs), stg, sb))
     out = run(lines)
     seen = set()
     for (rs, stg, sb), o in zip(cases, out):
