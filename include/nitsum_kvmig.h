@@ -351,7 +351,7 @@ int nts_shard_linear_workspace(const nts_linear_desc *d, size_t *bytes);
  * that must reach every kernel variant.  Errors: NTS_EINVAL as above.
  */
 typedef struct nts_linear_launch {
-    int32_t tiled;       /* 1: matrix-core tiles of tile_rows x tile_cols (256 x 256, 256 x 128 or 128 x 128);
+    int32_t tiled;       /* 1: matrix-core tiles of tile_rows x tile_cols (256 or 128 rows by 256, 192 or 128 columns, not 128 x 256);
                             0: weight-streaming kernel, or, with tile_rows == 16, the decode kernel */
     int32_t tile_rows;   /* batch rows per workgroup */
     int32_t tile_cols;   /* output columns (weight rows) per workgroup */

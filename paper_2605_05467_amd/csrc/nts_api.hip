@@ -838,8 +838,8 @@ static bool launch_to_geom(const nts_linear_launch *how, LinearGeom *g)
     c.splits = how->k_splits;
     if (c.splits < 1 || c.splits > 32) return false;
     if (how->tiled) {
-        const bool known = (how->tile_rows == 256 && (how->tile_cols == 256 || how->tile_cols == 128)) ||
-                           (how->tile_rows == 128 && how->tile_cols == 128);
+        const bool known = (how->tile_rows == 256 && (how->tile_cols == 256 || how->tile_cols == 192 || how->tile_cols == 128)) ||
+                           (how->tile_rows == 128 && (how->tile_cols == 192 || how->tile_cols == 128));
         if (!known || c.splits != 1) return false;
         if (g->M < how->tile_rows) return false;         // as in the default choice: a whole batch tile at least
         g->tiled = how->tile_cols;

@@ -36,7 +36,7 @@ struct nts_ctx {
     std::string err;
     // configurations nts_shard_linear_tune found fastest, by (M, shard rows, reduction length, format)
     struct TunedLinear {
-        int tiled;      // tile width of the tiled kernel (256 or 128), 0: streaming / decode kernel
+        int tiled;      // tile width of the tiled kernel (256, 192 or 128), 0: streaming / decode kernel
         int tiled_rows; // its tile height (256 or 128)
         int mt, cw, rt, nsets, splits, ks;
     };
@@ -153,7 +153,7 @@ NtsStreamCfg nts_linear_stream_config(int M, int Nn, int K);
 int nts_linear_use_tiled(int M, int Nn, int K, int *rows);   // tile width (and height) of the tiled kernel, 0: not tiled
 // one way of running a problem: the tiled kernel, or the streaming / decode kernel with `cfg`
 struct NtsLinearCand {
-    int tiled = 0;          // tile width of the tiled kernel (256 or 128), 0: streaming / decode kernel
+    int tiled = 0;          // tile width of the tiled kernel (256, 192 or 128), 0: streaming / decode kernel
     int tiled_rows = 256;   // its tile height (256 or 128)
     NtsStreamCfg cfg;
     double est_us = 0.;

@@ -425,7 +425,7 @@ __global__ __launch_bounds__(64 * KS) void nts_linear_decode_kernel(
 // ---------------------------------------------------------------------------
 // Large batches (prefill): bound by the matrix cores.  A 256-thread workgroup computes a
 // 64*MA x 64*NB tile of Y (MA = NB = 4: 256 x 256; MA = 4, NB = 2: 256 x 128; MA = NB = 2:
-// 128 x 128); each of its four wavefronts owns a 32*MA x 32*NB part as MA x NB tiles of
+// 128 x 128; NB = 3: 256 x 192 and 128 x 192); each of its four wavefronts owns a 32*MA x 32*NB part as MA x NB tiles of
 // v_mfma_f32_32x32x16 (16*MA*NB fp32 accumulators per lane, one wavefront per SIMD).  X and
 // weight rows are both contiguous along k, so both operands are staged the same way: 64-wide k
 // slabs go global -> registers -> LDS (row pitch 144 B, which spreads the 32 rows a
@@ -436,7 +436,10 @@ __global__ __launch_bounds__(64 * KS) void nts_linear_decode_kernel(
 // whose 256 x 256 tiling leaves the last round of workgroups half empty or fills too few
 // compute units (measured: 6144 outputs at M = 4096, 384 tiles of 256 x 256 in 1.5 rounds,
 // 210 us; 768 of 256 x 128 in 3 rounds, 178 us; 4096 outputs at M = 1024, 64 tiles of
-// 256 x 256, streaming kernel 56 us; 256 tiles of 128 x 128, 45 us).
+// 256 x 256, streaming kernel 56 us; 256 tiles of 128 x 128, 45 us).  The 192-wide tiles are
+// for outputs they divide into a whole number of rounds where the others do not (6144 outputs:
+// M = 2048, 192 tiles of 256 x 256, 106 us; 256 of 256 x 192, 87.5 us; M = 1024, 192 tiles of
+// 256 x 128, 61.7 us; 256 of 128 x 192, 57 us); per compute unit they run at the wide tile's rate.
 constexpr int kTileK = 64;                              // slab depth; a tile is 64 * MA rows by 64 * NB columns
 constexpr int kSupM = 4, kSupN = 8;                     // tiles per XCD-resident block
 constexpr int kPitch = kTileK * 2 + 16;                 // bytes per LDS row
@@ -621,7 +624,9 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
     nts_lds_barrier();                                  // every wavefront is done with the tile buffers
     {
         constexpr int kOutPitch = 64 * NB + 8;          // bytes per strip row in LDS
-        constexpr int kLanesRow = 4 * NB, kRowsIns = 64 / kLanesRow;
+        constexpr int kLanesRow = 4 * NB, kRowsIns = 64 / kLanesRow;   // NB = 3: five rows a pass, four lanes idle
+        constexpr int kPasses = (32 + kRowsIns - 1) / kRowsIns;
+        constexpr bool kRagged = 64 % kLanesRow != 0 || 32 % kRowsIns != 0;
         unsigned char *strip = lds + wv * 32 * kOutPitch;
         const int orow = lane / kLanesRow, ocol = (lane % kLanesRow) * 8;
 #pragma unroll
@@ -636,8 +641,9 @@ __global__ __launch_bounds__(256) void nts_linear_tiled_kernel(
                 }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the strip is complete (LDS works in order)
 #pragma unroll
-            for (int j = 0; j < 32 / kRowsIns; ++j) {
+            for (int j = 0; j < kPasses; ++j) {
                 const int r = j * kRowsIns + orow;
+                if (kRagged && (orow >= kRowsIns || r >= 32)) continue;
                 const u32x2 lo = *reinterpret_cast<const u32x2 *>(strip + r * kOutPitch + ocol * 2);
                 const u32x2 hi = *reinterpret_cast<const u32x2 *>(strip + r * kOutPitch + ocol * 2 + 8);
                 const u32x4 val = {lo[0], lo[1], hi[0], hi[1]};
@@ -858,13 +864,16 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
 }
 
 // Estimated time of the tiled kernel with tiles of rows x cols: rounds of 256 workgroups, each
-// round a fixed cost plus its slabs (measured per slab: 1.57 us for 256 x 256, 0.91 us for
-// 256 x 128, 0.6 us for 128 x 128).
+// round a fixed cost plus its slabs (measured per slab: 1.57 us for 256 x 256, 1.22 us for
+// 256 x 192, 0.91 us for 256 x 128, 0.76 us for 128 x 192, 0.6 us for 128 x 128).
 static double tiled_estimate_us(int M, int Nn, int K, int rows, int cols)
 {
     const int64_t tiles = int64_t((M + rows - 1) / rows) * ((Nn + cols - 1) / cols);
     const int S = K / kTileK;
-    const double per_round = cols == 256 ? 11. + 1.57 * S : rows == 256 ? 8. + 0.91 * S : 4. + 0.6 * S;
+    const double per_round = cols == 256   ? 11. + 1.57 * S
+                             : cols == 192 ? (rows == 256 ? 6. + 1.22 * S : 3.6 + 0.76 * S)
+                             : rows == 256 ? 8. + 0.91 * S
+                                           : 4. + 0.6 * S;
     return 2.5 + double((tiles + 255) / 256) * per_round;
 }
 
@@ -876,7 +885,10 @@ static double tiled_estimate_us(int M, int Nn, int K, int rows, int cols)
 // ragged last round.  128 x 128 is for outputs too small for either (measured on every such
 // prefill shape of the 8B model: level with or up to 30 % ahead of the streaming kernel, and
 // behind the larger tiles wherever those qualify).
-int nts_linear_use_tiled(int M, int Nn, int K, int *rows)
+// The two 192-wide tiles replace that choice where their estimate is 5 % or more below its
+// estimate (outputs they cut into a whole number of rounds: measured 5-17 % faster on the six such
+// prefill shapes of the 8B model, never chosen on the other 43).
+static int tiled_base_choice(int M, int Nn, int K, int *rows)
 {
     *rows = 256;
     if (M < 256) return 0;
@@ -895,10 +907,30 @@ int nts_linear_use_tiled(int M, int Nn, int K, int *rows)
     return 0;
 }
 
+int nts_linear_use_tiled(int M, int Nn, int K, int *rows)
+{
+    const int base = tiled_base_choice(M, Nn, K, rows);
+    if (!base) return 0;
+    double best = 0.95 * tiled_estimate_us(M, Nn, K, *rows, base);
+    int cols = base;
+    const int64_t tn = (Nn + 191) / 192;
+    for (int r = 256; r >= 128; r -= 128) {
+        if (r == 256 ? M <= 256 : M < 512) continue;     // the same batch sizes as the other tiles of that height
+        if (int64_t((M + r - 1) / r) * tn < 160) continue;
+        const double t = tiled_estimate_us(M, Nn, K, r, 192);
+        if (t < best) {
+            best = t;
+            cols = 192;
+            *rows = r;
+        }
+    }
+    return cols;
+}
+
 // Every configuration that may be fastest for a problem, for nts_shard_linear_tune to time: the
 // streaming kernel's variants with each K split that is valid for them, the decode kernel's
 // (row blocks, wavefronts per K range, K split) combinations for M <= 16, and the tiled kernel
-// in its three tile shapes for M >= 128.  Each gets the same estimate nts_linear_stream_config uses
+// in its five tile shapes for M >= 128.  Each gets the same estimate nts_linear_stream_config uses
 // (the tiled kernel: tiled_estimate_us); the list is cut to those within `slack` of
 // the smallest estimate, sorted by estimate, at most `max_out`.  The configuration
 // nts_shard_linear uses by default is always first.
@@ -978,7 +1010,7 @@ int nts_linear_candidates(int M, int Nn, int K, double slack, NtsLinearCand *out
                     all.push_back(c);
                 }
     }
-    static const int kTiles[3][2] = {{256, 256}, {256, 128}, {128, 128}};
+    static const int kTiles[5][2] = {{256, 256}, {256, 192}, {256, 128}, {128, 192}, {128, 128}};
     for (const auto &t : kTiles) {
         if (M < t[0]) continue;
         NtsLinearCand c;
@@ -1034,6 +1066,10 @@ hipError_t nts_launch_linear_tiled(const uint16_t *X, int64_t ldx, const uint16_
 #define NTS_TILED(NB, MA)                                                                              \
     return f16 ? launch_tiled_one<F16, NB, MA>(X, ldx, A, lda, Y, ldy, M, Nn, K, st)                   \
                : launch_tiled_one<Bf16, NB, MA>(X, ldx, A, lda, Y, ldy, M, Nn, K, st);
+    if (tile_cols == 192) {
+        if (tile_rows == 128) NTS_TILED(3, 2)
+        NTS_TILED(3, 4)
+    }
     if (tile_rows == 128) NTS_TILED(2, 2)
     if (tile_cols == 128) NTS_TILED(2, 4)
     NTS_TILED(4, 4)
