@@ -900,7 +900,10 @@ static int tiled_base_choice(int M, int Nn, int K, int *rows)
         return tiled_estimate_us(M, Nn, K, 256, 128) < 0.97 * tiled_estimate_us(M, Nn, K, 256, 256) ? 128 : 256;
     if (ok256) return 256;
     if (ok128c) return 128;
-    if (M >= 512 && t128s >= 160) {      // with fewer than four row tiles the streaming kernel stays ahead
+    // with fewer than four row tiles the streaming kernel stays ahead, and so it does with 160 to 191
+    // tiles on long reductions, which it splits over the idle compute units (160 tiles of 5120 columns
+    // at M = 512: tiled 11-17 % ahead for K = 640 ... 3456, 4 % behind at K = 5120, 26 % at K = 13824)
+    if (M >= 512 && (t128s >= 192 || (t128s >= 160 && K <= 4096))) {
         *rows = 128;
         return 128;
     }

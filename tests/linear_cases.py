@@ -32,7 +32,7 @@ CASES = [
     (640, 8200, 320, 128, 192, False, 1, True),
     (130, 4104, 6144, 192, 128, True, 1, False),
     (200, 17008, 256, 256, 128, False, 1, False),
-    (600, 4104, 320, 128, 128, False, 1, True),
+    (600, 5000, 320, 128, 128, False, 1, True),
     (777, 7000, 256, 256, 128, False, 1, True),
     (256, 28680, 320, 256, 128, False, 1, True),
     (200, 4104, 8320, 256, 128, True, 1, False),
