@@ -144,8 +144,9 @@ def test_every_kernel_variant(env, case, split):
 @pytest.mark.parametrize("M", [520, 777])
 @pytest.mark.parametrize("split", ["out", "in"])
 def test_tiled_kernel_ragged_edges(env, M, split):
-    """Outputs with at least 160 tiles of 256 x 256 go to the tiled matrix-core
-    kernel: ragged edges in both output dimensions, both element formats."""
+    """Outputs of this size go to the tiled matrix-core kernel (in whichever tile
+    shape the library picks for them): ragged edges in both output dimensions,
+    both element formats."""
     tp = 2
     n_out, n_in = (2 * 19000, 256) if split == "out" else (19000, 2 * 256)
     run_case(env, M, n_out, n_in, tp, 1, split, seed=M + 7)
