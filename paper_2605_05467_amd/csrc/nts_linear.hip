@@ -866,14 +866,14 @@ hipError_t nts_launch_linear_stream(const uint16_t *X, int64_t ldx, const uint16
 }
 
 // Estimated time of the tiled kernel with tiles of rows x cols: rounds of 256 workgroups, each
-// round a fixed cost plus its slabs (measured per slab: 1.57 us for 256 x 256, 1.22 us for
-// 256 x 192, 0.91 us for 256 x 128, 0.76 us for 128 x 192, 0.6 us for 128 x 128).
+// round a fixed cost plus its slabs (measured per slab: 1.57 us for 256 x 256, 1.19 us for
+// 256 x 192 (fitted over K = 256 ... 4096), 0.91 us for 256 x 128, 0.76 us for 128 x 192, 0.6 us for 128 x 128).
 static double tiled_estimate_us(int M, int Nn, int K, int rows, int cols)
 {
     const int64_t tiles = int64_t((M + rows - 1) / rows) * ((Nn + cols - 1) / cols);
     const int S = K / kTileK;
     const double per_round = cols == 256   ? 11. + 1.57 * S
-                             : cols == 192 ? (rows == 256 ? 6. + 1.22 * S : 3.6 + 0.76 * S)
+                             : cols == 192 ? (rows == 256 ? 7.8 + 1.19 * S : 3.6 + 0.76 * S)
                              : rows == 256 ? 8. + 0.91 * S
                                            : 4. + 0.6 * S;
     return 2.5 + double((tiles + 255) / 256) * per_round;
