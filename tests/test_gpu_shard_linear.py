@@ -350,6 +350,40 @@ def test_tuned_configuration_keeps_parity(env, M, n_out, n_in, tp, split):
         b.nts_free(ctx)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_all_five_tile_shapes_give_the_same_bits(env, dtype):
+    """The tiled kernel's five tile shapes, each named explicitly through
+    nts_shard_linear_with, on one problem that is ragged for all of them (700 rows,
+    1000 columns of a TP-2 shard, row padding): integer inputs, so every shape must
+    produce the oracle's once-rounded result bit for bit, and nothing past the row."""
+    torch, b, ctx = env
+    M, n_out, n_in, tp = 700, 2000, 320, 2
+    nn, pad = n_out // tp, 8
+    kw = dict(M=M, n_out=n_out, n_in=n_in, tp=tp, rank=1, split=b.NTS_SPLIT_OUT, ldy=nn + pad,
+              dtype=b.NTS_BF16 if dtype == "bf16" else b.NTS_F16)
+    Xh, Wh = linear_inputs_int(4242, M, n_out, n_in, x_cols=n_in, dtype=dtype)
+    decode = osl.bf16_to_f64 if dtype == "bf16" else osl.f16_to_f64
+    want, _ = osl.shard_linear(decode(Xh), decode(Wh), tp, 1, "out")
+    bits = osl.round_to_bits(want, dtype)
+    Xd = torch.from_numpy(Xh.view(np.int16)).cuda()
+    Wd = torch.from_numpy(Wh.view(np.int16)).cuda()
+    st = torch.cuda.current_stream().cuda_stream
+    proto = b.nts_shard_linear_launch(**kw)
+    for rows, cols in [(256, 256), (256, 192), (256, 128), (128, 192), (128, 128)]:
+        how = type(proto)(tiled=1, tile_rows=rows, tile_cols=cols, k_splits=1, slabs_ahead=proto.slabs_ahead, k_waves=1)
+        Yd = torch.full((M, nn + pad), 12345, dtype=torch.int16, device="cuda")
+        b.nts_shard_linear_with(ctx, how, Xd.data_ptr(), Wd.data_ptr(), Yd.data_ptr(), hip_stream=st, **kw)
+        torch.cuda.synchronize()
+        got = Yd.cpu().numpy().view(np.uint16)
+        assert np.array_equal(got[:, :nn], bits), (rows, cols)
+        assert np.all(got[:, nn:] == 12345), (rows, cols)
+    # a tile taller than the batch is refused, as in the default choice
+    small = dict(kw, M=200)
+    how = type(proto)(tiled=1, tile_rows=256, tile_cols=192, k_splits=1, slabs_ahead=proto.slabs_ahead, k_waves=1)
+    with pytest.raises(b.NtsError):
+        b.nts_shard_linear_with(ctx, how, Xd.data_ptr(), Wd.data_ptr(), Yd.data_ptr(), hip_stream=st, **small)
+
+
 @pytest.mark.parametrize("M,n_out,n_in,tp,split,dtype", [
     (1, 4096, 14336, 1, "in", "bf16"), (16, 6144, 4096, 1, "out", "bf16"), (9, 1000, 12352, 1, "out", "f16"),
     (64, 4096, 4096, 4, "in", "bf16"), (130, 4104, 6144, 1, "out", "f16"), (300, 2048, 2048, 1, "out", "bf16"),
